@@ -1,0 +1,239 @@
+"""Pins for the CPU oracle: everything here runs without a GPU.
+
+Each test holds the oracle (fp64 Kahan sum of fp16 inputs, the definition
+R(X) = sum x_i of the paper's Section 4) to something other than itself:
+numpy's independent half decoder, closed forms, Python's exactly rounded
+``math.fsum``, exact 128-bit integer arithmetic, and the ones-matrix MMA
+identities of Sections 4.1 / 4.3.
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2001_05585_amd import workloads as W
+
+
+def ulp64(v: float) -> float:
+    return math.ulp(v) if v != 0.0 else 2.0 ** -1074
+
+
+# ---------------------------------------------------------------- decoder ---
+
+def test_decoder_matches_numpy_for_every_code(oracle_lib):
+    codes = np.arange(65536, dtype=np.uint16)
+    ref = codes.view(np.float16).astype(np.float64)
+    for c in range(65536):
+        got = oracle_lib.fp16_to_f64(c)
+        r = ref[c]
+        if math.isnan(r):
+            assert math.isnan(got), hex(c)
+        else:
+            assert got == r and math.copysign(1.0, got) == math.copysign(1.0, r), hex(c)
+
+
+def test_decoder_landmarks(oracle_lib):
+    f = oracle_lib.fp16_to_f64
+    assert f(0x3C00) == 1.0
+    assert f(0xBC00) == -1.0
+    assert f(0x0001) == 2.0 ** -24          # smallest subnormal
+    assert f(0x03FF) == 1023 * 2.0 ** -24   # largest subnormal
+    assert f(0x0400) == 2.0 ** -14          # smallest normal
+    assert f(0x7BFF) == 65504.0             # largest finite
+    assert f(0x3BFF) == 1.0 - 2.0 ** -11
+    assert f(0x7C00) == math.inf and f(0xFC00) == -math.inf
+    assert math.isnan(f(0x7E00))
+
+
+# ----------------------------------------------------------- closed forms ---
+
+@pytest.mark.parametrize("n", [0, 1, 7, 8, 511, 512, 513, 2048, 65536 + 7, 1 << 20, 1 << 24])
+def test_all_ones_gives_n(oracle_lib, n):
+    s, a = oracle_lib.sum_f16(W.ones(n))
+    assert s == float(n) and a == float(n)
+
+
+@pytest.mark.parametrize("c", [2.0, -3.0, 0.5, 0.25, -0.125, 1024.0, 2.0 ** -20])
+@pytest.mark.parametrize("n", [1, 1000, 4097, 1 << 18])
+def test_constant_gives_n_times_c(oracle_lib, n, c):
+    s, a = oracle_lib.sum_f16(W.constant(n, c))
+    assert s == n * c          # exact in binary64: n * c has < 53 significant bits
+    assert a == n * abs(c)
+
+
+@pytest.mark.parametrize("n,step", [(2, 1.0), (100, 1.0), (2048, 1.0), (2048, 0.5), (1500, 2.0 ** -10)])
+def test_plain_ramp(oracle_lib, n, step):
+    # x_i = i * step for i < 2048 is fp16-exact; sum = n (n - 1) / 2 * step
+    s, _ = oracle_lib.sum_f16(W.periodic_ramp(n, 2048, step))
+    assert s == n * (n - 1) // 2 * step
+
+
+@pytest.mark.parametrize("n,period,step", [(1 << 20, 4, 1.0), (16384, 2048, 1.0), (100003, 37, 0.25),
+                                           (1 << 22, 2048, 2.0 ** -5), (5, 7, 1.0)])
+def test_periodic_ramp(oracle_lib, n, period, step):
+    q, r = divmod(n, period)
+    expect = (q * (period * (period - 1) // 2) + r * (r - 1) // 2) * step
+    s, a = oracle_lib.sum_f16(W.periodic_ramp(n, period, step))
+    assert s == expect and a == expect
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 3, 1000, 1001, (1 << 20) + 1])
+@pytest.mark.parametrize("c", [1.0, 65504.0, 2.0 ** -24])
+def test_alternating_cancels(oracle_lib, n, c):
+    s, a = oracle_lib.sum_f16(W.alternating(n, c))
+    assert s == (c if n % 2 else 0.0)
+    assert a == n * c
+
+
+def test_blocks_of_plus_then_minus(oracle_lib):
+    x = np.concatenate([W.constant(70000, 3.0), W.constant(70000, -3.0), W.constant(5, 0.5)])
+    s, a = oracle_lib.sum_f16(x)
+    assert s == 2.5 and a == 420002.5
+
+
+def test_one_hot_and_prefix(oracle_lib):
+    n = 3000
+    for p in (0, 1, 7, 8, 511, 512, 2047, 2048, n - 1):
+        assert oracle_lib.sum_f16(W.one_hot(n, p))[0] == 1.0
+        assert oracle_lib.sum_f16(W.one_hot(n, p, -0.5))[0] == -0.5
+    for k in (0, 1, 511, 512, 513, n):
+        assert oracle_lib.sum_f16(W.prefix_indicator(n, k))[0] == float(k)
+
+
+def test_subnormals_are_honoured(oracle_lib):
+    x = np.full(1 << 24, 1, dtype=np.uint16)      # 2^24 copies of 2^-24
+    s, a = oracle_lib.sum_f16(x)
+    assert s == 1.0 and a == 1.0
+
+
+def test_special_values_propagate(oracle_lib):
+    base = W.ones(100).view(np.uint16).copy()
+    x = base.copy(); x[17] = 0x7C00
+    assert oracle_lib.sum_f16(x)[0] == math.inf
+    x[50] = 0xFC00
+    assert math.isnan(oracle_lib.sum_f16(x)[0])
+    x = base.copy(); x[3] = 0x7E01
+    assert math.isnan(oracle_lib.sum_f16(x)[0])
+
+
+# ------------------------------------------------ brute force on tiny n ---
+
+def test_brute_force_every_small_n(oracle_lib):
+    # integer inputs: Python int arithmetic is the exact answer for every prefix length
+    full = W.small_integers(2101, seed=11)
+    ints = [int(v) for v in full.astype(np.float64)]
+    acc = 0
+    absacc = 0
+    for n in range(0, 2101):
+        s, a = oracle_lib.sum_f16(full[:n])
+        assert s == float(acc) and a == float(absacc), n
+        e, ea, bad = oracle_lib.exact_sum_f16(full[:n])
+        assert e == acc and ea == absacc and bad == 0
+        if n < 2100:
+            acc += ints[n]
+            absacc += abs(ints[n])
+
+
+@pytest.mark.parametrize("kind", ["uniform01", "uniform_pm1", "normal"])
+def test_brute_force_random_values_vs_fsum(oracle_lib, kind):
+    # numpy's decoder + Python's exactly rounded fsum: an independent exact answer
+    for n in (1, 2, 3, 17, 255, 1000, 2100, 50000):
+        x = W.generate(kind, n, seed=5 + n)
+        vals = x.astype(np.float64).tolist()
+        want = math.fsum(vals)
+        want_abs = math.fsum(abs(v) for v in vals)
+        s, a = oracle_lib.sum_f16(x)
+        assert abs(s - want) <= 2 * ulp64(want), (kind, n)
+        assert abs(a - want_abs) <= 2 * ulp64(want_abs), (kind, n)
+        # and the uncompensated serial sum (the paper's CPU comparison) is close too
+        assert abs(oracle_lib.sum_f16_naive(x) - want) <= 1e-12 * want_abs + 1e-300
+
+
+# ------------------------------------------- exact 128-bit integer pin ---
+
+@pytest.mark.parametrize("kind,seed_cfg,n", [("uniform01", 1, 1 << 20), ("uniform01", 2, 1 << 22),
+                                             ("normal", 3, 1 << 22), ("uniform_pm1", 4, 4_000_007),
+                                             ("uniform01", 5, (1 << 21) + 7)])
+def test_kahan_equals_exact_integer_sum(oracle_lib, kind, seed_cfg, n):
+    x = W.generate(kind, n, W.config_seed(seed_cfg))
+    s, a = oracle_lib.sum_f16(x)
+    e, ea, bad = oracle_lib.exact_sum_f16(x)
+    assert bad == 0
+    want, want_abs = float(e), float(ea)      # Fraction -> float is correctly rounded
+    assert abs(s - want) <= 2 * ulp64(want)
+    assert abs(a - want_abs) <= 2 * ulp64(want_abs)
+    sb, ab, used = oracle_lib.sum_f16_blocked(x, 4)
+    assert 1 <= used <= 4
+    assert abs(sb - want) <= 2 * ulp64(want)
+    assert abs(ab - want_abs) <= 2 * ulp64(want_abs)
+
+
+def test_exact_checker_against_python_ints(oracle_lib):
+    # every finite code once, positive and negative: the exact sum is 0, sum|x| known in closed form
+    codes = np.array([c for c in range(65536) if (c >> 10) & 31 != 31], dtype=np.uint16)
+    e, ea, bad = oracle_lib.exact_sum_f16(codes)
+    assert e == 0 and bad == 0
+    total = Fraction(0)
+    for c in range(0x7C00):
+        total += Fraction(float(np.uint16(c).view(np.float16)))
+    assert ea == 2 * total
+    assert oracle_lib.exact_sum_f16(np.arange(65536, dtype=np.uint16))[2] == 2048
+    s, a = oracle_lib.sum_f16(codes)
+    assert s == 0.0 or abs(s) <= 2 * ulp64(float(ea))   # ordered +codes then -codes: not exact cancellation stepwise
+    assert abs(a - float(ea)) <= 2 * ulp64(float(ea))
+
+
+def test_kahan_beats_naive_where_it_matters(oracle_lib):
+    # 2^24 values of 0.1 (fp16: 0.0999755859375) after a 65504 head: the
+    # exact answer is known in closed form; the compensated sum must hit it.
+    n = 1 << 22
+    x = np.concatenate([W.constant(1, 65504.0), np.full(n, np.float16(0.1))])
+    tenth = Fraction(float(np.float16(0.1)))
+    want = float(Fraction(65504) + n * tenth)
+    assert oracle_lib.sum_f16(x)[0] == want
+
+
+# --------------------------------------- ones-matrix MMA identities ---
+
+def test_mma_two_step_every_entry_is_the_tile_total():
+    from oracle import mma_model as M
+    rng = np.random.default_rng(3)
+    for m in (2, 4, 16):
+        X = rng.integers(-9, 10, size=(m, m)).astype(np.float64)
+        D = M.mma(M.ones(m), X, M.zeros(m))
+        # first MMA: column sums of X, replicated down every row
+        assert np.array_equal(D, np.tile(X.sum(axis=0), (m, 1)))
+        Dp = M.two_step(X)
+        assert np.all(Dp == X.sum())
+
+
+def test_mma_chain_equals_sum_of_tile_totals():
+    from oracle import mma_model as M
+    rng = np.random.default_rng(4)
+    for m, R in ((4, 1), (4, 5), (16, 4), (16, 8)):
+        tiles = [rng.integers(-9, 10, size=(m, m)).astype(np.float64) for _ in range(R)]
+        C = M.chain(tiles)
+        assert np.all(C == sum(t.sum() for t in tiles))
+
+
+@pytest.mark.parametrize("n", [0, 1, 15, 16, 17, 255, 256, 257, 5000])
+def test_mma_recurrence_and_single_pass_equal_the_definition(oracle_lib, n):
+    from oracle import mma_model as M
+    x = W.small_integers(n, seed=99 + n)
+    want = oracle_lib.sum_f16(x)[0]
+    vals = x.astype(np.float64)
+    assert M.recurrence(vals, 4) == want
+    assert M.recurrence(vals, 16) == want
+    for R, wpb in ((1, 8), (4, 4), (5, 1)):
+        assert M.single_pass(vals, 16, R, wpb) == want
+
+
+def test_blocked_special_values(oracle_lib):
+    x = W.ones(1000).view(np.uint16).copy()
+    x[900] = 0x7C00
+    assert oracle_lib.sum_f16_blocked(x, 4)[0] == math.inf
+    x[10] = 0xFC00
+    assert math.isnan(oracle_lib.sum_f16_blocked(x, 4)[0])
+    assert oracle_lib.sum_f16_blocked(W.ones(0), 4)[:2] == (0.0, 0.0)
+    assert oracle_lib.sum_f16_blocked(W.ones(3), 8)[:2] == (3.0, 3.0)
