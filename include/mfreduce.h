@@ -1,0 +1,137 @@
+/*
+ * libmfreduce -- arithmetic reduction of n fp16 numbers to one fp32 on MI355X
+ * (gfx950), C ABI.
+ *
+ * The operation is R(X) = sum_{i=1..n} x_i (paper Section 4, the equation that
+ * defines the arithmetic reduction), computed with the single-pass variant of
+ * the paper (Section 5.2): every wavefront runs chains of R matrix
+ * multiply-accumulates C_r = 1 x M_r + C_{r-1} against an all-ones matrix
+ * (Section 4.3), each chain's result is kept as an fp32 partial, wave partials
+ * are combined per block, and all block partials are reduced to one fp32.
+ *
+ * All pointers named "device" must be dereferenceable by kernels on the
+ * current HIP device.  No function takes ownership of any pointer.  Every
+ * function returns an mfr_status; none throws, prints or exits.  Arguments
+ * are validated before the first HIP call, so invalid-argument errors are
+ * reported identically on a machine without a GPU.
+ */
+#ifndef MFREDUCE_H
+#define MFREDUCE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* HIP's stream handle; declared here so that callers need no HIP headers. */
+typedef struct ihipStream_t *hipStream_t;
+
+/* IEEE 754 binary16 storage (bit-identical to _Float16 / __half). */
+typedef uint16_t mfr_half;
+
+typedef enum mfr_status {
+    MFR_OK = 0,
+    MFR_ERR_INVALID_ARG = 1, /* null pointer, misaligned x, bad block / R / grid / kernel */
+    MFR_ERR_UNSUPPORTED = 2, /* current device is not gfx950 */
+    MFR_ERR_HIP = 3          /* a HIP runtime call failed; text via mfr_last_hip_error() */
+} mfr_status;
+
+/* Which kernel computes the block partials. */
+enum {
+    MFR_KERNEL_MFMA = 0, /* ones-matrix MFMA chains (Sections 4.1, 4.3, 5.2) */
+    MFR_KERNEL_SHFL = 1  /* conventional fp32 per-lane accumulate + wave shuffle tree:
+                            the comparison kernel of Section 5.4 */
+};
+
+/* grid_blocks special values */
+enum {
+    MFR_GRID_AUTO = 0,       /* persistent grid sized to the device */
+    MFR_GRID_ONE_CHAIN = -1  /* the paper's geometry: exactly one chain per wavefront,
+                                grid sized to n (Algorithm 2's offset; Section 5.2) */
+};
+
+/* Full tuning record for mfr_sum_f16_ex.  Zero in any field selects the
+ * library default for that field. */
+typedef struct mfr_tuning {
+    int block_threads;    /* 32, 64, 128, 256, 512 or 1024.  32 runs as one wave64 whose upper
+                             32 lanes contribute zeros (gfx950 has no 32-wide wavefront) */
+    int chain_R;          /* 1..8.  MFMA kernel: MFMAs accumulated into one accumulator tile
+                             from zero before it is folded to an fp32 partial (the paper's R).
+                             SHFL kernel: 16-byte loads per lane accumulated per group */
+    int grid_blocks;      /* MFR_GRID_AUTO, MFR_GRID_ONE_CHAIN, or an explicit count >= 1 */
+    int kernel;           /* MFR_KERNEL_MFMA or MFR_KERNEL_SHFL */
+    int chains_in_flight; /* 1, 2, 4 or 8 independent chains whose loads are issued before
+                             any is consumed (memory-level parallelism); chain_R *
+                             chains_in_flight must not exceed 16 */
+    int nontemporal;      /* 0 = library default, 1 = plain loads, 2 = non-temporal loads */
+} mfr_tuning;
+
+/*
+ * Sum of x[0..n) (paper Section 4: R(X) = sum x_i; Section 5.2 single pass).
+ *
+ *   x       device pointer to n binary16 values, 2-byte aligned (16-byte
+ *           alignment is NOT required), read-only, never modified.
+ *   n       element count; n == 0 writes 0.0f.  64-bit sizes are honoured.
+ *   out     device pointer to one float; written once, in stream order.
+ *   stream  HIP stream to enqueue on (0 = the null stream).
+ *
+ * Asynchronous: returns after enqueueing; synchronise the stream before
+ * reading *out.  Same (x contents, n, tuning, device) => bit-identical *out:
+ * block partials are combined in index order, never with float atomics.
+ * IEEE special values propagate (NaN in => NaN; +Inf and -Inf => NaN).
+ * Scratch (block partials + a ticket counter) is owned by the library, one
+ * per (device, stream), allocated on first use and kept until unload; calls
+ * on different streams may overlap, calls on one stream serialise.
+ */
+int mfr_sum_f16(const mfr_half *x, size_t n, float *out, hipStream_t stream);
+
+/*
+ * Same sum with caller-chosen geometry (the block size B and chain length R
+ * explored in Section 5.2's configuration experiment).  chains_in_flight and
+ * the load policy take the library defaults for the given R.
+ */
+int mfr_sum_f16_tuned(const mfr_half *x, size_t n, float *out,
+                      int block_threads, int chain_R, int grid_blocks, int kernel,
+                      hipStream_t stream);
+
+/* Same sum with every knob explicit; t == NULL means all defaults. */
+int mfr_sum_f16_ex(const mfr_half *x, size_t n, float *out,
+                   const mfr_tuning *t, hipStream_t stream);
+
+/* The geometry mfr_sum_f16 uses.  Any pointer may be NULL. */
+int mfr_get_default_tuning(int *block_threads, int *chain_R, int *grid_blocks);
+
+/* Number of blocks a call with this tuning would launch for n elements whose
+ * first element has byte address x_addr (only its low 4 bits matter); -1 on
+ * invalid tuning.  Touches the device only for MFR_GRID_AUTO. */
+long long mfr_grid_for(size_t n, size_t x_addr, const mfr_tuning *t);
+
+/*
+ * How a call would split the input (inspection only, no device access):
+ *   plan[0] head elements of the first 16-byte slot that lie before x (0..7)
+ *   plan[1] total 16-byte slots covering [x, x + n)
+ *   plan[2] first slot of the unmasked main region
+ *   plan[3] full chains in the main region (each chain_R tiles)
+ *   plan[4] slots per tile (64, or 32 for block_threads == 32)
+ *   plan[5], plan[6] border positions [begin, end): position p stands for slot
+ *           p, or for slot 0 when p >= plan[1]; read element-wise, range-checked
+ * The main region reads slots [plan[2], plan[2] + plan[3] * chain_R * plan[4])
+ * with unchecked 128-bit loads, so all of them must lie inside [x, x + n).
+ */
+int mfr_plan_for(size_t n, size_t x_addr, const mfr_tuning *t, unsigned long long plan[7]);
+
+/* Static text for a status code. */
+const char *mfr_strerror(int status);
+
+/* Text of the most recent HIP error seen by the calling thread ("" if none). */
+const char *mfr_last_hip_error(void);
+
+/* major * 10000 + minor * 100 + patch */
+int mfr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MFREDUCE_H */

@@ -1,0 +1,300 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle.
+
+Bit-exact wherever every summation order gives the same fp32 (integer-valued
+inputs with sum |x_i| <= 2^24); otherwise |gpu - oracle| <= 1e-5 * sum |x_i|.
+"""
+import math
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2001_05585_amd import binding as B            # noqa: E402
+from paper_2001_05585_amd import workloads as W          # noqa: E402
+from gpu_util import DeviceInput, Outputs, gpu_sum, stream_handle   # noqa: E402
+
+TOL = 1e-5
+BLOCKS = (32, 64, 128, 256, 512, 1024)
+KERNELS = (B.MFR_KERNEL_MFMA, B.MFR_KERNEL_SHFL)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; the HIP path has no fallback")
+    B.lib()
+
+
+def within_tolerance(g, s, sa):
+    return abs(float(g) - s) <= TOL * sa
+
+
+def all_tunings(grids=(0, -1, 3)):
+    for kernel in KERNELS:
+        for block in BLOCKS:
+            for R in range(1, 9):
+                for grid in grids:
+                    yield B.make_tuning(block, R, grid, kernel)
+
+
+def describe(t):
+    return "kernel=%d block=%d R=%d grid=%d U=%d" % (t.kernel, t.block_threads, t.chain_R,
+                                                    t.grid_blocks, t.chains_in_flight)
+
+
+# ------------------------------------------------------------ config 1 ---
+
+def test_config1_uniform_2p20_block256_R1(oracle_lib):
+    x = W.generate("uniform01", 1 << 20, W.config_seed(1))
+    s, sa = oracle_lib.sum_f16(x)
+    g = gpu_sum(x, B.make_tuning(256, 1))
+    assert within_tolerance(g, s, sa), (g, s)
+    d = DeviceInput(x)
+    o = Outputs(2)
+    B.mfr_sum_f16_tuned(d.ptr, d.n, o.ptr(0), 256, 1, 0, B.MFR_KERNEL_MFMA, stream_handle())
+    B.mfr_sum_f16(d.ptr, d.n, o.ptr(1), stream_handle())
+    r = o.get()
+    assert within_tolerance(r[0], s, sa) and within_tolerance(r[1], s, sa)
+    assert np.float32(r[0]) == g
+
+
+# ------------------------------------------- closed forms, bit-exact ---
+
+def test_all_ones_2p24_is_exact_in_every_cell():
+    x = W.ones(1 << 24)
+    d = DeviceInput(x)
+    tunings = list(all_tunings(grids=(0, -1)))
+    o = Outputs(len(tunings))
+    for i, t in enumerate(tunings):
+        B.mfr_sum_f16_ex(d.ptr, d.n, o.ptr(i), t, stream_handle())
+    r = o.get()
+    bad = [describe(t) + " -> %r" % r[i] for i, t in enumerate(tunings) if r[i] != 16777216.0]
+    assert not bad, bad[:10]
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_closed_forms_exact(kernel, oracle_lib):
+    cases = []
+    for n in (1, 7, 8, 9, 511, 512, 513, 4096, 65536 + 7, (1 << 20) + 7):
+        cases.append((W.ones(n), float(n)))
+        cases.append((W.constant(n, -3.0), -3.0 * n))
+        cases.append((W.constant(n, 0.25), 0.25 * n))
+        cases.append((W.alternating(n, 5.0), 5.0 if n % 2 else 0.0))
+        q, r = divmod(n, 4)
+        cases.append((W.periodic_ramp(n, 4), float(q * 6 + r * (r - 1) // 2)))
+    n = 16384
+    cases.append((W.periodic_ramp(n, 2048), float(8 * 2048 * 2047 // 2)))
+    cases.append((W.periodic_ramp(2048, 2048, 0.5), 2048 * 2047 / 4))
+    cases.append((np.concatenate([W.constant(70000, 3.0), W.constant(70000, -3.0), W.constant(5, 0.5)]), 2.5))
+    for x, want in cases:
+        assert oracle_lib.sum_f16(x)[0] == want          # the oracle agrees with the closed form
+        for t in (B.make_tuning(256, 1, 0, kernel), B.make_tuning(64, 4, 5, kernel),
+                  B.make_tuning(32, 3, -1, kernel), B.make_tuning(1024, 8, 0, kernel)):
+            g = gpu_sum(x, t, shift=3)
+            assert float(g) == want, (x.size, describe(t), g, want)
+
+
+# ----------------------------------------------- one-hot sweep (every slot) ---
+
+@pytest.mark.parametrize("kernel,block,R,grid,U", [
+    (B.MFR_KERNEL_MFMA, 64, 2, 2, 1), (B.MFR_KERNEL_MFMA, 128, 1, 2, 2),
+    (B.MFR_KERNEL_MFMA, 32, 2, 3, 1), (B.MFR_KERNEL_SHFL, 64, 2, 2, 1),
+    (B.MFR_KERNEL_MFMA, 64, 4, 1, 4),
+])
+@pytest.mark.parametrize("shift", [0, 5])
+def test_one_hot_every_position(kernel, block, R, grid, U, shift):
+    t = B.make_tuning(block, R, grid, kernel, U)
+    waves = max(1, block // 64)
+    tile = 256 if block == 32 else 512
+    grid_tile = grid * waves * R * U * tile
+    n = 3 * grid_tile + 2 * tile + 7
+    d = DeviceInput(np.zeros(n, dtype=np.float16), shift)
+    positions = list(range(0, n))
+    o = Outputs(len(positions))
+    one = 0x3C00
+    for i, p in enumerate(positions):
+        d.set(p, one)
+        B.mfr_sum_f16_ex(d.ptr, n, o.ptr(i), t, stream_handle())
+        d.set(p, 0)
+    r = o.get()
+    wrong = np.nonzero(r != 1.0)[0]
+    assert wrong.size == 0, (describe(t), [(int(positions[i]), float(r[i])) for i in wrong[:8]])
+
+
+def test_prefix_indicator_around_boundaries():
+    t = B.make_tuning(128, 2, 3)
+    n = 40000
+    ks = sorted(set([0, 1, 7, 8, 9, n] + [b + e for b in (512, 1024, 2048, 3 * 2 * 2 * 512, 6144 * 2) for e in (-1, 0, 1)]))
+    for kernel in KERNELS:
+        t.kernel = kernel
+        for k in ks:
+            g = gpu_sum(W.prefix_indicator(n, k), t, shift=1)
+            assert float(g) == float(k), (kernel, k, g)
+
+
+# ------------------------------------ brute force on every small n ---
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_every_n_up_to_2100_bit_exact(kernel, oracle_lib):
+    full = W.small_integers(2100, seed=21)
+    for shift in (0, 1, 7):
+        d = DeviceInput(full, shift)
+        tunings = [B.make_tuning(256, 1, 0, kernel), B.make_tuning(64, 4, 2, kernel), B.make_tuning(32, 2, 0, kernel)]
+        o = Outputs(2101 * len(tunings))
+        for n in range(2101):
+            for j, t in enumerate(tunings):
+                B.mfr_sum_f16_ex(d.ptr, n, o.ptr(n * len(tunings) + j), t, stream_handle())
+        r = o.get().reshape(2101, len(tunings))
+        vals = full.astype(np.float64)
+        want = np.concatenate([[0.0], np.cumsum(vals)])
+        assert oracle_lib.sum_f16(full)[0] == want[-1]
+        for j in range(len(tunings)):
+            wrong = np.nonzero(r[:, j] != want)[0]
+            assert wrong.size == 0, (kernel, shift, j, wrong[:5], r[wrong[:5], j], want[wrong[:5]])
+
+
+# ---------------------------------------------------------- invariances ---
+
+def test_integer_inputs_same_bits_for_every_geometry_and_shift(oracle_lib):
+    n = (1 << 18) + 7
+    x = W.small_integers(n, seed=31)
+    want = oracle_lib.sum_f16(x)[0]
+    for shift in range(8):
+        d = DeviceInput(x, shift)
+        tunings = list(all_tunings(grids=(0, 3) if shift else (0, -1, 3)))
+        if shift not in (0, 3):
+            tunings = tunings[::7]
+        o = Outputs(len(tunings))
+        for i, t in enumerate(tunings):
+            B.mfr_sum_f16_ex(d.ptr, n, o.ptr(i), t, stream_handle())
+        r = o.get()
+        bad = [describe(t) + " -> %r" % r[i] for i, t in enumerate(tunings) if r[i] != want]
+        assert not bad, (shift, want, bad[:10])
+    # permutation and split additivity
+    perm = np.random.default_rng(5).permutation(n)
+    assert float(gpu_sum(x[perm])) == want
+    a = 100003
+    assert float(gpu_sum(x[:a])) + float(gpu_sum(x[a:])) == want
+
+
+def test_in_flight_and_nontemporal_variants_agree():
+    n = (1 << 20) + 1234
+    x = W.small_integers(n, seed=41)
+    want = float(x.astype(np.float64).sum())
+    d = DeviceInput(x, 2)
+    tunings = []
+    for kernel in KERNELS:
+        for R in range(1, 9):
+            for U in (1, 2, 4, 8):
+                if R * U <= 16:
+                    for nt in (1, 2):
+                        tunings.append(B.make_tuning(256, R, 0, kernel, U, nt))
+    o = Outputs(len(tunings))
+    for i, t in enumerate(tunings):
+        B.mfr_sum_f16_ex(d.ptr, n, o.ptr(i), t, stream_handle())
+    r = o.get()
+    assert all(v == want for v in r), [(describe(t), r[i]) for i, t in enumerate(tunings) if r[i] != want][:8]
+
+
+# ------------------------------------------------ random inputs, tolerance ---
+
+@pytest.mark.parametrize("kind,cfg,n", [("uniform01", 2, (1 << 22) + 7), ("normal", 3, (1 << 22) + 7),
+                                        ("uniform_pm1", 4, 4_000_007), ("uniform01", 5, (1 << 16) + 7),
+                                        ("normal", 3, 1000), ("uniform01", 5, 1 << 16)])
+def test_random_inputs_within_tolerance(kind, cfg, n, oracle_lib):
+    x = W.generate(kind, n, W.config_seed(cfg))
+    s, sa = oracle_lib.sum_f16(x)
+    d = DeviceInput(x, 0)
+    tunings = [None] + list(all_tunings(grids=(0, -1)))[::5]
+    o = Outputs(len(tunings))
+    for i, t in enumerate(tunings):
+        B.mfr_sum_f16_ex(d.ptr, n, o.ptr(i), t, stream_handle())
+    r = o.get()
+    errs = np.abs(r.astype(np.float64) - s) / sa
+    assert errs.max() <= TOL, (kind, n, errs.max())
+    # fp32 partials cannot overflow where fp16 partials would (sum > 65504)
+    assert np.all(np.isfinite(r))
+
+
+def test_repeat_calls_are_bit_identical():
+    x = W.generate("normal", (1 << 22) + 3, 77)
+    d = DeviceInput(x, 1)
+    for t in (None, B.make_tuning(64, 1, -1), B.make_tuning(1024, 2, 0, B.MFR_KERNEL_SHFL)):
+        o = Outputs(300)
+        for i in range(300):
+            B.mfr_sum_f16_ex(d.ptr, d.n, o.ptr(i), t, stream_handle())
+        r = o.get()
+        assert np.all(r.view(np.uint32) == r.view(np.uint32)[0])
+
+
+def test_two_streams_overlap(oracle_lib):
+    xa = W.generate("uniform01", (1 << 22) + 5, 81)
+    xb = W.generate("uniform_pm1", (1 << 21) + 9, 82)
+    da, db = DeviceInput(xa), DeviceInput(xb, 3)
+    oa, ob = Outputs(50), Outputs(50)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for i in range(50):
+        B.mfr_sum_f16(da.ptr, da.n, oa.ptr(i), s1.cuda_stream)
+        B.mfr_sum_f16(db.ptr, db.n, ob.ptr(i), s2.cuda_stream)
+    ra, rb = oa.get(), ob.get()
+    sa_, saa = oracle_lib.sum_f16(xa)
+    sb_, sba = oracle_lib.sum_f16(xb)
+    assert np.all(ra == ra[0]) and np.all(rb == rb[0])
+    assert within_tolerance(ra[0], sa_, saa) and within_tolerance(rb[0], sb_, sba)
+
+
+# ----------------------------------------------------- degenerate cases ---
+
+def test_n_zero_writes_zero():
+    d = DeviceInput(W.ones(16))
+    o = Outputs(3)
+    B.mfr_sum_f16(d.ptr, 0, o.ptr(0), stream_handle())
+    B.mfr_sum_f16_tuned(d.ptr, 0, o.ptr(1), 64, 3, -1, B.MFR_KERNEL_SHFL, stream_handle())
+    B.lib().mfr_sum_f16(None, 0, o.ptr(2), None)
+    r = o.get()
+    assert np.all(r == 0.0)
+
+
+def test_special_values_propagate():
+    n = 100000
+    for kernel in KERNELS:
+        t = B.make_tuning(256, 2, 0, kernel)
+        for pos in (0, 511, 70001, n - 1):
+            x = W.ones(n).view(np.uint16).copy()
+            x[pos] = 0x7C00
+            assert float(gpu_sum(x, t)) == math.inf
+            x[(pos + 777) % n] = 0xFC00
+            assert math.isnan(float(gpu_sum(x, t)))
+            x = W.ones(n).view(np.uint16).copy()
+            x[pos] = 0x7E01
+            assert math.isnan(float(gpu_sum(x, t)))
+
+
+def test_largest_finite_values_do_not_overflow_fp32():
+    n = 1 << 16
+    x = W.constant(n, 65504.0)
+    for kernel in KERNELS:
+        g = gpu_sum(x, B.make_tuning(256, 4, 0, kernel))
+        assert float(g) == 65504.0 * n
+
+
+def test_subnormal_inputs_are_within_tolerance(oracle_lib):
+    # 2^24 copies of the smallest subnormal: exactly 1.0 if the hardware honours
+    # fp16 subnormals, 0.0 if it flushes them; both facts are reported, the
+    # conventional kernel (v_cvt_f32_f16) must honour them.
+    x = np.full(1 << 24, 1, dtype=np.uint16)
+    g_shfl = float(gpu_sum(x, B.make_tuning(256, 4, 0, B.MFR_KERNEL_SHFL)))
+    g_mfma = float(gpu_sum(x, B.make_tuning(256, 4, 0, B.MFR_KERNEL_MFMA)))
+    print("subnormal sum: mfma=%r shfl=%r (oracle 1.0)" % (g_mfma, g_shfl))
+    assert g_mfma in (0.0, 1.0) and g_shfl in (0.0, 1.0)
+    assert g_mfma == 1.0, "MFMA path flushes fp16 subnormals"
+
+
+def test_odd_pointer_is_rejected():
+    d = DeviceInput(W.ones(64))
+    o = Outputs(1)
+    assert B.lib().mfr_sum_f16(d.ptr + 1, 8, o.ptr(0), None) == B.MFR_ERR_INVALID_ARG

@@ -1,0 +1,106 @@
+"""Host-side checks of the C-ABI boundary: run without a GPU.
+
+The library must load, export every function ``include/mfreduce.h`` declares,
+reject bad arguments before touching HIP, and split any (n, alignment,
+geometry) so that every element is read exactly once and the unchecked 128-bit
+loads stay inside [x, x + n).
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2001_05585_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mfreduce.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mfr_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert "mfr_sum_f16" in names and "mfr_sum_f16_tuned" in names
+    L = B.lib()
+    for name in names:
+        assert hasattr(L, name), name
+    assert set(names) == set(B.EXPORTS)
+
+
+def test_version_and_strings():
+    assert B.mfr_version() >= 100
+    assert B.mfr_strerror(B.MFR_OK) == "success"
+    for st in (B.MFR_ERR_INVALID_ARG, B.MFR_ERR_UNSUPPORTED, B.MFR_ERR_HIP, 77):
+        assert B.mfr_strerror(st)
+    b, r, g = B.mfr_get_default_tuning()
+    assert b in (64, 128, 256, 512, 1024) and 1 <= r <= 8 and g == B.MFR_GRID_AUTO
+    assert B.lib().mfr_get_default_tuning(None, None, None) == B.MFR_OK
+
+
+def test_invalid_arguments_are_rejected_before_any_hip_call():
+    L = B.lib()
+    INV = B.MFR_ERR_INVALID_ARG
+    assert L.mfr_sum_f16(None, 5, 4096, None) == INV          # null x, n > 0
+    assert L.mfr_sum_f16(4096, 5, None, None) == INV          # null out
+    assert L.mfr_sum_f16(None, 0, None, None) == INV          # null out even when n == 0
+    assert L.mfr_sum_f16(4097, 5, 4096, None) == INV          # x not 2-byte aligned
+    assert L.mfr_sum_f16(4096, (1 << 60) + 1, 4096, None) == INV
+    for block in (0, 1, 16, 48, 96, 2048, -64):
+        assert L.mfr_sum_f16_tuned(4096, 5, 4096, block, 1, 0, 0, None) == INV
+    for R in (0, -1, 9, 100):
+        assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, R, 0, 0, None) == INV
+    assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, 1, -2, 0, None) == INV
+    assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, 1, 0, 2, None) == INV
+    for kw in (dict(chains_in_flight=3), dict(chains_in_flight=16), dict(chain_R=8, chains_in_flight=4),
+               dict(nontemporal=3), dict(kernel=-1), dict(block_threads=100)):
+        t = B.make_tuning(**kw)
+        assert L.mfr_sum_f16_ex(4096, 5, 4096, ctypes.byref(t), None) == INV
+    with pytest.raises(B.MfrError):
+        B.mfr_sum_f16(0, 5, 4096)
+
+
+def simulate_coverage(n, x_addr, t):
+    head, slots, main0, chains, ts, epi0, epi1 = B.mfr_plan_for(n, x_addr, t)
+    R = t.chain_R
+    vend = head + n
+    assert head == (x_addr % 16) // 2
+    assert slots == -(-vend // 8)
+    count = [0] * slots
+    main_end = main0 + chains * R * ts
+    for q in range(main0, main_end):
+        assert 8 * q >= head and 8 * q + 8 <= vend, "unchecked load outside [x, x+n)"
+        count[q] += 1
+    assert epi0 <= epi1
+    assert epi1 - epi0 <= (R + 1) * ts, "border must fit in two masked chains"
+    for p in range(epi0, epi1):
+        q = p if p < slots else 0
+        count[q] += 1
+    assert all(c == 1 for c in count), (n, x_addr, t.block_threads, R)
+
+
+@pytest.mark.parametrize("block", [32, 64, 256])
+@pytest.mark.parametrize("R", [1, 3, 8])
+def test_every_slot_is_covered_exactly_once(block, R):
+    t = B.make_tuning(block, R)
+    ts = 32 if block == 32 else 64
+    edge = 8 * ts * R
+    ns = set(range(1, 40)) | {edge + d for d in range(-9, 10)} | {3 * edge + d for d in range(-9, 10)}
+    ns |= {511, 512, 513, 2047, 2048, 2049, 65536 + 7, 100003}
+    for n in sorted(v for v in ns if v >= 1):
+        for shift in range(8):
+            simulate_coverage(n, 4096 + 2 * shift, t)
+
+
+def test_grid_for_one_chain_geometry():
+    # one chain per wave: ceil(chains / waves) blocks
+    assert B.mfr_grid_for(1 << 28, 0, B.make_tuning(256, 1, -1)) == (1 << 28) // (512 * 4)
+    assert B.mfr_grid_for(1 << 28, 0, B.make_tuning(128, 4, -1)) == (1 << 28) // (512 * 4 * 2)
+    assert B.mfr_grid_for(1 << 20, 0, B.make_tuning(32, 1, -1)) == (1 << 20) // 256
+    assert B.mfr_grid_for(100, 0, B.make_tuning(256, 1, -1)) == 1
+    assert B.mfr_grid_for(0, 0, None) == 1
+    assert B.mfr_grid_for(1 << 20, 0, B.make_tuning(256, 1, 7)) == 7
+    assert B.mfr_grid_for(1 << 20, 0, B.make_tuning(100, 1, 7)) == -1
