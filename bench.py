@@ -139,7 +139,7 @@ def headline(args):
     x = W.generate(kind, n, W.config_seed(cfg))
     bufs = make_buffers(torch, np, x, args.buffers)
     out = torch.zeros(4, dtype=torch.float32, device="cuda")
-    tuning = B.make_tuning(args.block, args.R, args.grid, args.kernel, args.in_flight, args.nontemporal)
+    tuning = B.make_tuning(args.block, args.R, args.grid, args.kernel, args.in_flight, args.nontemporal, args.combine)
     grid = B.mfr_grid_for(n, bufs[0].data_ptr(), tuning)
     log("timing: block=%d R=%d grid=%d kernel=%d ..." % (tuning.block_threads, tuning.chain_R, grid, tuning.kernel))
     wall, ev = time_calls(torch, B, bufs, n, out, tuning, args.steps, args.warmup)
@@ -193,8 +193,10 @@ def main():
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--in-flight", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=0)
+    ap.add_argument("--combine", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", choices=["config2", "config5", "tune"], default=None)
+    ap.add_argument("--quick", type=int, default=0, help="sweeps: keep every k-th combination")
     ap.add_argument("--out", default=None, help="file for sweep tables (default gpurun_out/<sweep>.txt)")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -52,6 +52,14 @@ enum {
                                 grid sized to n (Algorithm 2's offset; Section 5.2) */
 };
 
+/* How the block partials become one value (Section 5.2 uses float atomics on
+ * one location; both modes here add them in index order instead). */
+enum {
+    MFR_COMBINE_AUTO = 0,          /* single launch for grids up to 1024 blocks, else two */
+    MFR_COMBINE_SINGLE_LAUNCH = 1, /* the block that draws the last ticket adds the partials */
+    MFR_COMBINE_TWO_LAUNCHES = 2   /* a second one-block kernel adds the partials */
+};
+
 /* Full tuning record for mfr_sum_f16_ex.  Zero in any field selects the
  * library default for that field. */
 typedef struct mfr_tuning {
@@ -66,6 +74,7 @@ typedef struct mfr_tuning {
                              any is consumed (memory-level parallelism); chain_R *
                              chains_in_flight must not exceed 16 */
     int nontemporal;      /* 0 = library default, 1 = plain loads, 2 = non-temporal loads */
+    int combine;          /* MFR_COMBINE_* */
 } mfr_tuning;
 
 /*

@@ -136,6 +136,34 @@ __device__ __forceinline__ double wave64_sum_f64(double v)
     return v;
 }
 
+// All threads of one block: sum of partials[0..count) in binary64, fixed order
+// (thread t takes t, t + blockDim, ... with four running sums, then lanes, then
+// waves).  Loads are device-scope atomic loads so that values published by
+// other compute dies are observed.  Result valid in thread 0.
+__device__ __forceinline__ double block_sum_f64(const float *partials, unsigned int count, double *lds)
+{
+    const unsigned int lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, wpb = (blockDim.x + 63u) >> 6;
+    double t0 = 0.0, t1 = 0.0, t2 = 0.0, t3 = 0.0;
+    const unsigned int step = blockDim.x;
+    unsigned int i = threadIdx.x;
+    for (; i + 3u * step < count; i += 4u * step) {
+        const float p0 = __hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float p1 = __hip_atomic_load(&partials[i + step], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float p2 = __hip_atomic_load(&partials[i + 2u * step], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float p3 = __hip_atomic_load(&partials[i + 3u * step], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t0 += (double)p0; t1 += (double)p1; t2 += (double)p2; t3 += (double)p3;
+    }
+    for (; i < count; i += step)
+        t0 += (double)__hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    double t = wave64_sum_f64((t0 + t1) + (t2 + t3));
+    if (lane == 0) lds[wave] = t;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0)
+        for (unsigned int w = 0; w < wpb; ++w) total += lds[w];
+    return total;
+}
+
 // ------------------------------------------------------ tile consumers ---
 
 // One MFMA of the chain: C = 1 x M + C  (Section 4.3).  A is the all-ones
@@ -264,27 +292,40 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
         if (threadIdx.x == 0) *a.out = block_sum;
         return;
     }
+    if (a.ticket == nullptr) {
+        // two-launch combine: the partial is picked up by combine_kernel
+        if (threadIdx.x == 0) a.partials[blockIdx.x] = block_sum;
+        return;
+    }
+    // Single-launch combine.  A release fence at device scope costs a write-back
+    // of the whole L2 per block, so ordering is obtained from the atomics
+    // themselves: the partial is published with a returning device-scope
+    // exchange, and the ticket is drawn only after that exchange has returned,
+    // i.e. after it has been performed at the device's coherence point.  The
+    // block that draws the last ticket therefore finds every partial there.
     if (threadIdx.x == 0) {
-        __hip_atomic_store(&a.partials[blockIdx.x], block_sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();
+        unsigned int prev = __hip_atomic_exchange((unsigned int *)&a.partials[blockIdx.x],
+                                                  __float_as_uint(block_sum), __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+        // the exchange result must be in a register (waits for it) and no later
+        // memory operation may be moved above this point
+        asm volatile("" : "+v"(prev) : : "memory");
         // wraps to 0 after the last block, so the counter is ready for the next call
         const unsigned int old = atomicInc(a.ticket, gridDim.x - 1u);
         is_last = (old == gridDim.x - 1u) ? 1u : 0u;
     }
     __syncthreads();
     if (!is_last) return;
-    __threadfence();
-    double t = 0.0;
-    for (unsigned int i = threadIdx.x; i < gridDim.x; i += blockDim.x)
-        t += (double)__hip_atomic_load(&a.partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    t = wave64_sum_f64(t);
-    if (lane == 0) wave_partials_f64[wave] = t;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double total = 0.0;
-        for (unsigned int i = 0; i < wpb; ++i) total += wave_partials_f64[i];
-        *a.out = (float)total;
-    }
+    const double total = block_sum_f64(a.partials, gridDim.x, wave_partials_f64);
+    if (threadIdx.x == 0) *a.out = (float)total;
+}
+
+// Second launch of the two-launch combine: one block adds all block partials.
+__global__ void __launch_bounds__(1024) combine_kernel(const float *partials, unsigned int count, float *out)
+{
+    __shared__ double wave_partials_f64[kMaxWavesPerBlock];
+    const double total = block_sum_f64(partials, count, wave_partials_f64);
+    if (threadIdx.x == 0) *out = (float)total;
 }
 
 __global__ void store_zero_kernel(float *out) { *out = 0.f; }
@@ -323,7 +364,8 @@ std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
 
 constexpr int kDefaultBlock = 256;
 constexpr int kDefaultR = 4;
-constexpr int kDefaultWavesPerCU = 32;
+constexpr int kDefaultWavesPerCU = 4;
+constexpr long long kTicketMaxBlocks = 1024;   // larger grids combine with a second launch
 
 int default_in_flight(int R)
 {
@@ -355,8 +397,9 @@ int resolve_tuning(const mfr_tuning *in, mfr_tuning *t)
     const int u = z.chains_in_flight;
     if (!(u == 1 || u == 2 || u == 4 || u == 8)) return MFR_ERR_INVALID_ARG;
     if (u * z.chain_R > 16) return MFR_ERR_INVALID_ARG;
-    if (z.nontemporal == 0) z.nontemporal = 1;
+    if (z.nontemporal == 0) z.nontemporal = 2;
     if (z.nontemporal != 1 && z.nontemporal != 2) return MFR_ERR_INVALID_ARG;
+    if (z.combine < 0 || z.combine > 2) return MFR_ERR_INVALID_ARG;
     *t = z;
     return MFR_OK;
 }
@@ -528,14 +571,22 @@ int sum_impl(const mfr_half *x, size_t n, float *out, const mfr_tuning *tin, hip
     }
     p.a.base = (const uint4v *)((size_t)x & ~(size_t)15);
     p.a.x = (const unsigned short *)x;
+    const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES ||
+                              (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
     p.a.partials = s.partials;
-    p.a.ticket = s.ticket;
+    p.a.ticket = two_launches ? nullptr : s.ticket;
     p.a.out = out;
 
     const hipError_t e = t.kernel == MFR_KERNEL_MFMA
                              ? launch_k<MFR_KERNEL_MFMA>(p, (int)grid, t, stream)
                              : launch_k<MFR_KERNEL_SHFL>(p, (int)grid, t, stream);
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    if (grid > 1 && two_launches) {
+        hipLaunchKernelGGL(combine_kernel, dim3(1), dim3(grid > 4096 ? 1024 : 256), 0, stream,
+                           (const float *)s.partials, (unsigned int)grid, out);
+        const hipError_t e2 = hipGetLastError();
+        if (e2 != hipSuccess) return hip_fail(e2, "combine launch");
+    }
     return MFR_OK;
 }
 

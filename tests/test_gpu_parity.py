@@ -33,16 +33,18 @@ def within_tolerance(g, s, sa):
 
 
 def all_tunings(grids=(0, -1, 3)):
+    i = 0
     for kernel in KERNELS:
         for block in BLOCKS:
             for R in range(1, 9):
                 for grid in grids:
-                    yield B.make_tuning(block, R, grid, kernel)
+                    i += 1
+                    yield B.make_tuning(block, R, grid, kernel, combine=i % 3)
 
 
 def describe(t):
-    return "kernel=%d block=%d R=%d grid=%d U=%d" % (t.kernel, t.block_threads, t.chain_R,
-                                                    t.grid_blocks, t.chains_in_flight)
+    return "kernel=%d block=%d R=%d grid=%d U=%d nt=%d combine=%d" % (
+        t.kernel, t.block_threads, t.chain_R, t.grid_blocks, t.chains_in_flight, t.nontemporal, t.combine)
 
 
 # ------------------------------------------------------------ config 1 ---
@@ -219,10 +221,30 @@ def test_random_inputs_within_tolerance(kind, cfg, n, oracle_lib):
     assert np.all(np.isfinite(r))
 
 
+def test_both_combine_modes_agree(oracle_lib):
+    n = (1 << 23) + 77
+    x = W.generate("uniform_pm1", n, 123)
+    s, sa = oracle_lib.sum_f16(x)
+    d = DeviceInput(x, 4)
+    tunings = [B.make_tuning(block, R, grid, 0, 0, 0, combine)
+               for block in (64, 256, 1024) for R in (1, 4) for grid in (0, 2, 777, 5000, -1)
+               for combine in (B.MFR_COMBINE_SINGLE_LAUNCH, B.MFR_COMBINE_TWO_LAUNCHES)]
+    o = Outputs(len(tunings))
+    for i, t in enumerate(tunings):
+        B.mfr_sum_f16_ex(d.ptr, n, o.ptr(i), t, stream_handle())
+    r = o.get()
+    assert np.abs(r.astype(np.float64) - s).max() <= TOL * sa
+    # the two modes add the same fp32 partials in binary64: same fp32 result up to one rounding
+    pairs = r.reshape(-1, 2)
+    assert np.all(np.abs(pairs[:, 0] - pairs[:, 1]) <= np.spacing(np.abs(pairs[:, 0]).astype(np.float32)))
+
+
 def test_repeat_calls_are_bit_identical():
     x = W.generate("normal", (1 << 22) + 3, 77)
     d = DeviceInput(x, 1)
-    for t in (None, B.make_tuning(64, 1, -1), B.make_tuning(1024, 2, 0, B.MFR_KERNEL_SHFL)):
+    for t in (None, B.make_tuning(64, 1, -1), B.make_tuning(1024, 2, 0, B.MFR_KERNEL_SHFL),
+              B.make_tuning(128, 2, 4000, 0, 0, 0, B.MFR_COMBINE_SINGLE_LAUNCH),
+              B.make_tuning(128, 2, 4000, 0, 0, 0, B.MFR_COMBINE_TWO_LAUNCHES)):
         o = Outputs(300)
         for i in range(300):
             B.mfr_sum_f16_ex(d.ptr, d.n, o.ptr(i), t, stream_handle())

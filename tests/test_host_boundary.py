@@ -56,7 +56,7 @@ def test_invalid_arguments_are_rejected_before_any_hip_call():
     assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, 1, -2, 0, None) == INV
     assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, 1, 0, 2, None) == INV
     for kw in (dict(chains_in_flight=3), dict(chains_in_flight=16), dict(chain_R=8, chains_in_flight=4),
-               dict(nontemporal=3), dict(kernel=-1), dict(block_threads=100)):
+               dict(nontemporal=3), dict(kernel=-1), dict(block_threads=100), dict(combine=3), dict(combine=-1)):
         t = B.make_tuning(**kw)
         assert L.mfr_sum_f16_ex(4096, 5, 4096, ctypes.byref(t), None) == INV
     with pytest.raises(B.MfrError):
