@@ -180,6 +180,32 @@ def headline(args):
     print(json.dumps(result), flush=True)
 
 
+def traffic(args):
+    """A short run for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: a few launches of the
+    sum kernel on rotating buffers, and a plain elementwise copy of the same 512 MiB (reads n*2
+    bytes, writes n*2 bytes) whose counter reading calibrates the unit of the counters."""
+    import numpy as np
+    import torch
+    from paper_2001_05585_amd import binding as B
+    from paper_2001_05585_amd import workloads as W
+    torch.cuda.set_device(0)
+    n = args.n
+    x = W.generate("normal", n, W.config_seed(3))
+    bufs = make_buffers(torch, np, x, args.buffers)
+    dst = torch.empty_like(bufs[0])
+    out = torch.zeros(4, dtype=torch.float32, device="cuda")
+    tuning = B.make_tuning(args.block, args.R, args.grid, args.kernel, args.in_flight, args.nontemporal, args.combine)
+    stream = torch.cuda.current_stream().cuda_stream
+    for i in range(args.steps):
+        B.mfr_sum_f16_ex(bufs[i % len(bufs)].data_ptr(), n, out.data_ptr(), tuning, stream)
+    torch.cuda.synchronize()
+    for i in range(4):
+        torch.mul(bufs[i % len(bufs)], 1, out=dst)       # elementwise copy kernel of known size
+    torch.cuda.synchronize()
+    print(json.dumps({"mode": "traffic", "n": n, "sum_launches": args.steps, "copy_launches": 4,
+                      "copy_bytes_read": 2 * n, "copy_bytes_written": 2 * n, "result": float(out[0].item())}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -195,6 +221,7 @@ def main():
     ap.add_argument("--nontemporal", type=int, default=0)
     ap.add_argument("--combine", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic", action="store_true", help="short run for rocprofv3 --pmc counters")
     ap.add_argument("--sweep", choices=["config2", "config5", "tune"], default=None)
     ap.add_argument("--quick", type=int, default=0, help="sweeps: keep every k-th combination")
     ap.add_argument("--out", default=None, help="file for sweep tables (default gpurun_out/<sweep>.txt)")
@@ -202,7 +229,9 @@ def main():
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (--gpus 1); the reduction shards trivially "
                          "but no multi-GPU path is part of it")
-    if args.sweep:
+    if args.traffic:
+        traffic(args)
+    elif args.sweep:
         import bench_sweeps
         bench_sweeps.run(args)
     else:

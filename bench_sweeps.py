@@ -108,6 +108,79 @@ def tune(args, torch, np, B, W):
             emit(f, "# %d %4d %d %d %d %7d %8.2f %7.1f %5.1f" % (kernel, block, R, U, nt, grid, dt * 1e6, gbps, 100 * gbps / HBM_PEAK_GBPS))
 
 
+def arena_pointers(base_ptr, arena_bytes, n, max_count=4096):
+    """Distinct, 256-byte aligned starting addresses for n-element inputs inside one arena."""
+    stride = (2 * n + 255) // 256 * 256
+    count = max(1, min(max_count, arena_bytes // stride))
+    return [base_ptr + i * stride for i in range(count)]
+
+
+def time_rotating(timer, ptrs, n, tuning, steps, warmup):
+    torch, B = timer.torch, timer.B
+    k = len(ptrs)
+    for i in range(warmup):
+        B.mfr_sum_f16_ex(ptrs[i % k], n, timer.out.data_ptr(), tuning, timer.stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        B.mfr_sum_f16_ex(ptrs[(warmup + i) % k], n, timer.out.data_ptr(), tuning, timer.stream)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / steps
+
+
+def config2(args, torch, np, B, W):
+    """Block x R cells (Section 5.2's configuration experiment) at n = 2^26, uniform [0,1)."""
+    n = 1 << 26
+    x = W.generate("uniform01", n, W.config_seed(2))
+    copies = 16                                     # 2 GiB in rotation: the last-level cache cannot hold it
+    bufs = device_buffers(torch, np, x, copies)
+    ptrs = [b.data_ptr() for b in bufs]
+    ones = torch.ones(1 << 24, dtype=torch.float16, device="cuda")
+    timer = Timer(torch, B)
+    heat(timer, bufs, n)
+    with open_out(args, "config2.txt") as f:
+        emit(f, "# config 2: n=2^26 uniform[0,1), MFMA-chain kernel; rotating %d x 128 MiB buffers (cold) and one buffer (warm, cache-resident)" % copies)
+        emit(f, "# grid: persistent = MFR_GRID_AUTO, one-chain = one chain of R MFMAs per wave (the paper's geometry)")
+        emit(f, "# block R grid_mode blocks cold_us cold_Gelem/s cold_GB/s cold_pct warm_us warm_GB/s ones_2p24")
+        for grid_mode, gname in ((B.MFR_GRID_AUTO, "persistent"), (B.MFR_GRID_ONE_CHAIN, "one-chain")):
+            for block in (32, 64, 128, 256, 512, 1024):
+                for R in range(1, 9):
+                    t = B.make_tuning(block, R, grid_mode)
+                    steps = args.steps if grid_mode == B.MFR_GRID_AUTO else max(5, args.steps // 4)
+                    cold = time_rotating(timer, ptrs, n, t, steps, 3)
+                    warm = time_rotating(timer, ptrs[:1], n, t, steps, 3)
+                    B.mfr_sum_f16_ex(ones.data_ptr(), 1 << 24, timer.out.data_ptr(), t, timer.stream)
+                    exact = "exact" if timer.result() == 16777216.0 else "WRONG(%r)" % timer.result()
+                    label = "32(wave64,half-filled)" if block == 32 else str(block)
+                    emit(f, "%s %d %s %d %.2f %.1f %.1f %.1f %.2f %.1f %s" % (
+                        label, R, gname, B.mfr_grid_for(n, ptrs[0], t), cold * 1e6, n / cold / 1e9,
+                        2 * n / cold / 1e9, 100 * 2 * n / cold / 1e9 / HBM_PEAK_GBPS, warm * 1e6, 2 * n / warm / 1e9, exact))
+
+
+def config5(args, torch, np, B, W):
+    """n = 2^16 .. 2^30 and each 2^k + 7; MFMA-chain kernel and shuffle-tree kernel, default tuning."""
+    nmax = (1 << 30) + 7
+    x = W.generate("uniform01", nmax, W.config_seed(5))
+    arena = torch.from_numpy(x.view(np.int16)).cuda()
+    arena_bytes = 2 * nmax
+    timer = Timer(torch, B)
+    heat(timer, [arena], 1 << 28)
+    with open_out(args, "config5.txt") as f:
+        emit(f, "# config 5: uniform[0,1); inputs rotate through a 2 GiB arena (distinct addresses per call) so that")
+        emit(f, "# sizes below the last-level cache capacity are not served from cache; default tuning per kernel")
+        emit(f, "# n kernel blocks us Gelem/s GB/s pct_of_8TB/s")
+        for k in range(16, 31):
+            for n in (1 << k, (1 << k) + 7):
+                ptrs = arena_pointers(arena.data_ptr(), arena_bytes, n)
+                for kernel, kname in ((B.MFR_KERNEL_MFMA, "mfma_chain"), (B.MFR_KERNEL_SHFL, "shfl_tree")):
+                    t = B.make_tuning(kernel=kernel)
+                    steps = max(10, min(args.steps * 4, int(2e-2 / max(2 * n / 6e12, 4e-6))))
+                    dt = time_rotating(timer, ptrs, n, t, steps, 5)
+                    emit(f, "%d %s %d %.2f %.2f %.1f %.2f" % (n, kname, B.mfr_grid_for(n, ptrs[0], t), dt * 1e6,
+                                                            n / dt / 1e9, 2 * n / dt / 1e9, 100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS))
+
+
 def run(args):
     import numpy as np
     import torch
@@ -117,4 +190,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"tune": tune}[args.sweep](args, torch, np, B, W)
+    {"tune": tune, "config2": config2, "config5": config5}[args.sweep](args, torch, np, B, W)

@@ -365,7 +365,7 @@ std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
 constexpr int kDefaultBlock = 256;
 constexpr int kDefaultR = 4;
 constexpr int kDefaultWavesPerCU = 4;
-constexpr long long kTicketMaxBlocks = 1024;   // larger grids combine with a second launch
+constexpr long long kTicketMaxBlocks = 320;    // larger grids combine with a second launch
 
 int default_in_flight(int R)
 {

@@ -1,0 +1,122 @@
+"""GPU parity at the full sizes of the five configurations, in the launch
+configuration bench.py times (default tuning) and in the swept geometries.
+
+Acceptance: |gpu - oracle| <= 1e-5 * sum |x_i| (oracle = fp64 Kahan sum; for
+n >= 2^26 the same oracle over host threads, which the CPU tests pin to the
+exact integer sum)."""
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2001_05585_amd import binding as B            # noqa: E402
+from paper_2001_05585_amd import workloads as W          # noqa: E402
+from gpu_util import Outputs, stream_handle              # noqa: E402
+from test_golden import golden_rows                      # noqa: E402
+
+TOL = 1e-5
+THREADS = min(16, os.cpu_count() or 1)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; the HIP path has no fallback")
+    B.lib()
+
+
+def golden(cfg, n):
+    for c, _, m, s, sa in golden_rows():
+        if c == cfg and m == n:
+            return s, sa
+    return None
+
+
+def oracle_of(oracle_lib, x):
+    if x.size <= 1 << 24:
+        return oracle_lib.sum_f16(x)
+    s, sa, _ = oracle_lib.sum_f16_blocked(x, THREADS)
+    return s, sa
+
+
+def upload(x):
+    t = torch.from_numpy(x.view(np.int16)).cuda()
+    assert t.data_ptr() % 16 == 0
+    return t
+
+
+def run_all(dev, n, tunings, offset_elems=0):
+    o = Outputs(len(tunings))
+    for i, t in enumerate(tunings):
+        B.mfr_sum_f16_ex(dev.data_ptr() + 2 * offset_elems, n, o.ptr(i), t, stream_handle())
+    return o.get().astype(np.float64)
+
+
+def test_config2_every_block_R_cell_at_2p26(oracle_lib):
+    n = 1 << 26
+    x = W.generate("uniform01", n, W.config_seed(2))
+    s, sa = oracle_of(oracle_lib, x)
+    assert (s, sa) == golden(2, n) or abs(s - golden(2, n)[0]) <= 1e-9 * sa
+    dev = upload(x)
+    tunings = [B.make_tuning(block, R, grid) for block in (32, 64, 128, 256, 512, 1024)
+               for R in range(1, 9) for grid in (B.MFR_GRID_AUTO, B.MFR_GRID_ONE_CHAIN)]
+    r = run_all(dev, n, tunings)
+    err = np.abs(r - s) / sa
+    print("config 2: max |err|/sum|x| over %d cells = %.3g" % (len(tunings), err.max()))
+    assert err.max() <= TOL
+
+
+def test_config3_normal_2p28_headline(oracle_lib):
+    n = 1 << 28
+    x = W.generate("normal", n, W.config_seed(3))
+    s, sa = oracle_of(oracle_lib, x)
+    gs, gsa = golden(3, n)
+    assert abs(s - gs) <= 1e-12 * sa and abs(sa - gsa) <= 1e-12 * sa
+    dev = upload(x)
+    tunings = [None, B.make_tuning(kernel=B.MFR_KERNEL_SHFL), B.make_tuning(128, 4, B.MFR_GRID_ONE_CHAIN),
+               B.make_tuning(256, 1), B.make_tuning(1024, 8, 4096)]
+    r = run_all(dev, n, tunings)
+    err = np.abs(r - s)
+    print("config 3: gpu=%r oracle=%.6f |err|/sum|x|=%.3g |err|/|sum|=%.3g" % (r[0], s, err[0] / sa, err[0] / abs(s)))
+    assert (err / sa).max() <= TOL
+    # misaligned view of the same buffer (a slice starting at element 1)
+    s1, sa1 = oracle_of(oracle_lib, x[1:])
+    r1 = run_all(dev, n - 1, [None, B.make_tuning(kernel=B.MFR_KERNEL_SHFL)], offset_elems=1)
+    assert (np.abs(r1 - s1) / sa1).max() <= TOL
+
+
+@pytest.mark.parametrize("n", [400_000_000, 400_000_007])
+def test_config4_uniform_pm1_400M(oracle_lib, n):
+    x = W.generate("uniform_pm1", n, W.config_seed(4))
+    s, sa = oracle_of(oracle_lib, x)
+    gs, gsa = golden(4, n)
+    assert abs(s - gs) <= 1e-12 * sa and abs(sa - gsa) <= 1e-12 * sa
+    dev = upload(x)
+    r = run_all(dev, n, [None, B.make_tuning(kernel=B.MFR_KERNEL_SHFL), B.make_tuning(64, 2, 3000)])
+    err = np.abs(r - s) / sa
+    print("config 4 (n=%d): max |err|/sum|x| = %.3g" % (n, err.max()))
+    assert err.max() <= TOL
+
+
+def test_config5_size_sweep_up_to_2p30(oracle_lib):
+    nmax = (1 << 30) + 7
+    x = W.generate("uniform01", nmax, W.config_seed(5))
+    dev = upload(x)
+    sizes = [m for k in range(16, 31) for m in (1 << k, (1 << k) + 7)]
+    tunings = [None, B.make_tuning(kernel=B.MFR_KERNEL_SHFL)]
+    worst = 0.0
+    for n in sizes:
+        s, sa = oracle_of(oracle_lib, x[:n])
+        g = golden(5, n)
+        if g is not None:
+            assert abs(s - g[0]) <= 1e-12 * sa
+        r = run_all(dev, n, tunings)
+        err = (np.abs(r - s) / sa).max()
+        worst = max(worst, err)
+        assert err <= TOL, (n, r, s)
+        assert np.all(np.isfinite(r))
+    print("config 5: worst |err|/sum|x| over %d sizes x 2 kernels = %.3g" % (len(sizes), worst))
