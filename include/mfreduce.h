@@ -38,6 +38,13 @@ typedef enum mfr_status {
     MFR_ERR_HIP = 3          /* a HIP runtime call failed; text via mfr_last_hip_error() */
 } mfr_status;
 
+/* Element types.  binary16 is the paper's; the other two run the same kernels. */
+enum {
+    MFR_DTYPE_F16 = 0,  /* IEEE binary16: v_mfma_f32_16x16x32_f16, 8 values per lane per tile */
+    MFR_DTYPE_BF16 = 1, /* bfloat16: v_mfma_f32_16x16x32_bf16 */
+    MFR_DTYPE_F32 = 2   /* IEEE binary32: four v_mfma_f32_16x16x4_f32 per tile, 4 values per lane */
+};
+
 /* Which kernel computes the block partials. */
 enum {
     MFR_KERNEL_MFMA = 0, /* ones-matrix MFMA chains (Sections 4.1, 4.3, 5.2) */
@@ -109,6 +116,33 @@ int mfr_sum_f16_tuned(const mfr_half *x, size_t n, float *out,
 int mfr_sum_f16_ex(const mfr_half *x, size_t n, float *out,
                    const mfr_tuning *t, hipStream_t stream);
 
+/*
+ * The same reduction (Section 4: R(X) = sum x_i, Section 5.2 single pass) for
+ * other element types; x must be aligned to its element size.  block_threads
+ * == 32 is accepted for binary16 only.  chain_R counts tiles (1 KiB loads per
+ * wave) for every type.
+ */
+int mfr_sum_bf16(const uint16_t *x, size_t n, float *out, hipStream_t stream);
+int mfr_sum_f32(const float *x, size_t n, float *out, hipStream_t stream);
+int mfr_sum_ex(const void *x, int dtype, size_t n, float *out, const mfr_tuning *t, hipStream_t stream);
+
+/*
+ * Batched form: out[r] = sum of x[r * row_stride + c], c in [0, cols), for r in
+ * [0, rows) -- one reduction R(X_r) (Section 4) per row, each computed exactly
+ * as a single call would (Section 5.2), all rows sharing one launch when the
+ * row stride is a multiple of 16 bytes (otherwise one launch per row).
+ *   x           device pointer, aligned to the element size
+ *   row_stride  distance between rows in elements, >= cols when rows > 1
+ *   out         device pointer to rows floats
+ * rows == 0 does nothing; cols == 0 writes zeros.  With MFR_GRID_AUTO the
+ * persistent grid is divided among the rows (many short rows: one block each).
+ * grid_blocks in the tuning counts blocks per row.
+ */
+int mfr_sum_rows_ex(const void *x, int dtype, size_t rows, size_t cols, size_t row_stride, float *out,
+                    const mfr_tuning *t, hipStream_t stream);
+int mfr_sum_f16_rows(const mfr_half *x, size_t rows, size_t cols, size_t row_stride, float *out,
+                     hipStream_t stream);
+
 /* The geometry mfr_sum_f16 uses.  Any pointer may be NULL. */
 int mfr_get_default_tuning(int *block_threads, int *chain_R, int *grid_blocks);
 
@@ -130,6 +164,8 @@ long long mfr_grid_for(size_t n, size_t x_addr, const mfr_tuning *t);
  * with unchecked 128-bit loads, so all of them must lie inside [x, x + n).
  */
 int mfr_plan_for(size_t n, size_t x_addr, const mfr_tuning *t, unsigned long long plan[7]);
+/* The same for any element type (a slot holds 8 16-bit or 4 32-bit values). */
+int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *t, unsigned long long plan[7]);
 
 /* Static text for a status code. */
 const char *mfr_strerror(int status);

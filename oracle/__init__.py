@@ -58,6 +58,14 @@ def _load():
     lib.oracle_fp16_to_f64.restype = ctypes.c_double
     lib.oracle_sum_f16.argtypes = [u16p, ctypes.c_size_t, dp, dp]
     lib.oracle_sum_f16.restype = None
+    lib.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
+    lib.oracle_bf16_to_f64.restype = ctypes.c_double
+    lib.oracle_f32_bits_to_f64.argtypes = [ctypes.c_uint32]
+    lib.oracle_f32_bits_to_f64.restype = ctypes.c_double
+    lib.oracle_sum_bf16.argtypes = [u16p, ctypes.c_size_t, dp, dp]
+    lib.oracle_sum_bf16.restype = None
+    lib.oracle_sum_f32.argtypes = [ctypes.POINTER(ctypes.c_uint32), ctypes.c_size_t, dp, dp]
+    lib.oracle_sum_f32.restype = None
     lib.oracle_sum_f16_naive.argtypes = [u16p, ctypes.c_size_t, dp]
     lib.oracle_sum_f16_naive.restype = None
     lib.oracle_sum_f16_blocked.argtypes = [u16p, ctypes.c_size_t, ctypes.c_int, dp, dp]
@@ -94,6 +102,45 @@ def sum_f16(x):
     s, sa = ctypes.c_double(), ctypes.c_double()
     _load().oracle_sum_f16(_ptr(a), a.size, ctypes.byref(s), ctypes.byref(sa))
     return s.value, sa.value
+
+
+def bf16_to_f64(bits: int) -> float:
+    return float(_load().oracle_bf16_to_f64(ctypes.c_uint16(int(bits) & 0xFFFF)))
+
+
+def f32_bits_to_f64(bits: int) -> float:
+    return float(_load().oracle_f32_bits_to_f64(ctypes.c_uint32(int(bits) & 0xFFFFFFFF)))
+
+
+def sum_bf16(x):
+    """(sum, sum_abs) of bfloat16 values given as uint16 storage bits."""
+    a = np.ascontiguousarray(np.asarray(x))
+    if a.dtype != np.uint16 or a.ndim != 1:
+        raise TypeError("sum_bf16 expects a 1-D uint16 array of bfloat16 bits")
+    s, sa = ctypes.c_double(), ctypes.c_double()
+    _load().oracle_sum_bf16(_ptr(a), a.size, ctypes.byref(s), ctypes.byref(sa))
+    return s.value, sa.value
+
+
+def sum_f32(x):
+    """(sum, sum_abs) of binary32 values (float32 array or its uint32 bits)."""
+    a = np.ascontiguousarray(np.asarray(x))
+    if a.dtype == np.float32:
+        a = a.view(np.uint32)
+    if a.dtype != np.uint32 or a.ndim != 1:
+        raise TypeError("sum_f32 expects a 1-D float32 / uint32 array")
+    s, sa = ctypes.c_double(), ctypes.c_double()
+    _load().oracle_sum_f32(a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), a.size,
+                           ctypes.byref(s), ctypes.byref(sa))
+    return s.value, sa.value
+
+
+def sum_rows(x2d, dtype: str = "f16"):
+    """Per-row (sum, sum_abs) arrays of a 2-D array: one oracle call per row."""
+    fn = {"f16": sum_f16, "bf16": sum_bf16, "f32": sum_f32}[dtype]
+    a = np.asarray(x2d)
+    res = [fn(np.ascontiguousarray(a[r])) for r in range(a.shape[0])]
+    return (np.array([r[0] for r in res], dtype=np.float64), np.array([r[1] for r in res], dtype=np.float64))
 
 
 def sum_f16_naive(x) -> float:

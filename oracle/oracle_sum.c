@@ -42,13 +42,58 @@ double oracle_fp16_to_f64(uint16_t h)
     return sign ? -v : v;
 }
 
+/* bfloat16 -> binary64: 1 sign, 8 exponent (bias 127), 7 fraction bits. */
+double oracle_bf16_to_f64(uint16_t h)
+{
+    const int sign = (h >> 15) & 1;
+    const int e = (h >> 7) & 0xff;
+    const int f = h & 0x7f;
+    double v;
+    if (e == 0) {
+        v = ldexp((double)f, -133);             /* zero or subnormal: f * 2^-7 * 2^-126 */
+    } else if (e == 255) {
+        v = f ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(128 + f), e - 134);  /* (1 + f/128) * 2^(e-127) */
+    }
+    return sign ? -v : v;
+}
+
+/* binary32 -> binary64 from the bit fields: 1 sign, 8 exponent (bias 127), 23 fraction. */
+double oracle_f32_bits_to_f64(uint32_t w)
+{
+    const int sign = (int)(w >> 31);
+    const int e = (int)((w >> 23) & 0xff);
+    const uint32_t f = w & 0x7fffffu;
+    double v;
+    if (e == 0) {
+        v = ldexp((double)f, -149);
+    } else if (e == 255) {
+        v = f ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(0x800000u + f), e - 150);
+    }
+    return sign ? -v : v;
+}
+
+enum { ORACLE_F16 = 0, ORACLE_BF16 = 1, ORACLE_F32 = 2 };
+
+static double value_at(const void *x, size_t i, int dtype)
+{
+    switch (dtype) {
+    case ORACLE_BF16: return oracle_bf16_to_f64(((const uint16_t *)x)[i]);
+    case ORACLE_F32: return oracle_f32_bits_to_f64(((const uint32_t *)x)[i]);
+    default: return oracle_fp16_to_f64(((const uint16_t *)x)[i]);
+    }
+}
+
 /* Kahan-compensated serial sum of x[0..n) and plain serial sum of |x_i|.
  * sum_abs feeds the acceptance tolerance |gpu - sum| <= 1e-5 * sum_abs. */
-void oracle_sum_f16(const uint16_t *x, size_t n, double *sum, double *sum_abs)
+void oracle_sum_typed(const void *x, size_t n, int dtype, double *sum, double *sum_abs)
 {
     double s = 0.0, c = 0.0, a = 0.0, ca = 0.0, plain = 0.0;
     for (size_t i = 0; i < n; ++i) {
-        const double v = oracle_fp16_to_f64(x[i]);
+        const double v = value_at(x, i, dtype);
         plain += v;
         const double y = v - c;
         const double t = s + y;
@@ -65,6 +110,46 @@ void oracle_sum_f16(const uint16_t *x, size_t n, double *sum, double *sum_abs)
     if (!isfinite(plain)) { s = plain; a = isnan(plain) ? plain : INFINITY; }
     if (sum) *sum = s;
     if (sum_abs) *sum_abs = a;
+}
+
+void oracle_sum_f16(const uint16_t *x, size_t n, double *sum, double *sum_abs)
+{
+    oracle_sum_typed(x, n, ORACLE_F16, sum, sum_abs);
+}
+
+/* bfloat16 and binary32 span far more than 53 bits of dynamic range, where
+ * plain Kahan loses a small term that follows a huge one; the sums of those
+ * types use the Kahan-Babuska (Neumaier) form, which keeps it.  Same serial
+ * order, same definition R(X) = sum x_i. */
+static void neumaier_sum_typed(const void *x, size_t n, int dtype, double *sum, double *sum_abs)
+{
+    double s = 0.0, c = 0.0, a = 0.0, ca = 0.0, plain = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        const double v = value_at(x, i, dtype);
+        plain += v;
+        const double t = s + v;
+        if (fabs(s) >= fabs(v)) c += (s - t) + v; else c += (v - t) + s;
+        s = t;
+        const double av = fabs(v);
+        const double ta = a + av;
+        ca += (a - ta) + av;          /* a >= av >= 0 except at the start, where the other form is exact too */
+        a = ta;
+    }
+    s += c;
+    a += ca;
+    if (!isfinite(plain)) { s = plain; a = isnan(plain) ? plain : INFINITY; }
+    if (sum) *sum = s;
+    if (sum_abs) *sum_abs = a;
+}
+
+void oracle_sum_bf16(const uint16_t *x, size_t n, double *sum, double *sum_abs)
+{
+    neumaier_sum_typed(x, n, ORACLE_BF16, sum, sum_abs);
+}
+
+void oracle_sum_f32(const uint32_t *x, size_t n, double *sum, double *sum_abs)
+{
+    neumaier_sum_typed(x, n, ORACLE_F32, sum, sum_abs);
 }
 
 /* Uncompensated serial binary64 sum: literally the paper's CPU comparison

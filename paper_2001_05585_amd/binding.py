@@ -18,8 +18,11 @@ MFR_KERNEL_MFMA, MFR_KERNEL_SHFL = 0, 1
 MFR_GRID_AUTO, MFR_GRID_ONE_CHAIN = 0, -1
 MFR_COMBINE_AUTO, MFR_COMBINE_SINGLE_LAUNCH, MFR_COMBINE_TWO_LAUNCHES = 0, 1, 2
 
-EXPORTS = ("mfr_sum_f16", "mfr_sum_f16_tuned", "mfr_sum_f16_ex", "mfr_get_default_tuning",
-           "mfr_grid_for", "mfr_plan_for", "mfr_strerror", "mfr_last_hip_error", "mfr_version")
+MFR_DTYPE_F16, MFR_DTYPE_BF16, MFR_DTYPE_F32 = 0, 1, 2
+
+EXPORTS = ("mfr_sum_f16", "mfr_sum_f16_tuned", "mfr_sum_f16_ex", "mfr_sum_bf16", "mfr_sum_f32", "mfr_sum_ex",
+           "mfr_sum_rows_ex", "mfr_sum_f16_rows", "mfr_get_default_tuning", "mfr_grid_for", "mfr_plan_for",
+           "mfr_plan_ex", "mfr_strerror", "mfr_last_hip_error", "mfr_version")
 
 
 class mfr_tuning(ctypes.Structure):
@@ -56,6 +59,18 @@ def lib() -> ctypes.CDLL:
     L.mfr_sum_f16_tuned.restype = ci
     L.mfr_sum_f16_ex.argtypes = [vp, sz, vp, ctypes.POINTER(mfr_tuning), vp]
     L.mfr_sum_f16_ex.restype = ci
+    L.mfr_sum_bf16.argtypes = [vp, sz, vp, vp]
+    L.mfr_sum_bf16.restype = ci
+    L.mfr_sum_f32.argtypes = [vp, sz, vp, vp]
+    L.mfr_sum_f32.restype = ci
+    L.mfr_sum_ex.argtypes = [vp, ci, sz, vp, ctypes.POINTER(mfr_tuning), vp]
+    L.mfr_sum_ex.restype = ci
+    L.mfr_sum_rows_ex.argtypes = [vp, ci, sz, sz, sz, vp, ctypes.POINTER(mfr_tuning), vp]
+    L.mfr_sum_rows_ex.restype = ci
+    L.mfr_sum_f16_rows.argtypes = [vp, sz, sz, sz, vp, vp]
+    L.mfr_sum_f16_rows.restype = ci
+    L.mfr_plan_ex.argtypes = [sz, sz, ci, ctypes.POINTER(mfr_tuning), ctypes.POINTER(ctypes.c_ulonglong)]
+    L.mfr_plan_ex.restype = ci
     ip = ctypes.POINTER(ci)
     L.mfr_get_default_tuning.argtypes = [ip, ip, ip]
     L.mfr_get_default_tuning.restype = ci
@@ -98,6 +113,36 @@ def make_tuning(block_threads=0, chain_R=0, grid_blocks=0, kernel=0, chains_in_f
 def mfr_sum_f16_ex(x: int, n: int, out: int, t: mfr_tuning | None = None, stream: int = 0) -> None:
     tp = ctypes.byref(t) if t is not None else None
     _check(lib().mfr_sum_f16_ex(x, n, out, tp, stream), "mfr_sum_f16_ex")
+
+
+def mfr_sum_bf16(x: int, n: int, out: int, stream: int = 0) -> None:
+    _check(lib().mfr_sum_bf16(x, n, out, stream), "mfr_sum_bf16")
+
+
+def mfr_sum_f32(x: int, n: int, out: int, stream: int = 0) -> None:
+    _check(lib().mfr_sum_f32(x, n, out, stream), "mfr_sum_f32")
+
+
+def mfr_sum_ex(x: int, dtype: int, n: int, out: int, t: mfr_tuning | None = None, stream: int = 0) -> None:
+    tp = ctypes.byref(t) if t is not None else None
+    _check(lib().mfr_sum_ex(x, dtype, n, out, tp, stream), "mfr_sum_ex")
+
+
+def mfr_sum_rows_ex(x: int, dtype: int, rows: int, cols: int, row_stride: int, out: int,
+                    t: mfr_tuning | None = None, stream: int = 0) -> None:
+    tp = ctypes.byref(t) if t is not None else None
+    _check(lib().mfr_sum_rows_ex(x, dtype, rows, cols, row_stride, out, tp, stream), "mfr_sum_rows_ex")
+
+
+def mfr_sum_f16_rows(x: int, rows: int, cols: int, row_stride: int, out: int, stream: int = 0) -> None:
+    _check(lib().mfr_sum_f16_rows(x, rows, cols, row_stride, out, stream), "mfr_sum_f16_rows")
+
+
+def mfr_plan_ex(n: int, x_addr: int, dtype: int, t: mfr_tuning | None = None):
+    plan = (ctypes.c_ulonglong * 7)()
+    tp = ctypes.byref(t) if t is not None else None
+    _check(lib().mfr_plan_ex(n, x_addr, dtype, tp, plan), "mfr_plan_ex")
+    return tuple(int(v) for v in plan)
 
 
 def mfr_get_default_tuning():

@@ -7,12 +7,14 @@ import sys
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SOURCES = [os.path.join(_HERE, "csrc", "mfreduce.hip")]
+CSRC = os.path.join(_HERE, "csrc")
+SOURCES = [os.path.join(CSRC, f) for f in ("mfreduce.hip", "launch_f16.hip", "launch_bf16.hip", "launch_f32.hip")]
+BUILD_DIR = os.path.join(_HERE, "_build")
 INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "libmfreduce.so")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Wall", "-Wextra",
     # no packed-fp32 VALU forms
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -26,9 +28,22 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+def _compile(src: str, obj: str, verbose: bool, extra_flags) -> None:
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, "-I", CSRC, "-c", src, "-o", obj]
+    if verbose:
+        print(" ".join(cmd), file=sys.stderr)
+    subprocess.run(cmd, check=True)
+
+
 def build(verbose: bool = False, extra_flags=()) -> str:
+    """Compile every translation unit (in parallel) and link libmfreduce.so."""
+    from concurrent.futures import ThreadPoolExecutor
+    os.makedirs(BUILD_DIR, exist_ok=True)
+    objs = [os.path.join(BUILD_DIR, os.path.basename(s)[:-4] + ".o") for s in SOURCES]
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as ex:
+        list(ex.map(lambda so: _compile(so[0], so[1], verbose, extra_flags), zip(SOURCES, objs)))
     tmp = LIB_PATH + ".tmp%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, "-o", tmp, *SOURCES]
+    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     if verbose:
         print(" ".join(cmd), file=sys.stderr)
     subprocess.run(cmd, check=True)

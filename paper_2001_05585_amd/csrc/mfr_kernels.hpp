@@ -1,0 +1,435 @@
+// Device code of libmfreduce (gfx950): the single-pass reduction of paper
+// Section 5.2 in three levels.
+//   1. every wavefront runs chains of R MFMAs  C_r = 1 x M_r + C_{r-1}
+//      (Section 4.3) with an fp32 accumulator, and folds each finished chain
+//      to one fp32 partial;
+//   2. the waves of a block combine their partials through LDS;
+//   3. block partials go to a scratch array; the block that draws the last
+//      ticket adds them in index order and writes the result, or a second
+//      one-block launch does (the paper adds them with float atomics, whose
+//      order varies from run to run).
+// A conventional kernel (per-lane fp32 accumulation + wave shuffle tree, the
+// comparison kernel of Section 5.4) shares levels 2 and 3.
+//
+// Memory view.  The input is addressed in 16-byte "slots" counted from x
+// rounded down to a 16-byte boundary.  Slot 0 may start before x (head
+// padding) and the last slot may end after x + n; those two are read
+// element-wise under a range check, padding contributes +0 (the border
+// handling Section 4.1 leaves to the implementation).  All other slots are
+// read with one 128-bit load per lane, 64 lanes = 1 KiB contiguous per load
+// instruction = one tile.  Any assignment of elements to matrix positions
+// yields the same total, so the layout is chosen for coalescing alone.
+//
+// Element types: binary16 (the paper's), bfloat16 and binary32.  A tile is one
+// 16x16x32 MFMA for the 16-bit types (8 values per lane) and four 16x16x4
+// MFMAs for binary32 (4 values per lane, one per MFMA).
+#ifndef MFR_KERNELS_HPP
+#define MFR_KERNELS_HPP
+
+#include <hip/hip_runtime.h>
+
+#include "mfreduce.h"
+
+namespace mfr {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxWavesPerBlock = 16;
+
+struct SumArgs {
+    const uint4v *base;          // x rounded down to 16 bytes: slot 0 (of row 0)
+    const void *x;               // first element (of row 0)
+    unsigned long long n;        // elements per row
+    unsigned long long vend;     // head + n: end of the valid range in slot-relative elements
+    unsigned long long main0;    // first slot of the unmasked main region
+    unsigned long long chains;   // number of full chains in the main region
+    unsigned long long epi0;     // border positions [epi0, epi1)
+    unsigned long long epi1;
+    unsigned long long slots;    // total slots covering [x, x + n)
+    unsigned long long row_slots;  // distance between rows in slots (rows share the 16-byte phase)
+    unsigned int head;           // elements of slot 0 that lie before x
+    float *partials;             // gridDim.x per row
+    unsigned int *ticket;        // one per row; nullptr = two-launch combine
+    float *out;                  // one per row
+};
+
+struct Plan {
+    SumArgs a;
+    int threads;                 // launched threads per block (>= 64)
+    int waves;                   // waves per block
+    bool half;                   // 32-thread geometry
+    unsigned long long chains;
+};
+
+template <int DT> struct ElemTraits;
+template <> struct ElemTraits<MFR_DTYPE_F16> { static constexpr unsigned per_slot = 8; typedef unsigned short storage; };
+template <> struct ElemTraits<MFR_DTYPE_BF16> { static constexpr unsigned per_slot = 8; typedef unsigned short storage; };
+template <> struct ElemTraits<MFR_DTYPE_F32> { static constexpr unsigned per_slot = 4; typedef unsigned int storage; };
+
+// ---------------------------------------------------------------- loads ---
+
+template <bool NT>
+__device__ __forceinline__ uint4v load_slot(const uint4v *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+// Slot q with every element range-checked against [x, x + n).  A slot that
+// lies wholly inside is one 128-bit load; a straddling slot is read with
+// independent element loads whose indices are clamped into range, so that all
+// of them are in flight together, and out-of-range elements are replaced by +0.
+template <int DT>
+__device__ __forceinline__ uint4v load_slot_guarded(const SumArgs &a, const uint4v *base, const void *x,
+                                                    unsigned long long q, bool active)
+{
+    constexpr unsigned E = ElemTraits<DT>::per_slot;
+    typedef typename ElemTraits<DT>::storage storage;
+    const unsigned long long v0 = q * E;
+    const bool full = active && v0 >= a.head && v0 + E <= a.vend;
+    uint4v r = {0u, 0u, 0u, 0u};
+    if (full) r = base[q];
+    if (active && !full) {
+        unsigned int h[E];
+#pragma unroll
+        for (unsigned k = 0; k < E; ++k) {
+            const unsigned long long v = v0 + k;
+            const bool ok = v >= a.head && v < a.vend;
+            const unsigned int t = ((const storage *)x)[ok ? v - a.head : 0ull];   // n >= 1: x[0] is readable
+            h[k] = ok ? t : 0u;
+        }
+        if constexpr (E == 8) {
+            r.x = h[0] | (h[1] << 16);
+            r.y = h[2] | (h[3] << 16);
+            r.z = h[4] | (h[5] << 16);
+            r.w = h[6] | (h[7] << 16);
+        } else {
+            r.x = h[0]; r.y = h[1]; r.z = h[2]; r.w = h[3];
+        }
+    }
+    return r;
+}
+
+// Border position p -> slot: positions past the last slot stand for slot 0
+// (the head slot is skipped by the main region and picked up here); positions
+// at or past epi1 yield zeros.
+template <int DT>
+__device__ __forceinline__ uint4v load_epilogue(const SumArgs &a, const uint4v *base, const void *x,
+                                                unsigned long long p, bool carries)
+{
+    return load_slot_guarded<DT>(a, base, x, p < a.slots ? p : 0ull, carries && p < a.epi1);
+}
+
+// ------------------------------------------------------- lane exchanges ---
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+    return v + __int_as_float(t);
+}
+
+// Sum over each row of 16 lanes, result in every lane of the row.
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);   // row_half_mirror
+    v = dpp_add<0x140>(v);   // row_mirror
+    return v;
+}
+
+// Sum over the 64 lanes, wave-uniform.
+__device__ __forceinline__ float wave64_sum(float v)
+{
+    v = row16_sum(v);
+    const float a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float b = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float c = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (a + b) + (c + d);
+}
+
+__device__ __forceinline__ double wave64_sum_f64(double v)
+{
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+// All threads of one block: sum of partials[0..count) in binary64, fixed order
+// (thread t takes t, t + blockDim, ... with four running sums, then lanes, then
+// waves).  Loads are device-scope atomic loads so that values published by
+// other compute dies are observed.  Result valid in thread 0.
+__device__ __forceinline__ double block_sum_f64(const float *partials, unsigned int count, double *lds)
+{
+    const unsigned int lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, wpb = (blockDim.x + 63u) >> 6;
+    double t0 = 0.0, t1 = 0.0, t2 = 0.0, t3 = 0.0;
+    const unsigned int step = blockDim.x;
+    unsigned int i = threadIdx.x;
+    for (; i + 3u * step < count; i += 4u * step) {
+        const float p0 = __hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float p1 = __hip_atomic_load(&partials[i + step], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float p2 = __hip_atomic_load(&partials[i + 2u * step], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float p3 = __hip_atomic_load(&partials[i + 3u * step], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t0 += (double)p0; t1 += (double)p1; t2 += (double)p2; t3 += (double)p3;
+    }
+    for (; i < count; i += step)
+        t0 += (double)__hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    double t = wave64_sum_f64((t0 + t1) + (t2 + t3));
+    if (lane == 0) lds[wave] = t;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0)
+        for (unsigned int w = 0; w < wpb; ++w) total += lds[w];
+    return total;
+}
+
+// ------------------------------------------------------ tile consumers ---
+
+// One tile of the chain: C = 1 x M + C  (Section 4.3).  A is the all-ones
+// operand, B the data tile; every row of C then holds the 16 column sums, i.e.
+// lane l holds column (l mod 16) in each of its 4 accumulator registers.
+template <int DT>
+__device__ __forceinline__ float4v mma_ones(uint4v tile, float4v c)
+{
+    if constexpr (DT == MFR_DTYPE_F16) {
+        const _Float16 one = (_Float16)1.0f;
+        const half8 ones = {one, one, one, one, one, one, one, one};
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, __builtin_bit_cast(half8, tile), c, 0, 0, 0);
+    } else if constexpr (DT == MFR_DTYPE_BF16) {
+        const __bf16 one = (__bf16)1.0f;
+        const bf16x8 ones = {one, one, one, one, one, one, one, one};
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, __builtin_bit_cast(bf16x8, tile), c, 0, 0, 0);
+    } else {
+        // binary32: B is 4x16, one value per lane per MFMA; the lane's four values go to four MFMAs
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(tile.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(tile.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(tile.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(tile.w), c, 0, 0, 0);
+        return c;
+    }
+}
+
+// Chain total from the accumulator: the 16 distinct column sums sit in one
+// register across the 16 lanes of a row (all rows and registers are copies),
+// so an fp32 row fold replaces the final "x ones" MMA and keeps the chain
+// result in fp32 (the accumulator is never rounded to a 16-bit type).
+__device__ __forceinline__ float chain_total(float4v c)
+{
+    return row16_sum(c.x);
+}
+
+// Conventional path: fp32 sum of the values of one slot.
+template <int DT>
+__device__ __forceinline__ float slot_sum_f32(uint4v s)
+{
+    if constexpr (DT == MFR_DTYPE_F16) {
+        const half8 h = __builtin_bit_cast(half8, s);
+        return (((float)h[0] + (float)h[1]) + ((float)h[2] + (float)h[3])) +
+               (((float)h[4] + (float)h[5]) + ((float)h[6] + (float)h[7]));
+    } else if constexpr (DT == MFR_DTYPE_BF16) {
+        // bfloat16 is the upper half of a binary32
+        const float f0 = __uint_as_float(s.x << 16), f1 = __uint_as_float(s.x & 0xffff0000u);
+        const float f2 = __uint_as_float(s.y << 16), f3 = __uint_as_float(s.y & 0xffff0000u);
+        const float f4 = __uint_as_float(s.z << 16), f5 = __uint_as_float(s.z & 0xffff0000u);
+        const float f6 = __uint_as_float(s.w << 16), f7 = __uint_as_float(s.w & 0xffff0000u);
+        return ((f0 + f1) + (f2 + f3)) + ((f4 + f5) + (f6 + f7));
+    } else {
+        return (__uint_as_float(s.x) + __uint_as_float(s.y)) + (__uint_as_float(s.z) + __uint_as_float(s.w));
+    }
+}
+
+// One chain of R tiles to one fp32 value.  MFMA path: the chain total, uniform
+// over the wave.  Conventional path: this lane's share of it.
+template <int KERNEL, int DT, int R>
+__device__ __forceinline__ float consume_chain(const uint4v (&v)[R])
+{
+    if constexpr (KERNEL == MFR_KERNEL_MFMA) {
+        float4v acc = {0.f, 0.f, 0.f, 0.f};                 // C_0 = 0
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc = mma_ones<DT>(v[r], acc);
+        return chain_total(acc);
+    } else {
+        float s = 0.f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) s += slot_sum_f32<DT>(v[r]);
+        return s;
+    }
+}
+
+// ------------------------------------------------------------- kernels ---
+
+// KERNEL: MFR_KERNEL_MFMA or MFR_KERNEL_SHFL.  DT: element type.  R: chain
+// length in tiles.  U: chains in flight.  NT: non-temporal loads.  HALF: only
+// lanes 0..31 carry data (the "32-thread block" geometry on a wave64 machine),
+// a tile is then 32 slots.  blockIdx.y selects the row of a batched call.
+template <int KERNEL, int DT, int R, int U, bool NT, bool HALF>
+__global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
+{
+    constexpr unsigned TS = HALF ? 32u : 64u;          // slots per tile
+    const unsigned lane = threadIdx.x & 63u;
+    const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform
+    const unsigned wpb = (blockDim.x + 63u) >> 6;
+    const unsigned long long W = (unsigned long long)gridDim.x * wpb;
+    const unsigned long long w = (unsigned long long)blockIdx.x * wpb + wave;
+    const bool carries = !HALF || lane < 32u;
+    const uint4v zero4 = {0u, 0u, 0u, 0u};
+
+    const unsigned long long row = blockIdx.y;
+    const uint4v *base = a.base + row * a.row_slots;
+    const void *x = (const char *)a.x + row * a.row_slots * 16ull;
+
+    // MFMA path: `partial` is the wave's running sum of chain totals (uniform).
+    // SHFL path: `partial` is this lane's running fp32 sum.
+    float partial = 0.f;
+    const uint4v *lane_base = base + a.main0 + (carries ? lane : 0u);
+
+    unsigned long long c = w;
+    if constexpr (U > 1) {
+        for (; c + (unsigned long long)(U - 1) * W < a.chains; c += (unsigned long long)U * W) {
+            uint4v v[U][R];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const uint4v *p = lane_base + ((c + (unsigned long long)u * W) * R + r) * TS;
+                    v[u][r] = carries ? load_slot<NT>(p) : zero4;
+                }
+            // all U * R loads are issued before the first is consumed
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < U; ++u) partial += consume_chain<KERNEL, DT, R>(v[u]);
+        }
+    }
+    for (; c < a.chains; c += W) {
+        uint4v v[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint4v *p = lane_base + (c * R + r) * TS;
+            v[r] = carries ? load_slot<NT>(p) : zero4;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        partial += consume_chain<KERNEL, DT, R>(v);
+    }
+
+    // Border: leftover whole tiles (fewer than R), leftover slots, the partial
+    // last slot and the head slot, as masked tiles in chains of R (at most two
+    // chains; tiles past the end are all zeros).
+    if (w == W - 1) {
+        for (unsigned long long p0 = a.epi0; p0 < a.epi1; p0 += (unsigned long long)R * TS) {
+            uint4v v[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                v[r] = load_epilogue<DT>(a, base, x, p0 + (unsigned long long)r * TS + lane, carries);
+            partial += consume_chain<KERNEL, DT, R>(v);
+        }
+    }
+
+    if constexpr (KERNEL == MFR_KERNEL_SHFL) partial = wave64_sum(partial);
+
+    // Level 2: one value per block from its wave partials.
+    __shared__ float wave_partials[kMaxWavesPerBlock];
+    __shared__ double wave_partials_f64[kMaxWavesPerBlock];
+    __shared__ unsigned int is_last;
+    if (lane == 0) wave_partials[wave] = partial;
+    __syncthreads();
+    float block_sum = 0.f;
+    if (wave == 0) {
+        const float t = lane < wpb ? wave_partials[lane] : 0.f;
+        block_sum = row16_sum(t);      // wpb <= 16: all partials sit in row 0
+    }
+
+    // Level 3: all block partials of the row to one value, in index order.
+    float *out = a.out + row;
+    if (gridDim.x == 1) {
+        if (threadIdx.x == 0) *out = block_sum;
+        return;
+    }
+    float *partials = a.partials + row * gridDim.x;
+    if (a.ticket == nullptr) {
+        // two-launch combine: the partial is picked up by combine_kernel
+        if (threadIdx.x == 0) partials[blockIdx.x] = block_sum;
+        return;
+    }
+    // Single-launch combine.  A release fence at device scope costs a write-back
+    // of the whole L2 per block, so ordering is obtained from the atomics
+    // themselves: the partial is published with a returning device-scope
+    // exchange, and the ticket is drawn only after that exchange has returned,
+    // i.e. after it has been performed at the device's coherence point.  The
+    // block that draws the last ticket therefore finds every partial there.
+    if (threadIdx.x == 0) {
+        unsigned int prev = __hip_atomic_exchange((unsigned int *)&partials[blockIdx.x],
+                                                  __float_as_uint(block_sum), __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+        // the exchange result must be in a register (waits for it) and no later
+        // memory operation may be moved above this point
+        asm volatile("" : "+v"(prev) : : "memory");
+        // wraps to 0 after the last block, so the counter is ready for the next call
+        const unsigned int old = atomicInc(a.ticket + row, gridDim.x - 1u);
+        is_last = (old == gridDim.x - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!is_last) return;
+    const double total = block_sum_f64(partials, gridDim.x, wave_partials_f64);
+    if (threadIdx.x == 0) *out = (float)total;
+}
+
+// ------------------------------------------------------------ launching ---
+
+template <int KERNEL, int DT, int R, int U>
+hipError_t launch_ru(const Plan &p, dim3 grid, bool nt, hipStream_t stream)
+{
+    const dim3 b((unsigned)p.threads);
+    if (p.half) {
+        if constexpr (DT == MFR_DTYPE_F16) {
+            if (nt) hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, true, true>), grid, b, 0, stream, p.a);
+            else hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, false, true>), grid, b, 0, stream, p.a);
+        } else {
+            return hipErrorInvalidValue;   // the 32-thread geometry exists for the paper's type only
+        }
+    } else {
+        if (nt) hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, true, false>), grid, b, 0, stream, p.a);
+        else hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, false, false>), grid, b, 0, stream, p.a);
+    }
+    return hipGetLastError();
+}
+
+template <int KERNEL, int DT>
+hipError_t launch_k(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream)
+{
+    const bool nt = t.nontemporal == 2;
+#define MFR_CASE(R_, U_) \
+    case (R_) * 16 + (U_): return launch_ru<KERNEL, DT, R_, U_>(p, grid, nt, stream);
+    switch (t.chain_R * 16 + t.chains_in_flight) {
+        MFR_CASE(1, 1) MFR_CASE(1, 2) MFR_CASE(1, 4) MFR_CASE(1, 8)
+        MFR_CASE(2, 1) MFR_CASE(2, 2) MFR_CASE(2, 4) MFR_CASE(2, 8)
+        MFR_CASE(3, 1) MFR_CASE(3, 2) MFR_CASE(3, 4)
+        MFR_CASE(4, 1) MFR_CASE(4, 2) MFR_CASE(4, 4)
+        MFR_CASE(5, 1) MFR_CASE(5, 2)
+        MFR_CASE(6, 1) MFR_CASE(6, 2)
+        MFR_CASE(7, 1) MFR_CASE(7, 2)
+        MFR_CASE(8, 1) MFR_CASE(8, 2)
+    default: return hipErrorInvalidValue;
+    }
+#undef MFR_CASE
+}
+
+template <int DT>
+hipError_t launch_sum(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream)
+{
+    return t.kernel == MFR_KERNEL_MFMA ? launch_k<MFR_KERNEL_MFMA, DT>(p, grid, t, stream)
+                                       : launch_k<MFR_KERNEL_SHFL, DT>(p, grid, t, stream);
+}
+
+// one translation unit per element type (they compile in parallel)
+hipError_t launch_sum_f16(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
+hipError_t launch_sum_bf16(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
+hipError_t launch_sum_f32(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
+
+}  // namespace mfr
+
+#endif  // MFR_KERNELS_HPP

@@ -108,6 +108,48 @@ def generate(kind: str, n: int, seed: int, offset: int = 0, out: np.ndarray | No
     return out
 
 
+def to_bf16_bits(v: np.ndarray) -> np.ndarray:
+    """float -> bfloat16 storage bits (uint16), round to nearest even; NaN stays NaN."""
+    w = np.ascontiguousarray(v, dtype=np.float32).view(np.uint32)
+    bias = np.uint32(0x7FFF) + ((w >> np.uint32(16)) & np.uint32(1))
+    with np.errstate(over="ignore"):
+        r = ((w + bias) >> np.uint32(16)).astype(np.uint16)
+    nan = np.isnan(np.asarray(v, dtype=np.float32))
+    if nan.any():
+        r[nan] = np.uint16(0x7FC0)
+    return r
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def generate_f32(kind: str, n: int, seed: int, offset: int = 0) -> np.ndarray:
+    """float32 array of the same streams (values rounded to binary32 instead of binary16)."""
+    out = np.empty(n, dtype=np.float32)
+    for a in range(0, n, _CHUNK):
+        b = min(a + _CHUNK, n)
+        lo, hi = offset + a, offset + b
+        if kind == "uniform01":
+            out[a:b] = np.minimum(_unit(seed, lo, hi).astype(np.float32), np.float32(1.0 - 2.0 ** -24))
+        elif kind == "uniform_pm1":
+            out[a:b] = np.minimum((2.0 * _unit(seed, lo, hi) - 1.0).astype(np.float32), np.float32(1.0 - 2.0 ** -24))
+        elif kind == "normal":
+            u = _unit(seed ^ 0x5851F42D4C957F2D, 2 * lo, 2 * hi)
+            out[a:b] = (np.sqrt(-2.0 * np.log(1.0 - u[0::2])) * np.cos(2.0 * np.pi * u[1::2])).astype(np.float32)
+        else:
+            raise KeyError(kind)
+    return out
+
+
+def generate_bf16(kind: str, n: int, seed: int, offset: int = 0) -> np.ndarray:
+    """bfloat16 storage bits (uint16) of the same streams."""
+    bits = to_bf16_bits(generate_f32(kind, n, seed, offset))
+    if kind in ("uniform01", "uniform_pm1"):
+        bits[bits == 0x3F80] = 0x3F7F          # a rounded-up 1.0 -> largest bfloat16 below 1
+    return bits
+
+
 # --- closed-form patterns (all values are small integers, hence fp16-exact) ---
 
 def ones(n: int) -> np.ndarray:

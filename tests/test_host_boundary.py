@@ -63,16 +63,20 @@ def test_invalid_arguments_are_rejected_before_any_hip_call():
         B.mfr_sum_f16(0, 5, 4096)
 
 
-def simulate_coverage(n, x_addr, t):
-    head, slots, main0, chains, ts, epi0, epi1 = B.mfr_plan_for(n, x_addr, t)
+def simulate_coverage(n, x_addr, t, dtype=0):
+    head, slots, main0, chains, ts, epi0, epi1 = B.mfr_plan_ex(n, x_addr, dtype, t)
+    if dtype == 0:
+        assert (head, slots, main0, chains, ts, epi0, epi1) == B.mfr_plan_for(n, x_addr, t)
+    esize = 4 if dtype == B.MFR_DTYPE_F32 else 2
+    per_slot = 16 // esize
     R = t.chain_R
     vend = head + n
-    assert head == (x_addr % 16) // 2
-    assert slots == -(-vend // 8)
+    assert head == (x_addr % 16) // esize
+    assert slots == -(-vend // per_slot)
     count = [0] * slots
     main_end = main0 + chains * R * ts
     for q in range(main0, main_end):
-        assert 8 * q >= head and 8 * q + 8 <= vend, "unchecked load outside [x, x+n)"
+        assert per_slot * q >= head and per_slot * (q + 1) <= vend, "unchecked load outside [x, x+n)"
         count[q] += 1
     assert epi0 <= epi1
     assert epi1 - epi0 <= (R + 1) * ts, "border must fit in two masked chains"
@@ -93,6 +97,38 @@ def test_every_slot_is_covered_exactly_once(block, R):
     for n in sorted(v for v in ns if v >= 1):
         for shift in range(8):
             simulate_coverage(n, 4096 + 2 * shift, t)
+
+
+@pytest.mark.parametrize("dtype", [B.MFR_DTYPE_BF16, B.MFR_DTYPE_F32])
+def test_every_slot_is_covered_exactly_once_other_types(dtype):
+    esize = 4 if dtype == B.MFR_DTYPE_F32 else 2
+    for R in (1, 4):
+        t = B.make_tuning(256, R)
+        edge = (16 // esize) * 64 * R
+        ns = set(range(1, 20)) | {edge + d for d in range(-5, 6)} | {2 * edge + d for d in range(-5, 6)} | {100003}
+        for n in sorted(ns):
+            for shift in range(16 // esize):
+                simulate_coverage(n, 4096 + esize * shift, t, dtype)
+    # the 32-thread geometry exists for binary16 only; unknown types are rejected
+    plan = (ctypes.c_ulonglong * 7)()
+    t32 = B.make_tuning(32, 1)
+    assert B.lib().mfr_plan_ex(100, 4096, dtype, ctypes.byref(t32), plan) == B.MFR_ERR_INVALID_ARG
+    assert B.lib().mfr_plan_ex(100, 4096, 7, None, plan) == B.MFR_ERR_INVALID_ARG
+
+
+def test_typed_and_batched_entries_reject_bad_arguments():
+    L = B.lib()
+    INV = B.MFR_ERR_INVALID_ARG
+    assert L.mfr_sum_f32(4098, 5, 4096, None) == INV             # not 4-byte aligned
+    assert L.mfr_sum_bf16(4097, 5, 4096, None) == INV
+    assert L.mfr_sum_ex(4096, 3, 5, 4096, None, None) == INV     # unknown element type
+    assert L.mfr_sum_ex(4096, -1, 5, 4096, None, None) == INV
+    assert L.mfr_sum_f32(None, 5, 4096, None) == INV
+    assert L.mfr_sum_rows_ex(4096, 0, 4, 100, 99, 4096, None, None) == INV   # stride < cols
+    assert L.mfr_sum_rows_ex(None, 0, 4, 100, 100, 4096, None, None) == INV
+    assert L.mfr_sum_rows_ex(4096, 0, 4, 100, 100, None, None, None) == INV
+    assert L.mfr_sum_rows_ex(4096, 0, 0, 100, 100, 4096, None, None) == B.MFR_OK   # no rows: nothing to do
+    assert L.mfr_sum_f16_rows(4097, 2, 8, 8, 4096, None) == INV
 
 
 def test_grid_for_one_chain_geometry():

@@ -237,3 +237,69 @@ def test_blocked_special_values(oracle_lib):
     assert math.isnan(oracle_lib.sum_f16_blocked(x, 4)[0])
     assert oracle_lib.sum_f16_blocked(W.ones(0), 4)[:2] == (0.0, 0.0)
     assert oracle_lib.sum_f16_blocked(W.ones(3), 8)[:2] == (3.0, 3.0)
+
+
+# ------------------------------------------- bfloat16 and binary32 inputs ---
+
+def test_bf16_decoder_matches_bit_shift_for_every_code(oracle_lib):
+    codes = np.arange(65536, dtype=np.uint16)
+    ref = W.bf16_bits_to_f32(codes).astype(np.float64)     # bfloat16 = upper half of a binary32
+    for c in range(65536):
+        got = oracle_lib.bf16_to_f64(c)
+        if math.isnan(ref[c]):
+            assert math.isnan(got), hex(c)
+        else:
+            assert got == ref[c] and math.copysign(1.0, got) == math.copysign(1.0, ref[c]), hex(c)
+    assert oracle_lib.bf16_to_f64(0x3F80) == 1.0 and oracle_lib.bf16_to_f64(0x0001) == 2.0 ** -133
+    assert oracle_lib.bf16_to_f64(0x7F7F) == (2.0 - 2.0 ** -7) * 2.0 ** 127
+
+
+def test_f32_decoder_matches_numpy(oracle_lib):
+    rng = np.random.default_rng(8)
+    codes = np.concatenate([rng.integers(0, 1 << 32, size=200000, dtype=np.uint64).astype(np.uint32),
+                            np.array([0, 1, 0x007FFFFF, 0x00800000, 0x3F800000, 0x7F7FFFFF, 0x7F800000,
+                                      0xFF800000, 0x7FC00000, 0x80000000, 0x80000001], dtype=np.uint32)])
+    ref = codes.view(np.float32).astype(np.float64)
+    for c, r in zip(codes.tolist(), ref.tolist()):
+        got = oracle_lib.f32_bits_to_f64(c)
+        assert (math.isnan(got) and math.isnan(r)) or (got == r and math.copysign(1.0, got) == math.copysign(1.0, r)), hex(c)
+
+
+@pytest.mark.parametrize("kind", ["uniform01", "uniform_pm1", "normal"])
+def test_bf16_and_f32_sums_against_fsum(oracle_lib, kind):
+    for n in (0, 1, 5, 1000, 70001):
+        b = W.generate_bf16(kind, n, seed=300 + n)
+        vals = W.bf16_bits_to_f32(b).astype(np.float64).tolist()
+        want, want_abs = math.fsum(vals), math.fsum(abs(v) for v in vals)
+        s, a = oracle_lib.sum_bf16(b)
+        assert abs(s - want) <= 2 * ulp64(want) and abs(a - want_abs) <= 2 * ulp64(want_abs)
+        f = W.generate_f32(kind, n, seed=400 + n)
+        vals = f.astype(np.float64).tolist()
+        want, want_abs = math.fsum(vals), math.fsum(abs(v) for v in vals)
+        s, a = oracle_lib.sum_f32(f)
+        assert abs(s - want) <= 2 * ulp64(want) and abs(a - want_abs) <= 2 * ulp64(want_abs)
+
+
+def test_bf16_and_f32_closed_forms(oracle_lib):
+    for n in (1, 511, 4096, 100003):
+        ones_b = np.full(n, 0x3F80, dtype=np.uint16)
+        assert oracle_lib.sum_bf16(ones_b) == (float(n), float(n))
+        assert oracle_lib.sum_f32(np.full(n, -2.5, dtype=np.float32)) == (-2.5 * n, 2.5 * n)
+        alt = np.full(n, 0x4040, dtype=np.uint16)          # 3.0
+        alt[1::2] |= 0x8000
+        assert oracle_lib.sum_bf16(alt)[0] == (3.0 if n % 2 else 0.0)
+    ramp = np.arange(1 << 20, dtype=np.float32)            # exact in binary32 below 2^24
+    assert oracle_lib.sum_f32(ramp)[0] == float((1 << 20) * ((1 << 20) - 1) // 2)
+    # wide dynamic range: the small term must survive the cancellation of the huge ones
+    wide = np.array([2.0 ** 100, 1.0, -(2.0 ** 100)], dtype=np.float32)
+    assert oracle_lib.sum_f32(wide)[0] == 1.0
+    inf = np.array([1.0, np.inf, 2.0], dtype=np.float32)
+    assert oracle_lib.sum_f32(inf)[0] == math.inf
+    assert math.isnan(oracle_lib.sum_f32(np.array([np.inf, -np.inf], dtype=np.float32))[0])
+
+
+def test_rows_helper_is_the_per_row_oracle(oracle_lib):
+    x = W.small_integers(12 * 37, seed=5).reshape(12, 37)
+    s, sa = oracle_lib.sum_rows(x)
+    assert np.array_equal(s, x.astype(np.float64).sum(axis=1))
+    assert np.array_equal(sa, np.abs(x.astype(np.float64)).sum(axis=1))
