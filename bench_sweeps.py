@@ -181,6 +181,101 @@ def config5(args, torch, np, B, W):
                                                             n / dt / 1e9, 2 * n / dt / 1e9, 100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS))
 
 
+def types(args, torch, np, B, W):
+    """512 MiB of each element type through both kernels (default tuning), rotating 4 buffers."""
+    timer = Timer(torch, B)
+    with open_out(args, "types.txt") as f:
+        emit(f, "# 512 MiB per call, normal(0,1), 4 rotating buffers, default tuning; GB/s = bytes / time")
+        emit(f, "# dtype n kernel us Gelem/s GB/s pct_of_8TB/s")
+        for dtype, name, esize in ((B.MFR_DTYPE_F16, "f16", 2), (B.MFR_DTYPE_BF16, "bf16", 2), (B.MFR_DTYPE_F32, "f32", 4)):
+            n = (1 << 29) // esize
+            if dtype == B.MFR_DTYPE_F16:
+                host = torch.from_numpy(W.generate("normal", n, 3).view(np.int16))
+            elif dtype == B.MFR_DTYPE_BF16:
+                host = torch.from_numpy(W.generate_bf16("normal", n, 3).view(np.int16))
+            else:
+                host = torch.from_numpy(W.generate_f32("normal", n, 3))
+            bufs = [host.cuda() for _ in range(4)]
+            for kernel, kname in ((B.MFR_KERNEL_MFMA, "mfma_chain"), (B.MFR_KERNEL_SHFL, "shfl_tree")):
+                t = B.make_tuning(kernel=kernel)
+
+                def call(i):
+                    B.mfr_sum_ex(bufs[i % 4].data_ptr(), dtype, n, timer.out.data_ptr(), t, timer.stream)
+                for i in range(20):
+                    call(i)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(args.steps):
+                    call(i)
+                e1.record()
+                torch.cuda.synchronize()
+                dt = e0.elapsed_time(e1) * 1e-3 / args.steps
+                gb = n * esize / dt / 1e9
+                emit(f, "%s %d %s %.2f %.1f %.1f %.1f" % (name, n, kname, dt * 1e6, n / dt / 1e9, gb, 100 * gb / HBM_PEAK_GBPS))
+            del bufs
+
+
+def tune_f32(args, torch, np, B, W):
+    """Geometry search for binary32 input (four MFMAs per tile)."""
+    n = 1 << 27
+    host = torch.from_numpy(W.generate_f32("normal", n, 3))
+    bufs = [host.cuda() for _ in range(4)]
+    timer = Timer(torch, B)
+    with open_out(args, "tune_f32.txt") as f:
+        emit(f, "# f32 n=2^27 (512 MiB); kernel block R U grid us GB/s pct")
+        for kernel in (0, 1):
+            for block in (256, 512, 1024):
+                for R, U in ((1, 2), (1, 4), (1, 8), (2, 1), (2, 2), (2, 4), (4, 1), (4, 2), (8, 1), (4, 4), (8, 2)):
+                    for grid in (256, 512, 1024):
+                        t = B.make_tuning(block, R, grid, kernel, U)
+
+                        def call(i):
+                            B.mfr_sum_ex(bufs[i % 4].data_ptr(), B.MFR_DTYPE_F32, n, timer.out.data_ptr(), t, timer.stream)
+                        for i in range(5):
+                            call(i)
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        for i in range(args.steps):
+                            call(i)
+                        e1.record()
+                        torch.cuda.synchronize()
+                        dt = e0.elapsed_time(e1) * 1e-3 / args.steps
+                        gb = 4 * n / dt / 1e9
+                        emit(f, "%d %d %d %d %d %.2f %.1f %.1f" % (kernel, block, R, U, grid, dt * 1e6, gb, 100 * gb / HBM_PEAK_GBPS))
+
+
+def rows(args, torch, np, B, W):
+    """Batched form: rows x cols fp16 with rows * cols = 2^28 (512 MiB), 4 rotating buffers."""
+    total = 1 << 28
+    host = torch.from_numpy(W.generate("normal", total, 3).view(np.int16))
+    bufs = [host.cuda() for _ in range(4)]
+    timer = Timer(torch, B)
+    out = torch.zeros(1 << 21, dtype=torch.float32, device="cuda")
+    with open_out(args, "rows.txt") as f:
+        emit(f, "# rows x cols = 2^28 fp16 (512 MiB per call), 4 rotating buffers; tuning 'default' = library choice")
+        emit(f, "# rows cols tuning us Gelem/s GB/s pct_of_8TB/s")
+        for lr in (0, 4, 8, 12, 14, 16, 18, 20):
+            r, c = 1 << lr, total >> lr
+            cands = [("default", None)]
+            if args.quick != 1:
+                cands += [("b%d_R%d_U%d" % (b, R, U), B.make_tuning(b, R, 0, 0, U)) for b, R, U in
+                          ((64, 1, 8), (64, 1, 4), (64, 2, 4), (64, 4, 2), (128, 1, 4), (256, 1, 2), (256, 1, 8), (64, 1, 1), (64, 1, 2))]
+            for name, t in cands:
+                def call(i):
+                    B.mfr_sum_rows_ex(bufs[i % 4].data_ptr(), B.MFR_DTYPE_F16, r, c, c, out.data_ptr(), t, timer.stream)
+                for i in range(5):
+                    call(i)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(args.steps):
+                    call(i)
+                e1.record()
+                torch.cuda.synchronize()
+                dt = e0.elapsed_time(e1) * 1e-3 / args.steps
+                gb = 2 * total / dt / 1e9
+                emit(f, "%d %d %s %.2f %.1f %.1f %.1f" % (r, c, name, dt * 1e6, total / dt / 1e9, gb, 100 * gb / HBM_PEAK_GBPS))
+
+
 def run(args):
     import numpy as np
     import torch
@@ -190,4 +285,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"tune": tune, "config2": config2, "config5": config5}[args.sweep](args, torch, np, B, W)
+    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32}[args.sweep](args, torch, np, B, W)

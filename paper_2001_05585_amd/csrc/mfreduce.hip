@@ -65,9 +65,11 @@ std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
 
 constexpr int kDefaultBlock = 256;
 constexpr int kDefaultR = 4;
+constexpr int kDefaultR_f32 = 8;               // four MFMAs per tile: one long chain overlaps them with the loads
 constexpr int kDefaultWavesPerCU = 4;          // one wave per SIMD
 constexpr long long kTicketMaxBlocks = 320;    // larger grids combine with a second launch
 constexpr size_t kMaxRowsPerLaunch = 65535;    // gridDim.y limit
+constexpr size_t kWaveRowBytes = 8192;         // rows shorter than this get a wave each when there are many
 
 int default_in_flight(int R)
 {
@@ -98,7 +100,7 @@ int resolve_tuning(const mfr_tuning *in, int dtype, mfr_tuning *t)
     if (in) z = *in;
     if (!valid_dtype(dtype)) return MFR_ERR_INVALID_ARG;
     if (z.block_threads == 0) z.block_threads = kDefaultBlock;
-    if (z.chain_R == 0) z.chain_R = kDefaultR;
+    if (z.chain_R == 0) z.chain_R = dtype == MFR_DTYPE_F32 ? kDefaultR_f32 : kDefaultR;
     if (!valid_block(z.block_threads)) return MFR_ERR_INVALID_ARG;
     if (z.block_threads == 32 && dtype != MFR_DTYPE_F16) return MFR_ERR_INVALID_ARG;
     if (z.chain_R < 1 || z.chain_R > 8) return MFR_ERR_INVALID_ARG;
@@ -259,11 +261,26 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
 
     // rows can share one launch when they all have the same 16-byte phase
     const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
-    const size_t batch = same_phase ? (rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch) : 1;
+
+    // Many short rows: every wave reduces a row of its own (no cross-wave or
+    // cross-block combine); chosen by the library only, with its own geometry.
+    const bool wave_rows = same_phase && tin == nullptr && cols * esize < kWaveRowBytes &&
+                           rows >= (size_t)info.cus * 4;
+    if (wave_rows) {
+        // one chain covers the whole row where possible, so that all of a row's
+        // loads are in flight together
+        size_t tiles = cols * esize / 1024;
+        t.block_threads = 256;
+        t.chain_R = tiles < 1 ? 1 : (tiles > 8 ? 8 : (int)tiles);
+        t.chains_in_flight = 1;
+    }
+    const size_t rows_per_block = wave_rows ? (size_t)t.block_threads / 64 : 1;
+    const size_t batch = !same_phase ? 1
+                         : (rows < kMaxRowsPerLaunch * rows_per_block ? rows : kMaxRowsPerLaunch * rows_per_block);
 
     Plan p;
     plan_region(cols, (size_t)x, esize, t, &p);
-    const long long grid = grid_blocks_for(p, t, info.cus, batch);
+    const long long grid = wave_rows ? 1 : grid_blocks_for(p, t, info.cus, batch);
     if (grid < 1) return MFR_ERR_INVALID_ARG;
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
@@ -280,10 +297,13 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
         p.a.base = (const uint4v *)((size_t)xr & ~(size_t)15);
         p.a.x = xr;
         p.a.row_slots = same_phase ? (row_stride * esize) / 16u : 0;
+        p.a.rows = nr;
+        p.a.wave_rows = wave_rows ? 1u : 0u;
         p.a.partials = s.partials;
         p.a.ticket = two_launches ? nullptr : s.tickets;
         p.a.out = out + r0;
-        const hipError_t e = launch_dtype(dtype, p, dim3((unsigned)grid, (unsigned)nr), t, stream);
+        const size_t grid_y = (nr + rows_per_block - 1) / rows_per_block;
+        const hipError_t e = launch_dtype(dtype, p, dim3((unsigned)grid, (unsigned)grid_y), t, stream);
         if (e != hipSuccess) return hip_fail(e, "kernel launch");
         if (grid > 1 && two_launches) {
             hipLaunchKernelGGL(combine_kernel, dim3((unsigned)nr), dim3(grid > 4096 ? 1024 : 256), 0, stream,

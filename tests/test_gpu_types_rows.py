@@ -182,6 +182,24 @@ def test_rows_integer_inputs_bit_exact(rows, cols, stride, oracle_lib):
             assert np.array_equal(got.astype(np.float64), want), (rows, cols, stride, shift, got[:4], want[:4])
 
 
+@pytest.mark.parametrize("cols", [5, 37, 512, 1000, 3000, 4095])
+def test_many_short_rows_one_wave_each(cols, oracle_lib):
+    # library defaults + many short rows: every wave reduces a row of its own
+    rows = 2051
+    stride = (cols + 7) // 8 * 8 + 8
+    flat = W.small_integers(rows * stride + 16, seed=cols)
+    x2d = np.stack([flat[r * stride:r * stride + cols] for r in range(rows)])
+    want, _ = oracle_lib.sum_rows(x2d)
+    for shift in (0, 3):
+        d = TypedInput(flat.view(np.uint16), shift)
+        got = rows_call(d.ptr, B.MFR_DTYPE_F16, rows, cols, stride)
+        assert np.array_equal(got.astype(np.float64), want), (cols, shift, got[:4], want[:4])
+    f = W.generate_f32("normal", rows * stride, 1234 + cols)
+    s, sa = oracle_lib.sum_rows(f.reshape(rows, stride)[:, :cols], "f32")
+    got = rows_call(TypedInput(f.view(np.uint32), 0).ptr, B.MFR_DTYPE_F32, rows, cols, stride).astype(np.float64)
+    assert (np.abs(got - s) <= TOL * sa).all()
+
+
 def test_rows_random_inputs_and_types(oracle_lib):
     rows, cols = 48, 50000
     stride = cols + 8
