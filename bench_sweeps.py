@@ -244,6 +244,25 @@ def tune_f32(args, torch, np, B, W):
                         emit(f, "%d %d %d %d %d %.2f %.1f %.1f" % (kernel, block, R, U, grid, dt * 1e6, gb, 100 * gb / HBM_PEAK_GBPS))
 
 
+def split(args, torch, np, B, W):
+    """Section 5.3's experiment: fraction of the domain through the MFMA path vs the conventional path."""
+    timer = Timer(torch, B)
+    with open_out(args, "split.txt") as f:
+        emit(f, "# split variant: permille of the domain (and of the waves) on the MFMA path; fp16 normal(0,1)")
+        emit(f, "# n residency block R U grid permille_mfma us Gelem/s GB/s")
+        for n, copies, label in ((1 << 28, 4, "HBM(4x512MiB rotating)"), (1 << 24, 1, "cache-resident(32MiB)")):
+            x = W.generate("normal", n, W.config_seed(3))
+            bufs = device_buffers(torch, np, x, copies)
+            heat(timer, bufs, n, 0.3)
+            for block, R, U, grid in ((256, 4, 2, 0), (256, 1, 8, 0), (1024, 1, 2, 2048), (256, 1, 2, 2048)):
+                for pm in (0, 100, 250, 400, 500, 600, 750, 900, 1000):
+                    t = B.make_tuning(block, R, grid, B.MFR_KERNEL_SPLIT, U, 0, 0, pm)
+                    dt = timer.run(bufs, n, t, args.steps, 5)
+                    emit(f, "%d %s %d %d %d %d %d %.2f %.1f %.1f" % (n, label, block, R, U, B.mfr_grid_for(n, bufs[0].data_ptr(), t),
+                                                                  pm, dt * 1e6, n / dt / 1e9, 2 * n / dt / 1e9))
+            del bufs
+
+
 def rows(args, torch, np, B, W):
     """Batched form: rows x cols fp16 with rows * cols = 2^28 (512 MiB), 4 rotating buffers."""
     total = 1 << 28
@@ -285,4 +304,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32}[args.sweep](args, torch, np, B, W)
+    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split}[args.sweep](args, torch, np, B, W)

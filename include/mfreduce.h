@@ -48,8 +48,11 @@ enum {
 /* Which kernel computes the block partials. */
 enum {
     MFR_KERNEL_MFMA = 0, /* ones-matrix MFMA chains (Sections 4.1, 4.3, 5.2) */
-    MFR_KERNEL_SHFL = 1  /* conventional fp32 per-lane accumulate + wave shuffle tree:
+    MFR_KERNEL_SHFL = 1, /* conventional fp32 per-lane accumulate + wave shuffle tree:
                             the comparison kernel of Section 5.4 */
+    MFR_KERNEL_SPLIT = 2 /* "split in two" (Section 5.3): a fraction of the domain through the MFMA
+                            chains and the rest through the conventional path, in one pass, on
+                            disjoint sets of waves.  binary16 only, block_threads >= 64 */
 };
 
 /* grid_blocks special values */
@@ -82,6 +85,9 @@ typedef struct mfr_tuning {
                              chains_in_flight must not exceed 16 */
     int nontemporal;      /* 0 = library default, 1 = plain loads, 2 = non-temporal loads */
     int combine;          /* MFR_COMBINE_* */
+    int split_permille;   /* MFR_KERNEL_SPLIT only: thousandths of the domain (and of the waves) that
+                             take the MFMA path, 0..1000 (Section 5.3's fraction f); rounded to whole
+                             chains and whole waves */
 } mfr_tuning;
 
 /*

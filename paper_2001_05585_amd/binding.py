@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmfreduce.so")
 
 MFR_OK, MFR_ERR_INVALID_ARG, MFR_ERR_UNSUPPORTED, MFR_ERR_HIP = 0, 1, 2, 3
-MFR_KERNEL_MFMA, MFR_KERNEL_SHFL = 0, 1
+MFR_KERNEL_MFMA, MFR_KERNEL_SHFL, MFR_KERNEL_SPLIT = 0, 1, 2
 MFR_GRID_AUTO, MFR_GRID_ONE_CHAIN = 0, -1
 MFR_COMBINE_AUTO, MFR_COMBINE_SINGLE_LAUNCH, MFR_COMBINE_TWO_LAUNCHES = 0, 1, 2
 
@@ -29,7 +29,7 @@ class mfr_tuning(ctypes.Structure):
     _fields_ = [("block_threads", ctypes.c_int), ("chain_R", ctypes.c_int),
                 ("grid_blocks", ctypes.c_int), ("kernel", ctypes.c_int),
                 ("chains_in_flight", ctypes.c_int), ("nontemporal", ctypes.c_int),
-                ("combine", ctypes.c_int)]
+                ("combine", ctypes.c_int), ("split_permille", ctypes.c_int)]
 
 
 class MfrError(RuntimeError):
@@ -106,8 +106,9 @@ def mfr_sum_f16_tuned(x: int, n: int, out: int, block_threads: int, chain_R: int
 
 
 def make_tuning(block_threads=0, chain_R=0, grid_blocks=0, kernel=0, chains_in_flight=0,
-                nontemporal=0, combine=0) -> mfr_tuning:
-    return mfr_tuning(block_threads, chain_R, grid_blocks, kernel, chains_in_flight, nontemporal, combine)
+                nontemporal=0, combine=0, split_permille=0) -> mfr_tuning:
+    return mfr_tuning(block_threads, chain_R, grid_blocks, kernel, chains_in_flight, nontemporal, combine,
+                      split_permille)
 
 
 def mfr_sum_f16_ex(x: int, n: int, out: int, t: mfr_tuning | None = None, stream: int = 0) -> None:

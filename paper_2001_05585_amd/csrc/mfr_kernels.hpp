@@ -51,6 +51,8 @@ struct SumArgs {
     unsigned long long slots;    // total slots covering [x, x + n)
     unsigned long long row_slots;  // distance between rows in slots (rows share the 16-byte phase)
     unsigned long long rows;     // rows of this launch
+    unsigned long long split_chains;  // MFR_KERNEL_SPLIT: chains [0, split_chains) take the MFMA path ...
+    unsigned long long split_waves;   // ... on waves [0, split_waves); the rest is conventional
     unsigned int wave_rows;      // nonzero: every wave reduces a row of its own (short rows)
     unsigned int head;           // elements of slot 0 that lie before x
     float *partials;             // gridDim.x per row
@@ -265,14 +267,75 @@ __device__ __forceinline__ float consume_chain(const uint4v (&v)[R])
 
 // ------------------------------------------------------------- kernels ---
 
-// KERNEL: MFR_KERNEL_MFMA or MFR_KERNEL_SHFL.  DT: element type.  R: chain
-// length in tiles.  U: chains in flight.  NT: non-temporal loads.  HALF: only
-// lanes 0..31 carry data (the "32-thread block" geometry on a wave64 machine),
-// a tile is then 32 slots.  blockIdx.y selects the row of a batched call.
+// The chains c, c + stride, c + 2 stride, ... below c_end of one wave, and (if
+// `border`) the border tiles.  KIND is MFR_KERNEL_MFMA (returns the wave's sum
+// of chain totals, uniform) or MFR_KERNEL_SHFL (returns this lane's fp32 sum).
+template <int KIND, int DT, int R, int U, bool NT, bool HALF>
+__device__ __forceinline__ float stream_chains(const SumArgs &a, const uint4v *base, const void *x, unsigned lane,
+                                               unsigned long long c, unsigned long long c_end,
+                                               unsigned long long stride, bool border)
+{
+    constexpr unsigned TS = HALF ? 32u : 64u;          // slots per tile
+    const bool carries = !HALF || lane < 32u;
+    const uint4v zero4 = {0u, 0u, 0u, 0u};
+    const uint4v *lane_base = base + a.main0 + (carries ? lane : 0u);
+    float partial = 0.f;
+
+    if constexpr (U > 1) {
+        for (; c + (unsigned long long)(U - 1) * stride < c_end; c += (unsigned long long)U * stride) {
+            uint4v v[U][R];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const uint4v *p = lane_base + ((c + (unsigned long long)u * stride) * R + r) * TS;
+                    v[u][r] = carries ? load_slot<NT>(p) : zero4;
+                }
+            // all U * R loads are issued before the first is consumed
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < U; ++u) partial += consume_chain<KIND, DT, R>(v[u]);
+        }
+    }
+    for (; c < c_end; c += stride) {
+        uint4v v[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint4v *p = lane_base + (c * R + r) * TS;
+            v[r] = carries ? load_slot<NT>(p) : zero4;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        partial += consume_chain<KIND, DT, R>(v);
+    }
+
+    // Border: leftover whole tiles (fewer than R), leftover slots, the partial
+    // last slot and the head slot, as masked tiles in chains of R (at most two
+    // chains; tiles past the end are all zeros).
+    if (border) {
+        for (unsigned long long p0 = a.epi0; p0 < a.epi1; p0 += (unsigned long long)R * TS) {
+            uint4v v[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                v[r] = load_epilogue<DT>(a, base, x, p0 + (unsigned long long)r * TS + lane, carries);
+            partial += consume_chain<KIND, DT, R>(v);
+        }
+    }
+    return partial;
+}
+
+// KERNEL: MFR_KERNEL_MFMA, MFR_KERNEL_SHFL or MFR_KERNEL_SPLIT.  DT: element
+// type.  R: chain length in tiles.  U: chains in flight.  NT: non-temporal
+// loads.  HALF: only lanes 0..31 carry data (the "32-thread block" geometry on
+// a wave64 machine), a tile is then 32 slots.  blockIdx.y selects the row of a
+// batched call.
+//
+// MFR_KERNEL_SPLIT (Section 5.3, "split in two"): the first a.split_chains
+// chains of the domain go through the MFMA path on the first a.split_waves
+// waves, the rest of the domain through the conventional path on the other
+// waves, all in the same pass.
 template <int KERNEL, int DT, int R, int U, bool NT, bool HALF>
 __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
 {
-    constexpr unsigned TS = HALF ? 32u : 64u;          // slots per tile
     const unsigned lane = threadIdx.x & 63u;
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform
     const unsigned wpb = (blockDim.x + 63u) >> 6;
@@ -282,61 +345,26 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
     const bool wave_rows = a.wave_rows != 0u;
     const unsigned long long W = wave_rows ? 1ull : (unsigned long long)gridDim.x * wpb;
     const unsigned long long w = wave_rows ? 0ull : (unsigned long long)blockIdx.x * wpb + wave;
-    const bool carries = !HALF || lane < 32u;
-    const uint4v zero4 = {0u, 0u, 0u, 0u};
 
     const unsigned long long row = wave_rows ? (unsigned long long)blockIdx.y * wpb + wave : blockIdx.y;
     if (row >= a.rows) return;          // whole waves only (wave-row mode); no barrier follows for them
     const uint4v *base = a.base + row * a.row_slots;
     const void *x = (const char *)a.x + row * a.row_slots * 16ull;
 
-    // MFMA path: `partial` is the wave's running sum of chain totals (uniform).
-    // SHFL path: `partial` is this lane's running fp32 sum.
-    float partial = 0.f;
-    const uint4v *lane_base = base + a.main0 + (carries ? lane : 0u);
-
-    unsigned long long c = w;
-    if constexpr (U > 1) {
-        for (; c + (unsigned long long)(U - 1) * W < a.chains; c += (unsigned long long)U * W) {
-            uint4v v[U][R];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const uint4v *p = lane_base + ((c + (unsigned long long)u * W) * R + r) * TS;
-                    v[u][r] = carries ? load_slot<NT>(p) : zero4;
-                }
-            // all U * R loads are issued before the first is consumed
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < U; ++u) partial += consume_chain<KERNEL, DT, R>(v[u]);
+    float partial;                       // the wave's fp32 partial, uniform
+    if constexpr (KERNEL == MFR_KERNEL_MFMA) {
+        partial = stream_chains<MFR_KERNEL_MFMA, DT, R, U, NT, HALF>(a, base, x, lane, w, a.chains, W, w == W - 1);
+    } else if constexpr (KERNEL == MFR_KERNEL_SHFL) {
+        partial = wave64_sum(stream_chains<MFR_KERNEL_SHFL, DT, R, U, NT, HALF>(a, base, x, lane, w, a.chains, W, w == W - 1));
+    } else {
+        const unsigned long long W1 = a.split_waves, C1 = a.split_chains;
+        if (w < W1) {
+            partial = stream_chains<MFR_KERNEL_MFMA, DT, R, U, NT, HALF>(a, base, x, lane, w, C1, W1, w == W - 1);
+        } else {
+            partial = wave64_sum(stream_chains<MFR_KERNEL_SHFL, DT, R, U, NT, HALF>(a, base, x, lane, C1 + (w - W1),
+                                                                                  a.chains, W - W1, w == W - 1));
         }
     }
-    for (; c < a.chains; c += W) {
-        uint4v v[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const uint4v *p = lane_base + (c * R + r) * TS;
-            v[r] = carries ? load_slot<NT>(p) : zero4;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        partial += consume_chain<KERNEL, DT, R>(v);
-    }
-
-    // Border: leftover whole tiles (fewer than R), leftover slots, the partial
-    // last slot and the head slot, as masked tiles in chains of R (at most two
-    // chains; tiles past the end are all zeros).
-    if (w == W - 1) {
-        for (unsigned long long p0 = a.epi0; p0 < a.epi1; p0 += (unsigned long long)R * TS) {
-            uint4v v[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                v[r] = load_epilogue<DT>(a, base, x, p0 + (unsigned long long)r * TS + lane, carries);
-            partial += consume_chain<KERNEL, DT, R>(v);
-        }
-    }
-
-    if constexpr (KERNEL == MFR_KERNEL_SHFL) partial = wave64_sum(partial);
 
     if (wave_rows) {
         if (lane == 0) a.out[row] = partial;
@@ -397,7 +425,7 @@ hipError_t launch_ru(const Plan &p, dim3 grid, bool nt, hipStream_t stream)
 {
     const dim3 b((unsigned)p.threads);
     if (p.half) {
-        if constexpr (DT == MFR_DTYPE_F16) {
+        if constexpr (DT == MFR_DTYPE_F16 && KERNEL != MFR_KERNEL_SPLIT) {
             if (nt) hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, true, true>), grid, b, 0, stream, p.a);
             else hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, false, true>), grid, b, 0, stream, p.a);
         } else {
@@ -433,8 +461,12 @@ hipError_t launch_k(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t s
 template <int DT>
 hipError_t launch_sum(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream)
 {
-    return t.kernel == MFR_KERNEL_MFMA ? launch_k<MFR_KERNEL_MFMA, DT>(p, grid, t, stream)
-                                       : launch_k<MFR_KERNEL_SHFL, DT>(p, grid, t, stream);
+    if (t.kernel == MFR_KERNEL_MFMA) return launch_k<MFR_KERNEL_MFMA, DT>(p, grid, t, stream);
+    if (t.kernel == MFR_KERNEL_SHFL) return launch_k<MFR_KERNEL_SHFL, DT>(p, grid, t, stream);
+    if constexpr (DT == MFR_DTYPE_F16) {
+        if (t.kernel == MFR_KERNEL_SPLIT && !p.half) return launch_k<MFR_KERNEL_SPLIT, DT>(p, grid, t, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 // one translation unit per element type (they compile in parallel)

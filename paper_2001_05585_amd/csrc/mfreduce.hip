@@ -105,7 +105,11 @@ int resolve_tuning(const mfr_tuning *in, int dtype, mfr_tuning *t)
     if (z.block_threads == 32 && dtype != MFR_DTYPE_F16) return MFR_ERR_INVALID_ARG;
     if (z.chain_R < 1 || z.chain_R > 8) return MFR_ERR_INVALID_ARG;
     if (z.grid_blocks < MFR_GRID_ONE_CHAIN) return MFR_ERR_INVALID_ARG;
-    if (z.kernel != MFR_KERNEL_MFMA && z.kernel != MFR_KERNEL_SHFL) return MFR_ERR_INVALID_ARG;
+    if (z.kernel != MFR_KERNEL_MFMA && z.kernel != MFR_KERNEL_SHFL && z.kernel != MFR_KERNEL_SPLIT)
+        return MFR_ERR_INVALID_ARG;
+    if (z.kernel == MFR_KERNEL_SPLIT && (dtype != MFR_DTYPE_F16 || z.block_threads == 32)) return MFR_ERR_INVALID_ARG;
+    if (z.split_permille < 0 || z.split_permille > 1000) return MFR_ERR_INVALID_ARG;
+    if (z.kernel != MFR_KERNEL_SPLIT && z.split_permille != 0) return MFR_ERR_INVALID_ARG;
     if (z.chains_in_flight == 0) z.chains_in_flight = default_in_flight(z.chain_R);
     const int u = z.chains_in_flight;
     if (!(u == 1 || u == 2 || u == 4 || u == 8)) return MFR_ERR_INVALID_ARG;
@@ -297,6 +301,18 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
         p.a.base = (const uint4v *)((size_t)xr & ~(size_t)15);
         p.a.x = xr;
         p.a.row_slots = same_phase ? (row_stride * esize) / 16u : 0;
+        if (t.kernel == MFR_KERNEL_SPLIT) {
+            // the same fraction of the chains and of the waves; a part without waves gets no chains
+            const unsigned long long W = (unsigned long long)grid * (unsigned)p.waves;
+            unsigned long long w1 = (W * (unsigned)t.split_permille + 500ull) / 1000ull;
+            unsigned long long c1 = (p.a.chains * (unsigned)t.split_permille + 500ull) / 1000ull;
+            if (w1 == 0) c1 = 0;
+            if (w1 >= W) { w1 = W; c1 = p.a.chains; }
+            if (c1 == 0) w1 = 0;
+            if (c1 == p.a.chains) w1 = W;
+            p.a.split_waves = w1;
+            p.a.split_chains = c1;
+        }
         p.a.rows = nr;
         p.a.wave_rows = wave_rows ? 1u : 0u;
         p.a.partials = s.partials;

@@ -239,6 +239,52 @@ def test_both_combine_modes_agree(oracle_lib):
     assert np.all(np.abs(pairs[:, 0] - pairs[:, 1]) <= np.spacing(np.abs(pairs[:, 0]).astype(np.float32)))
 
 
+# ------------------------------------------------ split variant (Section 5.3) ---
+
+def split_tunings():
+    for f in (0, 1, 250, 500, 873, 999, 1000):
+        for block, R, grid, U in ((256, 4, 0, 2), (64, 1, 7, 1), (512, 2, 0, 4), (128, 8, -1, 1), (1024, 3, 2, 2)):
+            yield B.make_tuning(block, R, grid, B.MFR_KERNEL_SPLIT, U, 0, 0, f)
+
+
+def test_split_variant_integer_inputs_bit_exact(oracle_lib):
+    for n in (1, 511, 5000, (1 << 18) + 7, (1 << 21) + 12345):
+        x = W.small_integers(n, seed=900 + n % 13, lo=-4, hi=4)
+        want = oracle_lib.sum_f16(x)[0]
+        for shift in (0, 5):
+            d = DeviceInput(x, shift)
+            ts = list(split_tunings())
+            o = Outputs(len(ts))
+            for i, t in enumerate(ts):
+                B.mfr_sum_f16_ex(d.ptr, n, o.ptr(i), t, stream_handle())
+            r = o.get()
+            bad = [(describe(t), t.split_permille, r[i]) for i, t in enumerate(ts) if r[i] != want]
+            assert not bad, (n, shift, want, bad[:6])
+
+
+def test_split_variant_one_hot_and_random(oracle_lib):
+    t = B.make_tuning(128, 2, 2, B.MFR_KERNEL_SPLIT, 1, 0, 0, 400)
+    n = 3 * (2 * 2 * 2 * 512) + 1024 + 7
+    d = DeviceInput(np.zeros(n, dtype=np.float16), 2)
+    o = Outputs(n)
+    for p in range(n):
+        d.set(p, 0x3C00)
+        B.mfr_sum_f16_ex(d.ptr, n, o.ptr(p), t, stream_handle())
+        d.set(p, 0)
+    r = o.get()
+    assert np.all(r == 1.0), np.nonzero(r != 1.0)[0][:8]
+    n = (1 << 23) + 3
+    x = W.generate("normal", n, 4242)
+    s, sa = oracle_lib.sum_f16(x)
+    d = DeviceInput(x)
+    ts = list(split_tunings())
+    o = Outputs(len(ts))
+    for i, tt in enumerate(ts):
+        B.mfr_sum_f16_ex(d.ptr, n, o.ptr(i), tt, stream_handle())
+    r = o.get().astype(np.float64)
+    assert (np.abs(r - s) / sa).max() <= TOL
+
+
 def test_repeat_calls_are_bit_identical():
     x = W.generate("normal", (1 << 22) + 3, 77)
     d = DeviceInput(x, 1)

@@ -54,9 +54,11 @@ def test_invalid_arguments_are_rejected_before_any_hip_call():
     for R in (0, -1, 9, 100):
         assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, R, 0, 0, None) == INV
     assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, 1, -2, 0, None) == INV
-    assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, 1, 0, 2, None) == INV
+    assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, 1, 0, 3, None) == INV
     for kw in (dict(chains_in_flight=3), dict(chains_in_flight=16), dict(chain_R=8, chains_in_flight=4),
-               dict(nontemporal=3), dict(kernel=-1), dict(block_threads=100), dict(combine=3), dict(combine=-1)):
+               dict(nontemporal=3), dict(kernel=-1), dict(block_threads=100), dict(combine=3), dict(combine=-1),
+               dict(kernel=2, split_permille=1001), dict(kernel=2, split_permille=-1), dict(kernel=0, split_permille=500),
+               dict(kernel=2, block_threads=32)):
         t = B.make_tuning(**kw)
         assert L.mfr_sum_f16_ex(4096, 5, 4096, ctypes.byref(t), None) == INV
     with pytest.raises(B.MfrError):
@@ -129,6 +131,8 @@ def test_typed_and_batched_entries_reject_bad_arguments():
     assert L.mfr_sum_rows_ex(4096, 0, 4, 100, 100, None, None, None) == INV
     assert L.mfr_sum_rows_ex(4096, 0, 0, 100, 100, 4096, None, None) == B.MFR_OK   # no rows: nothing to do
     assert L.mfr_sum_f16_rows(4097, 2, 8, 8, 4096, None) == INV
+    split = B.make_tuning(kernel=B.MFR_KERNEL_SPLIT, split_permille=500)
+    assert L.mfr_sum_ex(4096, B.MFR_DTYPE_F32, 5, 4096, ctypes.byref(split), None) == INV   # split: binary16 only
 
 
 def test_grid_for_one_chain_geometry():
