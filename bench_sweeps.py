@@ -263,6 +263,36 @@ def split(args, torch, np, B, W):
             del bufs
 
 
+def variants(args, torch, np, B, W):
+    """Section 5.4's comparison on this GPU: run time of the single-pass, recurrence and shuffle
+    kernels and the result each returns, over n, for normal(0,1) and uniform[0,1) inputs.
+    (The errors against the CPU oracle are tabulated by tests/test_gpu_recurrence.py::test_error_vs_n_table.)"""
+    timer = Timer(torch, B)
+    out = torch.zeros(4, dtype=torch.float32, device="cuda")
+    with open_out(args, "variants.txt") as f:
+        emit(f, "# kind n variant us Gelem/s result   (one buffer per n: sizes up to 2^26 are cache-resident)")
+        for kind, cfg in (("normal", 3), ("uniform01", 2)):
+            x = W.generate(kind, 1 << 28, W.config_seed(cfg))
+            dev = torch.from_numpy(x.view(np.int16)).cuda()
+            for k in range(10, 29, 2):
+                n = 1 << k
+                calls = (("single_pass", lambda: B.mfr_sum_f16(dev.data_ptr(), n, out.data_ptr(), timer.stream)),
+                         ("recurrence_R4", lambda: B.mfr_sum_f16_recurrence(dev.data_ptr(), n, out.data_ptr(), 4, timer.stream)),
+                         ("recurrence_R5", lambda: B.mfr_sum_f16_recurrence(dev.data_ptr(), n, out.data_ptr(), 5, timer.stream)),
+                         ("shuffle_tree", lambda: B.mfr_sum_f16_tuned(dev.data_ptr(), n, out.data_ptr(), 256, 4, 0, 1, timer.stream)))
+                for name, call in calls:
+                    for _ in range(5):
+                        call()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(args.steps):
+                        call()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    dt = e0.elapsed_time(e1) * 1e-3 / args.steps
+                    emit(f, "%s %d %s %.2f %.2f %r" % (kind, n, name, dt * 1e6, n / dt / 1e9, float(out[0].item())))
+
+
 def rows(args, torch, np, B, W):
     """Batched form: rows x cols fp16 with rows * cols = 2^28 (512 MiB), 4 rotating buffers."""
     total = 1 << 28
@@ -304,4 +334,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split}[args.sweep](args, torch, np, B, W)
+    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants}[args.sweep](args, torch, np, B, W)

@@ -149,6 +149,21 @@ int mfr_sum_rows_ex(const void *x, int dtype, size_t rows, size_t cols, size_t r
 int mfr_sum_f16_rows(const mfr_half *x, size_t rows, size_t cols, size_t row_stride, float *out,
                      hipStream_t stream);
 
+/*
+ * Variant #1 of the paper, "recurrence" (Section 5.1; Algorithms 1 and 2 with
+ * chains of chain_R MMAs, Section 4.3), as published: each level reduces every
+ * group of chain_R * 512 values to one value STORED AS binary16 (the 16 column
+ * sums of the chain are rounded to binary16, a last MMA adds them, the group
+ * total is rounded to binary16), and levels are relaunched until one value is
+ * left.  Provided to reproduce the behaviour Section 5.4 reports: the result
+ * carries binary16 rounding at every level and becomes +-Inf as soon as a group
+ * sum passes 65504.  Use mfr_sum_f16 for an accurate sum.
+ *   x, n, out, stream  as for mfr_sum_f16 (x is not modified: the levels live in
+ *                      library scratch); chain_R in 1..8.
+ * Groups are counted from x rounded down to 16 bytes (leading padding is zero).
+ */
+int mfr_sum_f16_recurrence(const mfr_half *x, size_t n, float *out, int chain_R, hipStream_t stream);
+
 /* The geometry mfr_sum_f16 uses.  Any pointer may be NULL. */
 int mfr_get_default_tuning(int *block_threads, int *chain_R, int *grid_blocks);
 

@@ -474,6 +474,12 @@ hipError_t launch_sum_f16(const Plan &p, dim3 grid, const mfr_tuning &t, hipStre
 hipError_t launch_sum_bf16(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
 hipError_t launch_sum_f32(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
 
+// One level of the recurrence variant (recurrence.hip): a.chains groups of R
+// tiles, one binary16 value out per group; final_out (if not null) receives the
+// value of group 0 as a float.
+hipError_t launch_recurrence_level(const SumArgs &a, int R, unsigned short *level_out, float *final_out,
+                                   hipStream_t stream);
+
 }  // namespace mfr
 
 #endif  // MFR_KERNELS_HPP

@@ -57,6 +57,8 @@ struct Scratch {
     size_t partials_capacity = 0;   // floats
     unsigned int *tickets = nullptr;
     size_t tickets_capacity = 0;    // counters, all zero between calls
+    unsigned short *levels = nullptr;   // recurrence variant: the binary16 partials of two levels
+    size_t levels_capacity = 0;
 };
 
 std::mutex g_mutex;
@@ -331,6 +333,59 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     return MFR_OK;
 }
 
+// Algorithm 1: relaunch the level kernel until one value is left.
+int recurrence_impl(const mfr_half *x, size_t n, float *out, int R, hipStream_t stream)
+{
+    if (R < 1 || R > 8) return MFR_ERR_INVALID_ARG;
+    if (!out) return MFR_ERR_INVALID_ARG;
+    if (n > 0 && !x) return MFR_ERR_INVALID_ARG;
+    if (((size_t)x & 1u) != 0 || n > ((size_t)1 << 60)) return MFR_ERR_INVALID_ARG;
+    int dev = 0;
+    MFR_HIP(hipGetDevice(&dev));
+    DeviceInfo info;
+    const int ds = device_info(dev, &info);
+    if (ds != MFR_OK) return ds;
+    if (!info.gfx950) return MFR_ERR_UNSUPPORTED;
+    if (n == 0) return fill_zero(out, 1, stream);
+
+    const size_t group = (size_t)R * 512;
+    const size_t first = (n + 7 + group - 1) / group + 1;      // level-1 values (head padding included)
+    const size_t second = (first + group - 1) / group + 1;
+    const size_t first_padded = (first + 7) / 8 * 8;            // keeps the second buffer 16-byte aligned
+    unsigned short *levels = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        Scratch &s = g_scratch[std::make_pair(dev, stream)];
+        const int st = grow((void **)&s.levels, &s.levels_capacity, first_padded + second + 8, sizeof(unsigned short),
+                            4096, false, stream);
+        if (st != MFR_OK) return st;
+        levels = s.levels;
+    }
+    unsigned short *buf[2] = {levels, levels + first_padded};
+
+    const void *cur = x;
+    size_t count = n;
+    int k = 0;
+    do {
+        mfr::SumArgs a;
+        memset(&a, 0, sizeof a);
+        const unsigned head = (unsigned)(((size_t)cur & 15u) / 2u);
+        a.base = (const uint4v *)((size_t)cur & ~(size_t)15);
+        a.x = cur;
+        a.n = count;
+        a.head = head;
+        a.vend = (unsigned long long)head + count;
+        a.slots = (a.vend + 7ull) / 8ull;
+        a.chains = (a.slots + 64ull * (unsigned)R - 1ull) / (64ull * (unsigned)R);   // groups, the last one padded
+        const hipError_t e = mfr::launch_recurrence_level(a, R, buf[k & 1], a.chains == 1 ? out : nullptr, stream);
+        if (e != hipSuccess) return hip_fail(e, "recurrence level launch");
+        cur = buf[k & 1];
+        count = (size_t)a.chains;
+        ++k;
+    } while (count > 1);
+    return MFR_OK;
+}
+
 int sum_impl(const void *x, int dtype, size_t n, float *out, const mfr_tuning *tin, hipStream_t stream)
 {
     return sum_rows_impl(x, dtype, 1, n, n, out, tin, stream);
@@ -389,6 +444,11 @@ int mfr_sum_f16_rows(const mfr_half *x, size_t rows, size_t cols, size_t row_str
                      hipStream_t stream)
 {
     return sum_rows_impl(x, MFR_DTYPE_F16, rows, cols, row_stride, out, nullptr, stream);
+}
+
+int mfr_sum_f16_recurrence(const mfr_half *x, size_t n, float *out, int chain_R, hipStream_t stream)
+{
+    return recurrence_impl(x, n, out, chain_R, stream);
 }
 
 int mfr_get_default_tuning(int *block_threads, int *chain_R, int *grid_blocks)
