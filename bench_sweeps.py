@@ -293,6 +293,36 @@ def variants(args, torch, np, B, W):
                     emit(f, "%s %d %s %.2f %.2f %r" % (kind, n, name, dt * 1e6, n / dt / 1e9, float(out[0].item())))
 
 
+def wide(args, torch, np, B, W):
+    """Run time of the binary64-accumulation mode beside the standard fp32 mode at n = 2^28."""
+    n = 1 << 28
+    x = W.generate("uniform01", n, W.config_seed(2))
+    bufs = device_buffers(torch, np, x, 4)
+    timer = Timer(torch, B)
+    out64 = torch.zeros(2, dtype=torch.float64, device="cuda")
+    heat(timer, bufs, n, 0.5)
+    with open_out(args, "wide.txt") as f:
+        emit(f, "# n=2^28 uniform[0,1), 4 rotating buffers; mode R U us Gelem/s GB/s pct_of_8TB/s result")
+        dt = timer.run(bufs, n, None, args.steps, 10)
+        emit(f, "fp32_partials 4 2 %.2f %.1f %.1f %.1f %r" % (dt * 1e6, n / dt / 1e9, 2 * n / dt / 1e9, 100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS, timer.result()))
+        for R, U in ((1, 8), (2, 4), (4, 2), (8, 1)):
+            t = B.make_tuning(256, R, 0, 0, U)
+
+            def call(i):
+                B.mfr_sum_f16_f64_ex(bufs[i % 4].data_ptr(), n, out64.data_ptr(), t, timer.stream)
+            for i in range(10):
+                call(i)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(args.steps):
+                call(i)
+            e1.record()
+            torch.cuda.synchronize()
+            dt = e0.elapsed_time(e1) * 1e-3 / args.steps
+            emit(f, "binary64_after_chain %d %d %.2f %.1f %.1f %.1f %r" % (R, U, dt * 1e6, n / dt / 1e9, 2 * n / dt / 1e9,
+                                                                      100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS, float(out64[0].item())))
+
+
 def rows(args, torch, np, B, W):
     """Batched form: rows x cols fp16 with rows * cols = 2^28 (512 MiB), 4 rotating buffers."""
     total = 1 << 28
@@ -334,4 +364,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants}[args.sweep](args, torch, np, B, W)
+    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants, "wide": wide}[args.sweep](args, torch, np, B, W)

@@ -150,6 +150,22 @@ int mfr_sum_f16_rows(const mfr_half *x, size_t rows, size_t cols, size_t row_str
                      hipStream_t stream);
 
 /*
+ * Higher-accuracy mode of the single-pass sum.  The chains of chain_R MFMAs
+ * keep fp32 accumulators as in Section 4.3, but every step after a chain --
+ * the running sum per lane, the wave, block and grid combines -- is carried in
+ * binary64 and the result is returned as a double.  The remaining error is
+ * that of the 32 * chain_R fp32 additions inside one accumulator column, so it
+ * does not grow with n: |result - sum| <= (32 chain_R + 4) 2^-24 sum|x_i| in the
+ * worst case, far less in practice; integer-valued inputs are summed exactly
+ * up to 2^53.  (Sections 2.2 and 5.4 discuss the precision of fp32 partials.)
+ *   out   device pointer to one double, 8-byte aligned.
+ *   t     as for mfr_sum_f16_ex; kernel must be MFR_KERNEL_MFMA, block_threads
+ *         >= 64, chain_R in {1, 2, 4, 8} (default 1).
+ */
+int mfr_sum_f16_f64(const mfr_half *x, size_t n, double *out, hipStream_t stream);
+int mfr_sum_f16_f64_ex(const mfr_half *x, size_t n, double *out, const mfr_tuning *t, hipStream_t stream);
+
+/*
  * Variant #1 of the paper, "recurrence" (Section 5.1; Algorithms 1 and 2 with
  * chains of chain_R MMAs, Section 4.3), as published: each level reduces every
  * group of chain_R * 512 values to one value STORED AS binary16 (the 16 column

@@ -21,7 +21,7 @@ MFR_COMBINE_AUTO, MFR_COMBINE_SINGLE_LAUNCH, MFR_COMBINE_TWO_LAUNCHES = 0, 1, 2
 MFR_DTYPE_F16, MFR_DTYPE_BF16, MFR_DTYPE_F32 = 0, 1, 2
 
 EXPORTS = ("mfr_sum_f16", "mfr_sum_f16_tuned", "mfr_sum_f16_ex", "mfr_sum_bf16", "mfr_sum_f32", "mfr_sum_ex",
-           "mfr_sum_rows_ex", "mfr_sum_f16_rows", "mfr_sum_f16_recurrence", "mfr_get_default_tuning", "mfr_grid_for", "mfr_plan_for",
+           "mfr_sum_rows_ex", "mfr_sum_f16_rows", "mfr_sum_f16_recurrence", "mfr_sum_f16_f64", "mfr_sum_f16_f64_ex", "mfr_get_default_tuning", "mfr_grid_for", "mfr_plan_for",
            "mfr_plan_ex", "mfr_strerror", "mfr_last_hip_error", "mfr_version")
 
 
@@ -69,6 +69,10 @@ def lib() -> ctypes.CDLL:
     L.mfr_sum_rows_ex.restype = ci
     L.mfr_sum_f16_rows.argtypes = [vp, sz, sz, sz, vp, vp]
     L.mfr_sum_f16_rows.restype = ci
+    L.mfr_sum_f16_f64.argtypes = [vp, sz, vp, vp]
+    L.mfr_sum_f16_f64.restype = ci
+    L.mfr_sum_f16_f64_ex.argtypes = [vp, sz, vp, ctypes.POINTER(mfr_tuning), vp]
+    L.mfr_sum_f16_f64_ex.restype = ci
     L.mfr_sum_f16_recurrence.argtypes = [vp, sz, vp, ci, vp]
     L.mfr_sum_f16_recurrence.restype = ci
     L.mfr_plan_ex.argtypes = [sz, sz, ci, ctypes.POINTER(mfr_tuning), ctypes.POINTER(ctypes.c_ulonglong)]
@@ -139,6 +143,15 @@ def mfr_sum_rows_ex(x: int, dtype: int, rows: int, cols: int, row_stride: int, o
 
 def mfr_sum_f16_rows(x: int, rows: int, cols: int, row_stride: int, out: int, stream: int = 0) -> None:
     _check(lib().mfr_sum_f16_rows(x, rows, cols, row_stride, out, stream), "mfr_sum_f16_rows")
+
+
+def mfr_sum_f16_f64(x: int, n: int, out: int, stream: int = 0) -> None:
+    _check(lib().mfr_sum_f16_f64(x, n, out, stream), "mfr_sum_f16_f64")
+
+
+def mfr_sum_f16_f64_ex(x: int, n: int, out: int, t: mfr_tuning | None = None, stream: int = 0) -> None:
+    tp = ctypes.byref(t) if t is not None else None
+    _check(lib().mfr_sum_f16_f64_ex(x, n, out, tp, stream), "mfr_sum_f16_f64_ex")
 
 
 def mfr_sum_f16_recurrence(x: int, n: int, out: int, chain_R: int, stream: int = 0) -> None:

@@ -247,16 +247,21 @@ __device__ __forceinline__ float slot_sum_f32(uint4v s)
     }
 }
 
+// Internal kind: MFMA chain whose 16 column sums are handed back unfolded
+// (lane l gets column l mod 16), for the binary64 accumulation mode.
+constexpr int KIND_MFMA_COLUMNS = 16;
+
 // One chain of R tiles to one fp32 value.  MFMA path: the chain total, uniform
 // over the wave.  Conventional path: this lane's share of it.
 template <int KERNEL, int DT, int R>
 __device__ __forceinline__ float consume_chain(const uint4v (&v)[R])
 {
-    if constexpr (KERNEL == MFR_KERNEL_MFMA) {
+    if constexpr (KERNEL == MFR_KERNEL_MFMA || KERNEL == KIND_MFMA_COLUMNS) {
         float4v acc = {0.f, 0.f, 0.f, 0.f};                 // C_0 = 0
 #pragma unroll
         for (int r = 0; r < R; ++r) acc = mma_ones<DT>(v[r], acc);
-        return chain_total(acc);
+        if constexpr (KERNEL == KIND_MFMA_COLUMNS) return acc.x;
+        else return chain_total(acc);
     } else {
         float s = 0.f;
 #pragma unroll
@@ -270,16 +275,16 @@ __device__ __forceinline__ float consume_chain(const uint4v (&v)[R])
 // The chains c, c + stride, c + 2 stride, ... below c_end of one wave, and (if
 // `border`) the border tiles.  KIND is MFR_KERNEL_MFMA (returns the wave's sum
 // of chain totals, uniform) or MFR_KERNEL_SHFL (returns this lane's fp32 sum).
-template <int KIND, int DT, int R, int U, bool NT, bool HALF>
-__device__ __forceinline__ float stream_chains(const SumArgs &a, const uint4v *base, const void *x, unsigned lane,
-                                               unsigned long long c, unsigned long long c_end,
-                                               unsigned long long stride, bool border)
+template <int KIND, int DT, int R, int U, bool NT, bool HALF, typename Acc = float>
+__device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *base, const void *x, unsigned lane,
+                                             unsigned long long c, unsigned long long c_end,
+                                             unsigned long long stride, bool border)
 {
     constexpr unsigned TS = HALF ? 32u : 64u;          // slots per tile
     const bool carries = !HALF || lane < 32u;
     const uint4v zero4 = {0u, 0u, 0u, 0u};
     const uint4v *lane_base = base + a.main0 + (carries ? lane : 0u);
-    float partial = 0.f;
+    Acc partial = 0;
 
     if constexpr (U > 1) {
         for (; c + (unsigned long long)(U - 1) * stride < c_end; c += (unsigned long long)U * stride) {
@@ -294,7 +299,7 @@ __device__ __forceinline__ float stream_chains(const SumArgs &a, const uint4v *b
             // all U * R loads are issued before the first is consumed
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int u = 0; u < U; ++u) partial += consume_chain<KIND, DT, R>(v[u]);
+            for (int u = 0; u < U; ++u) partial += (Acc)consume_chain<KIND, DT, R>(v[u]);
         }
     }
     for (; c < c_end; c += stride) {
@@ -305,7 +310,7 @@ __device__ __forceinline__ float stream_chains(const SumArgs &a, const uint4v *b
             v[r] = carries ? load_slot<NT>(p) : zero4;
         }
         __builtin_amdgcn_sched_barrier(0);
-        partial += consume_chain<KIND, DT, R>(v);
+        partial += (Acc)consume_chain<KIND, DT, R>(v);
     }
 
     // Border: leftover whole tiles (fewer than R), leftover slots, the partial
@@ -317,7 +322,7 @@ __device__ __forceinline__ float stream_chains(const SumArgs &a, const uint4v *b
 #pragma unroll
             for (int r = 0; r < R; ++r)
                 v[r] = load_epilogue<DT>(a, base, x, p0 + (unsigned long long)r * TS + lane, carries);
-            partial += consume_chain<KIND, DT, R>(v);
+            partial += (Acc)consume_chain<KIND, DT, R>(v);
         }
     }
     return partial;
@@ -473,6 +478,9 @@ hipError_t launch_sum(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t
 hipError_t launch_sum_f16(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
 hipError_t launch_sum_bf16(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
 hipError_t launch_sum_f32(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
+
+// Binary64 accumulation mode (launch_wide.hip): fp16 input, double result.
+hipError_t launch_sum_wide(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
 
 // One level of the recurrence variant (recurrence.hip): a.chains groups of R
 // tiles, one binary16 value out per group; final_out (if not null) receives the

@@ -386,6 +386,56 @@ int recurrence_impl(const mfr_half *x, size_t n, float *out, int R, hipStream_t 
     return MFR_OK;
 }
 
+__global__ void store_zero_f64_kernel(double *out) { *out = 0.0; }
+
+// fp16 input, chains in fp32, everything after a chain in binary64, double result.
+int sum_wide_impl(const mfr_half *x, size_t n, double *out, const mfr_tuning *tin, hipStream_t stream)
+{
+    mfr_tuning in;
+    memset(&in, 0, sizeof in);
+    if (tin) in = *tin;
+    if (in.chain_R == 0) in.chain_R = 1;          // shortest fp32 accumulation per column
+    mfr_tuning t;
+    const int st = resolve_tuning(&in, MFR_DTYPE_F16, &t);
+    if (st != MFR_OK) return st;
+    if (t.kernel != MFR_KERNEL_MFMA || t.block_threads == 32) return MFR_ERR_INVALID_ARG;
+    if (!(t.chain_R == 1 || t.chain_R == 2 || t.chain_R == 4 || t.chain_R == 8)) return MFR_ERR_INVALID_ARG;
+    if (!out || ((size_t)out & 7u) != 0) return MFR_ERR_INVALID_ARG;
+    if (n > 0 && !x) return MFR_ERR_INVALID_ARG;
+    if (((size_t)x & 1u) != 0 || n > ((size_t)1 << 60)) return MFR_ERR_INVALID_ARG;
+    int dev = 0;
+    MFR_HIP(hipGetDevice(&dev));
+    DeviceInfo info;
+    const int ds = device_info(dev, &info);
+    if (ds != MFR_OK) return ds;
+    if (!info.gfx950) return MFR_ERR_UNSUPPORTED;
+    if (n == 0) {
+        hipLaunchKernelGGL(store_zero_f64_kernel, dim3(1), dim3(1), 0, stream, out);
+        MFR_HIP(hipGetLastError());
+        return MFR_OK;
+    }
+    Plan p;
+    plan_region(n, (size_t)x, 2, t, &p);
+    const long long grid = grid_blocks_for(p, t, info.cus, 1);
+    if (grid < 1) return MFR_ERR_INVALID_ARG;
+    const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES ||
+                              (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
+    Scratch s;
+    if (grid > 1) {
+        const int ss = get_scratch(dev, stream, 2 * (size_t)grid + 2, 1, &s);   // doubles live in the float array
+        if (ss != MFR_OK) return ss;
+    }
+    p.a.base = (const uint4v *)((size_t)x & ~(size_t)15);
+    p.a.x = x;
+    p.a.rows = 1;
+    p.a.partials = s.partials;          // hipMalloc'ed: 8-byte aligned
+    p.a.ticket = two_launches ? nullptr : s.tickets;
+    p.a.out = (float *)out;
+    const hipError_t e = mfr::launch_sum_wide(p, dim3((unsigned)grid), t, stream);
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return MFR_OK;
+}
+
 int sum_impl(const void *x, int dtype, size_t n, float *out, const mfr_tuning *tin, hipStream_t stream)
 {
     return sum_rows_impl(x, dtype, 1, n, n, out, tin, stream);
@@ -444,6 +494,16 @@ int mfr_sum_f16_rows(const mfr_half *x, size_t rows, size_t cols, size_t row_str
                      hipStream_t stream)
 {
     return sum_rows_impl(x, MFR_DTYPE_F16, rows, cols, row_stride, out, nullptr, stream);
+}
+
+int mfr_sum_f16_f64(const mfr_half *x, size_t n, double *out, hipStream_t stream)
+{
+    return sum_wide_impl(x, n, out, nullptr, stream);
+}
+
+int mfr_sum_f16_f64_ex(const mfr_half *x, size_t n, double *out, const mfr_tuning *t, hipStream_t stream)
+{
+    return sum_wide_impl(x, n, out, t, stream);
 }
 
 int mfr_sum_f16_recurrence(const mfr_half *x, size_t n, float *out, int chain_R, hipStream_t stream)

@@ -1,0 +1,136 @@
+"""GPU parity of the higher-accuracy mode (fp32 chains, binary64 everywhere after
+them, double result) against the fp64 oracle.  Tolerance from the arithmetic:
+only the 32 R fp32 additions inside an accumulator column round, so
+|gpu - oracle| <= (32 R + 4) 2^-24 sum|x_i|; integer-valued inputs are exact."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2001_05585_amd import binding as B            # noqa: E402
+from paper_2001_05585_amd import workloads as W          # noqa: E402
+from gpu_util import DeviceInput, stream_handle          # noqa: E402
+
+
+@pytest.fixture(scope="module", autouse=True)
+def need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; the HIP path has no fallback")
+    B.lib()
+
+
+class Out64:
+    def __init__(self, count):
+        self.tensor = torch.full((count,), -12345.0, dtype=torch.float64, device="cuda")
+
+    def ptr(self, i=0):
+        return self.tensor.data_ptr() + 8 * i
+
+    def get(self):
+        torch.cuda.synchronize()
+        return self.tensor.cpu().numpy()
+
+
+def wide_tunings():
+    out = [None]
+    for R, U in ((1, 1), (1, 8), (2, 4), (4, 2), (8, 1), (8, 2)):
+        for block, grid, combine in ((256, 0, 0), (64, 3, 1), (1024, 0, 2), (128, -1, 0), (512, 700, 0)):
+            out.append(B.make_tuning(block, R, grid, 0, U, 0, combine))
+    return out
+
+
+def bound(t, sum_abs):
+    R = t.chain_R if t is not None and t.chain_R else 1
+    return (32 * R + 4) * 2.0 ** -24 * sum_abs
+
+
+def test_integer_inputs_exact_beyond_fp32(oracle_lib):
+    n = (1 << 25) + 7                      # all-ones: the sum is not representable in binary32
+    d = DeviceInput(W.ones(n), 3)
+    ts = wide_tunings()
+    o = Out64(len(ts))
+    for i, t in enumerate(ts):
+        B.mfr_sum_f16_f64_ex(d.ptr, n, o.ptr(i), t, stream_handle())
+    assert np.all(o.get() == float(n))
+    x = W.small_integers((1 << 22) + 99, seed=5, lo=-2048, hi=2047)
+    want = oracle_lib.sum_f16(x)[0]
+    assert want == float(np.sum(x.astype(np.int64)))
+    d = DeviceInput(x, 1)
+    o = Out64(len(ts))
+    for i, t in enumerate(ts):
+        B.mfr_sum_f16_f64_ex(d.ptr, d.n, o.ptr(i), t, stream_handle())
+    assert np.all(o.get() == want)
+
+
+def test_every_small_n_exact():
+    full = W.small_integers(2100, seed=3)
+    want = np.concatenate([[0.0], np.cumsum(full.astype(np.float64))])
+    for shift in (0, 7):
+        d = DeviceInput(full, shift)
+        o = Out64(2101)
+        for n in range(2101):
+            B.mfr_sum_f16_f64(d.ptr, n, o.ptr(n), stream_handle())
+        assert np.array_equal(o.get(), want)
+
+
+@pytest.mark.parametrize("kind,n", [("uniform01", (1 << 24) + 7), ("normal", (1 << 24) + 7), ("uniform_pm1", 4_000_007),
+                                    ("uniform01", 1000)])
+def test_random_inputs_within_the_chain_rounding_bound(kind, n, oracle_lib):
+    x = W.generate(kind, n, 2024)
+    s, sa = oracle_lib.sum_f16(x)
+    d = DeviceInput(x)
+    ts = wide_tunings()
+    o = Out64(len(ts))
+    for i, t in enumerate(ts):
+        B.mfr_sum_f16_f64_ex(d.ptr, n, o.ptr(i), t, stream_handle())
+    r = o.get()
+    worst = 0.0
+    for i, t in enumerate(ts):
+        err = abs(r[i] - s)
+        assert err <= bound(t, sa), (kind, n, i, err, bound(t, sa))
+        worst = max(worst, err / sa)
+    # the standard fp32 result for comparison
+    o32 = torch.zeros(1, dtype=torch.float32, device="cuda")
+    B.mfr_sum_f16(d.ptr, n, o32.data_ptr(), stream_handle())
+    torch.cuda.synchronize()
+    print("%s n=%d: worst |err|/sum|x| binary64 mode %.3g, fp32 mode %.3g" % (kind, n, worst, abs(float(o32[0]) - s) / sa))
+
+
+def test_wide_mode_headline_size_and_repeatability(oracle_lib):
+    n = 1 << 28
+    x = W.generate("uniform01", n, W.config_seed(2))
+    s, sa, _ = oracle_lib.sum_f16_blocked(x, 16)
+    t = torch.from_numpy(x.view(np.int16)).cuda()
+    o = Out64(20)
+    for i in range(20):
+        B.mfr_sum_f16_f64(t.data_ptr(), n, o.ptr(i), stream_handle())
+    r = o.get()
+    assert np.all(r == r[0])
+    assert abs(r[0] - s) <= 36 * 2.0 ** -24 * sa
+    o32 = torch.zeros(1, dtype=torch.float32, device="cuda")
+    B.mfr_sum_f16(t.data_ptr(), n, o32.data_ptr(), stream_handle())
+    torch.cuda.synchronize()
+    e64, e32 = abs(r[0] - s) / sa, abs(float(o32[0]) - s) / sa
+    print("uniform n=2^28: |err|/sum|x| binary64 mode %.3g, fp32 mode %.3g" % (e64, e32))
+    assert e64 <= e32 + 1e-12
+
+
+def test_wide_argument_checks_and_zero():
+    d = DeviceInput(W.ones(64))
+    o = Out64(2)
+    L = B.lib()
+    INV = B.MFR_ERR_INVALID_ARG
+    assert L.mfr_sum_f16_f64(d.ptr, 64, o.ptr(0) + 4, None) == INV        # out not 8-byte aligned
+    assert L.mfr_sum_f16_f64(d.ptr + 1, 64, o.ptr(0), None) == INV
+    assert L.mfr_sum_f16_f64(None, 64, o.ptr(0), None) == INV
+    assert L.mfr_sum_f16_f64(d.ptr, 64, None, None) == INV
+    import ctypes
+    for kw in (dict(kernel=1), dict(block_threads=32), dict(chain_R=3), dict(kernel=2, split_permille=10)):
+        t = B.make_tuning(**kw)
+        assert L.mfr_sum_f16_f64_ex(d.ptr, 64, o.ptr(0), ctypes.byref(t), None) == INV
+    B.mfr_sum_f16_f64(d.ptr, 0, o.ptr(0), stream_handle())
+    B.mfr_sum_f16_f64(d.ptr, 64, o.ptr(1), stream_handle())
+    r = o.get()
+    assert r[0] == 0.0 and r[1] == 64.0
