@@ -120,3 +120,30 @@ def test_config5_size_sweep_up_to_2p30(oracle_lib):
         assert err <= TOL, (n, r, s)
         assert np.all(np.isfinite(r))
     print("config 5: worst |err|/sum|x| over %d sizes x 2 kernels = %.3g" % (len(sizes), worst))
+
+
+def test_more_than_2p32_elements(oracle_lib):
+    """64-bit sizes: n = 2^32 + 2^20 + 7 all-ones (8 GiB on the device, filled there).  The binary64
+    mode must return n exactly; the fp32 modes must be within tolerance of n; a one-hot near the
+    end must be found."""
+    n = (1 << 32) + (1 << 20) + 7
+    free, _ = torch.cuda.mem_get_info()
+    if free < 2 * n + (1 << 30):
+        pytest.skip("not enough device memory for an 8 GiB input")
+    x = torch.ones(n + 8, dtype=torch.float16, device="cuda")
+    ptr = x.data_ptr() + 2            # misaligned start
+    o = Outputs(3)
+    o64 = torch.zeros(1, dtype=torch.float64, device="cuda")
+    B.mfr_sum_f16(ptr, n, o.ptr(0), stream_handle())
+    B.mfr_sum_f16_ex(ptr, n, o.ptr(1), B.make_tuning(kernel=B.MFR_KERNEL_SHFL), stream_handle())
+    B.mfr_sum_f16_ex(ptr, n, o.ptr(2), B.make_tuning(512, 2, 5000), stream_handle())
+    B.mfr_sum_f16_f64(ptr, n, o64.data_ptr(), stream_handle())
+    r = o.get().astype(np.float64)
+    assert float(o64[0]) == float(n)
+    assert np.all(np.abs(r - n) <= TOL * n), r
+    x.zero_()
+    x[n - 3] = 1.0                    # element n - 4 of the call's range
+    B.mfr_sum_f16(ptr, n, o.ptr(0), stream_handle())
+    B.mfr_sum_f16(ptr, n - 4, o.ptr(1), stream_handle())
+    r = o.get()
+    assert r[0] == 1.0 and r[1] == 0.0
