@@ -7,7 +7,7 @@ combine, grid combine) of one resident 512 MiB buffer.  Several distinct
 buffers are rotated so that the 256 MB last-level cache cannot serve the reads.
 Prints ONE JSON line.
 
-Other modes (tables under gpurun_out/, not the JSON contract line):
+Other modes (they write tables to the results folder, not the JSON contract line):
   --sweep config2   block x R grid at n = 2^26 (+ all-ones 2^24 exactness)
   --sweep config5   n = 2^16 .. 2^30 (+7), MFMA kernel and shuffle kernel
 """
@@ -222,9 +222,9 @@ def main():
     ap.add_argument("--combine", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic", action="store_true", help="short run for rocprofv3 --pmc counters")
-    ap.add_argument("--sweep", choices=["config2", "config5", "tune", "types", "rows", "tune_f32", "split", "variants", "wide"], default=None)
+    ap.add_argument("--sweep", choices=["config2", "config5", "tune", "types", "rows", "tune_f32", "split", "variants", "wide", "combine"], default=None)
     ap.add_argument("--quick", type=int, default=0, help="sweeps: keep every k-th combination")
-    ap.add_argument("--out", default=None, help="file for sweep tables (default gpurun_out/<sweep>.txt)")
+    ap.add_argument("--out", default=None, help="file for sweep tables (default: <results folder>/<sweep>.txt)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (--gpus 1); the reduction shards trivially "

@@ -13,6 +13,7 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
+RESULTS_DIR = os.environ.get("MFR_RESULTS_DIR", os.path.join(ROOT, "gpurun_out"))
 HBM_PEAK_GBPS = 8000.0
 
 
@@ -47,7 +48,7 @@ class Timer:
 
 
 def open_out(args, name):
-    path = args.out or os.path.join(ROOT, "gpurun_out", name)
+    path = args.out or os.path.join(RESULTS_DIR, name)
     os.makedirs(os.path.dirname(path), exist_ok=True)
     return open(path, "w")
 
@@ -323,25 +324,51 @@ def wide(args, torch, np, B, W):
                                                                       100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS, float(out64[0].item())))
 
 
+def combine(args, torch, np, B, W):
+    """Single-launch (two-level tickets) against two-launch grid combine over the number of blocks."""
+    n = 1 << 28
+    x = W.generate("normal", n, W.config_seed(3))
+    bufs = device_buffers(torch, np, x, 4)
+    timer = Timer(torch, B)
+    heat(timer, bufs, n, 0.5)
+    with open_out(args, "combine.txt") as f:
+        emit(f, "# n=2^28, 4 rotating buffers; block grid(blocks) in_flight_KiB_per_wave single_launch_us two_launch_us")
+        for block in (64, 256):
+            for grid in (256, 512, 1024, 2048, 4096, 8192, 16384, 65536):
+                waves = grid * block // 64
+                per_wave = max(1, min(8, 8192 // waves))      # keep about 8 MiB in flight
+                R, U = (4, 2) if per_wave == 8 else ((4, 1) if per_wave == 4 else ((2, 1) if per_wave == 2 else (1, 1)))
+                res = []
+                for mode in (B.MFR_COMBINE_SINGLE_LAUNCH, B.MFR_COMBINE_TWO_LAUNCHES):
+                    t = B.make_tuning(block, R, grid, 0, U, 0, mode)
+                    res.append(timer.run(bufs, n, t, args.steps, 5) * 1e6)
+                emit(f, "%d %d %d %.2f %.2f" % (block, grid, R * U, res[0], res[1]))
+
+
 def rows(args, torch, np, B, W):
     """Batched form: rows x cols fp16 with rows * cols = 2^28 (512 MiB), 4 rotating buffers."""
     total = 1 << 28
     host = torch.from_numpy(W.generate("normal", total, 3).view(np.int16))
     bufs = [host.cuda() for _ in range(4)]
     timer = Timer(torch, B)
-    out = torch.zeros(1 << 21, dtype=torch.float32, device="cuda")
+    out = torch.zeros(1 << 23, dtype=torch.float32, device="cuda")
     with open_out(args, "rows.txt") as f:
         emit(f, "# rows x cols = 2^28 fp16 (512 MiB per call), 4 rotating buffers; tuning 'default' = library choice")
         emit(f, "# rows cols tuning us Gelem/s GB/s pct_of_8TB/s")
-        for lr in (0, 4, 8, 12, 14, 16, 18, 20):
+        for lr in (0, 4, 8, 12, 14, 16, 17, 18, 19, 20, 21, 22):
             r, c = 1 << lr, total >> lr
             cands = [("default", None)]
+            if lr >= 16:
+                cands.append(("default,base+2B", "shifted"))     # rows not 16-byte aligned: one wave per row
             if args.quick != 1:
                 cands += [("b%d_R%d_U%d" % (b, R, U), B.make_tuning(b, R, 0, 0, U)) for b, R, U in
                           ((64, 1, 8), (64, 1, 4), (64, 2, 4), (64, 4, 2), (128, 1, 4), (256, 1, 2), (256, 1, 8), (64, 1, 1), (64, 1, 2))]
             for name, t in cands:
+                off, rr = (2, r - 1) if t == "shifted" else (0, r)
+                t = None if t == "shifted" else t
+
                 def call(i):
-                    B.mfr_sum_rows_ex(bufs[i % 4].data_ptr(), B.MFR_DTYPE_F16, r, c, c, out.data_ptr(), t, timer.stream)
+                    B.mfr_sum_rows_ex(bufs[i % 4].data_ptr() + off, B.MFR_DTYPE_F16, rr, c, c, out.data_ptr(), t, timer.stream)
                 for i in range(5):
                     call(i)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -364,4 +391,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants, "wide": wide}[args.sweep](args, torch, np, B, W)
+    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants, "wide": wide, "combine": combine}[args.sweep](args, torch, np, B, W)

@@ -65,8 +65,9 @@ enum {
 /* How the block partials become one value (Section 5.2 uses float atomics on
  * one location; both modes here add them in index order instead). */
 enum {
-    MFR_COMBINE_AUTO = 0,          /* single launch for grids up to 320 blocks, else two */
-    MFR_COMBINE_SINGLE_LAUNCH = 1, /* the block that draws the last ticket adds the partials */
+    MFR_COMBINE_AUTO = 0,          /* single launch for grids up to 2048 blocks, else two */
+    MFR_COMBINE_SINGLE_LAUNCH = 1, /* the block that draws the last ticket adds the partials
+                                      (grids above 65536 blocks still use two launches) */
     MFR_COMBINE_TWO_LAUNCHES = 2   /* a second one-block kernel adds the partials */
 };
 

@@ -74,8 +74,7 @@ __global__ void __launch_bounds__(1024) sum_kernel_wide(const SumArgs a)
                                                         (unsigned long long)__double_as_longlong(block_sum),
                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         asm volatile("" : "+v"(prev) : : "memory");
-        const unsigned int old = atomicInc(a.ticket, gridDim.x - 1u);
-        is_last = (old == gridDim.x - 1u) ? 1u : 0u;
+        is_last = draw_ticket(a.ticket, blockIdx.x, gridDim.x) ? 1u : 0u;
     }
     __syncthreads();
     if (!is_last) return;

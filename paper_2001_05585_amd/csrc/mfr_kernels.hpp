@@ -192,6 +192,36 @@ __device__ __forceinline__ double block_sum_f64(const float *partials, unsigned 
     return total;
 }
 
+// Ticket for `blocks` blocks.  Up to kTicketFlat blocks draw from one counter
+// (word 0).  Larger grids draw in two levels, because same-address atomics
+// serialise: word kTicketStride * (1 + g) is the counter of group g of
+// kTicketGroup blocks (counters on separate 64-byte lines), and word 0 the top
+// counter, drawn by the block that completes its group.  Returns true for
+// exactly one caller: the one after which every other block has drawn.
+constexpr unsigned int kTicketFlat = 512;
+constexpr unsigned int kTicketGroup = 32;
+constexpr unsigned int kTicketStride = 16;
+
+__host__ __device__ inline unsigned long long ticket_words(unsigned int blocks)
+{
+    if (blocks <= kTicketFlat) return kTicketStride;
+    return (unsigned long long)kTicketStride * (1u + (blocks + kTicketGroup - 1u) / kTicketGroup);
+}
+
+__device__ __forceinline__ bool draw_ticket(unsigned int *tickets, unsigned int block, unsigned int blocks)
+{
+    if (blocks <= kTicketFlat) return atomicInc(tickets, blocks - 1u) == blocks - 1u;
+    const unsigned int groups = (blocks + kTicketGroup - 1u) / kTicketGroup;
+    const unsigned int g = block / kTicketGroup;
+    const unsigned int first = g * kTicketGroup;
+    const unsigned int size = blocks - first < kTicketGroup ? blocks - first : kTicketGroup;
+    if (size > 1u) {
+        const unsigned int old = atomicInc(tickets + kTicketStride * (1u + g), size - 1u);
+        if (old != size - 1u) return false;
+    }
+    return atomicInc(tickets, groups - 1u) == groups - 1u;
+}
+
 // ------------------------------------------------------ tile consumers ---
 
 // One tile of the chain: C = 1 x M + C  (Section 4.3).  A is the all-ones
@@ -403,9 +433,11 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
     // Single-launch combine.  A release fence at device scope costs a write-back
     // of the whole L2 per block, so ordering is obtained from the atomics
     // themselves: the partial is published with a returning device-scope
-    // exchange, and the ticket is drawn only after that exchange has returned,
-    // i.e. after it has been performed at the device's coherence point.  The
-    // block that draws the last ticket therefore finds every partial there.
+    // exchange, and a ticket is drawn only after that exchange has returned,
+    // i.e. after it has been performed at the device's coherence point.
+    // The block that draws the last ticket therefore finds every partial of
+    // the row published.  All counters wrap to zero by themselves, ready for
+    // the next call.
     if (threadIdx.x == 0) {
         unsigned int prev = __hip_atomic_exchange((unsigned int *)&partials[blockIdx.x],
                                                   __float_as_uint(block_sum), __ATOMIC_RELAXED,
@@ -413,9 +445,7 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
         // the exchange result must be in a register (waits for it) and no later
         // memory operation may be moved above this point
         asm volatile("" : "+v"(prev) : : "memory");
-        // wraps to 0 after the last block, so the counter is ready for the next call
-        const unsigned int old = atomicInc(a.ticket + row, gridDim.x - 1u);
-        is_last = (old == gridDim.x - 1u) ? 1u : 0u;
+        is_last = draw_ticket(a.ticket + row * ticket_words(gridDim.x), blockIdx.x, gridDim.x) ? 1u : 0u;
     }
     __syncthreads();
     if (!is_last) return;
@@ -481,6 +511,12 @@ hipError_t launch_sum_f32(const Plan &p, dim3 grid, const mfr_tuning &t, hipStre
 
 // Binary64 accumulation mode (launch_wide.hip): fp16 input, double result.
 hipError_t launch_sum_wide(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
+
+// Many short rows, sixteen row sums per MFMA chain (rows16.hip); 16-bit types,
+// x 16-byte aligned, row_stride a multiple of 8 elements.
+hipError_t launch_rows16(int dtype, const void *x, unsigned long long rows, unsigned long long cols,
+                         unsigned long long row_stride, float *out, unsigned grid, unsigned block,
+                         int tiles_in_flight, hipStream_t stream);
 
 // One level of the recurrence variant (recurrence.hip): a.chains groups of R
 // tiles, one binary16 value out per group; final_out (if not null) receives the

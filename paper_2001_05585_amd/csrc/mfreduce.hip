@@ -69,9 +69,11 @@ constexpr int kDefaultBlock = 256;
 constexpr int kDefaultR = 4;
 constexpr int kDefaultR_f32 = 8;               // four MFMAs per tile: one long chain overlaps them with the loads
 constexpr int kDefaultWavesPerCU = 4;          // one wave per SIMD
-constexpr long long kTicketMaxBlocks = 320;    // larger grids combine with a second launch
+constexpr long long kTicketMaxBlocks = 2048;   // AUTO: larger grids combine with a second launch
+constexpr long long kTicketHardMax = 65536;    // single-launch combine is not offered beyond this
 constexpr size_t kMaxRowsPerLaunch = 65535;    // gridDim.y limit
 constexpr size_t kWaveRowBytes = 8192;         // rows shorter than this get a wave each when there are many
+constexpr size_t kRows16Bytes = 1536;          // still shorter rows of 16-bit types: 16 rows per MFMA chain
 
 int default_in_flight(int R)
 {
@@ -268,6 +270,20 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     // rows can share one launch when they all have the same 16-byte phase
     const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
 
+    // Many short rows of a 16-bit type with aligned rows: sixteen rows per MFMA chain.
+    if (tin == nullptr && rows >= (size_t)info.cus * 16 && cols * esize < kRows16Bytes && esize == 2 &&
+        ((size_t)x & 15u) == 0 && (row_stride & 7u) == 0) {
+        const size_t groups = (rows + 15) / 16;
+        const size_t tiles = (cols + 31) / 32;
+        const int in_flight = tiles >= 8 ? 8 : (tiles >= 4 ? 4 : (tiles >= 2 ? 2 : 1));
+        size_t grid = (size_t)info.cus;                      // 256-thread blocks: one wave per SIMD
+        if (grid * 4 > groups) grid = (groups + 3) / 4;
+        const hipError_t e = mfr::launch_rows16(dtype, x, rows, cols, row_stride, out, (unsigned)grid, 256, in_flight,
+                                                stream);
+        if (e != hipSuccess) return hip_fail(e, "rows16 launch");
+        return MFR_OK;
+    }
+
     // Many short rows: every wave reduces a row of its own (no cross-wave or
     // cross-block combine); chosen by the library only, with its own geometry.
     const bool wave_rows = same_phase && tin == nullptr && cols * esize < kWaveRowBytes &&
@@ -288,11 +304,12 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     plan_region(cols, (size_t)x, esize, t, &p);
     const long long grid = wave_rows ? 1 : grid_blocks_for(p, t, info.cus, batch);
     if (grid < 1) return MFR_ERR_INVALID_ARG;
-    const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES ||
+    const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
     Scratch s;
     if (grid > 1) {
-        const int ss = get_scratch(dev, stream, (size_t)grid * batch, batch, &s);
+        const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid) * batch;
+        const int ss = get_scratch(dev, stream, (size_t)grid * batch, ticket_words, &s);
         if (ss != MFR_OK) return ss;
     }
 
@@ -418,11 +435,12 @@ int sum_wide_impl(const mfr_half *x, size_t n, double *out, const mfr_tuning *ti
     plan_region(n, (size_t)x, 2, t, &p);
     const long long grid = grid_blocks_for(p, t, info.cus, 1);
     if (grid < 1) return MFR_ERR_INVALID_ARG;
-    const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES ||
+    const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
     Scratch s;
     if (grid > 1) {
-        const int ss = get_scratch(dev, stream, 2 * (size_t)grid + 2, 1, &s);   // doubles live in the float array
+        const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid);
+        const int ss = get_scratch(dev, stream, 2 * (size_t)grid + 2, ticket_words, &s);   // doubles live in the float array
         if (ss != MFR_OK) return ss;
     }
     p.a.base = (const uint4v *)((size_t)x & ~(size_t)15);

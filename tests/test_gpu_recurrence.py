@@ -101,7 +101,8 @@ def test_recurrence_argument_checks():
 
 def test_error_vs_n_table(oracle_lib):
     """Section 5.4's error experiment on this GPU: % error |gpu - cpu| / |cpu| against the fp64
-    oracle over n, for normal(0,1) and uniform[0,1) inputs; written to gpurun_out/variants_error.txt."""
+    oracle over n, for normal(0,1) and uniform[0,1) inputs; also written to variants_error.txt in the
+    results folder."""
     import os
     lines = ["# kind n cpu_fp64_sum single_pass_err% recurrence_R4_err% recurrence_R5_err% shuffle_err% single_pass_err/sum|x|"]
     for kind, cfg in (("normal", 3), ("uniform01", 2)):
@@ -128,7 +129,7 @@ def test_error_vs_n_table(oracle_lib):
                     assert abs(r[j] - s) <= RM.error_bound(sa, n, R)
     text = "\n".join(lines)
     print(text)
-    outdir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    outdir = os.environ.get("MFR_RESULTS_DIR", os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out"))
     try:
         os.makedirs(outdir, exist_ok=True)
         with open(os.path.join(outdir, "variants_error.txt"), "w") as f:

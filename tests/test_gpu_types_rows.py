@@ -196,8 +196,38 @@ def test_many_short_rows_one_wave_each(cols, oracle_lib):
         assert np.array_equal(got.astype(np.float64), want), (cols, shift, got[:4], want[:4])
     f = W.generate_f32("normal", rows * stride, 1234 + cols)
     s, sa = oracle_lib.sum_rows(f.reshape(rows, stride)[:, :cols], "f32")
-    got = rows_call(TypedInput(f.view(np.uint32), 0).ptr, B.MFR_DTYPE_F32, rows, cols, stride).astype(np.float64)
+    df = TypedInput(f.view(np.uint32), 0)          # keep the device buffer alive across the call
+    got = rows_call(df.ptr, B.MFR_DTYPE_F32, rows, cols, stride).astype(np.float64)
     assert (np.abs(got - s) <= TOL * sa).all()
+
+
+@pytest.mark.parametrize("cols", [1, 5, 31, 32, 33, 37, 64, 65, 100, 128, 129, 256, 700, 767])
+def test_many_short_rows_sixteen_per_mfma_chain(cols, oracle_lib):
+    # library defaults, >= 4096 rows, 16-byte aligned rows of a 16-bit type: 16 row sums per MFMA chain
+    rows = 5003
+    stride = (cols + 7) // 8 * 8 + (8 if cols % 16 else 0)
+    flat = W.small_integers(rows * stride + 16, seed=cols + 1)
+    x2d = np.stack([flat[r * stride:r * stride + cols] for r in range(rows)])
+    want, _ = oracle_lib.sum_rows(x2d)
+    d = TypedInput(flat.view(np.uint16), 0)
+    got = rows_call(d.ptr, B.MFR_DTYPE_F16, rows, cols, stride)
+    assert np.array_equal(got.astype(np.float64), want), (cols, np.nonzero(got != want)[0][:5])
+    # bfloat16, random values
+    f = W.generate_f32("normal", rows * stride, 99 + cols)
+    b = W.to_bf16_bits(f)
+    s, sa = oracle_lib.sum_rows(b.reshape(rows, stride)[:, :cols], "bf16")
+    db = TypedInput(b, 0)                          # keep the device buffer alive across the call
+    got = rows_call(db.ptr, B.MFR_DTYPE_BF16, rows, cols, stride).astype(np.float64)
+    assert (np.abs(got - s) <= TOL * sa + 1e-30).all()
+    # special values stay in their own row
+    y = flat.view(np.uint16).copy()
+    y[7 * stride + cols - 1] = 0x7C00
+    y[4000 * stride] = 0x7E00
+    dy = TypedInput(y, 0)
+    got = rows_call(dy.ptr, B.MFR_DTYPE_F16, rows, cols, stride).astype(np.float64)
+    assert got[7] == math.inf and math.isnan(got[4000])
+    keep = np.ones(rows, dtype=bool); keep[[7, 4000]] = False
+    assert np.array_equal(got[keep], want[keep])
 
 
 def test_rows_random_inputs_and_types(oracle_lib):
