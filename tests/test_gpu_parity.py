@@ -315,6 +315,36 @@ def test_two_streams_overlap(oracle_lib):
     assert within_tolerance(ra[0], sa_, saa) and within_tolerance(rb[0], sb_, sba)
 
 
+def test_host_threads_on_their_own_streams(oracle_lib):
+    import threading
+    inputs = [W.generate("uniform_pm1", (1 << 20) + 17 * k, 200 + k) for k in range(4)]
+    devs = [DeviceInput(x, k) for k, x in enumerate(inputs)]
+    outs = [Outputs(40) for _ in inputs]
+    streams = [torch.cuda.Stream() for _ in inputs]
+    errors = []
+
+    def work(k):
+        try:
+            for i in range(40):
+                t = None if i % 2 else B.make_tuning(128, 2, 300 + k)      # exercises scratch growth too
+                B.mfr_sum_f16_ex(devs[k].ptr, devs[k].n, outs[k].ptr(i), t, streams[k].cuda_stream)
+        except Exception as e:                                             # pragma: no cover
+            errors.append(e)
+
+    torch.cuda.synchronize()
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    for k, x in enumerate(inputs):
+        s, sa = oracle_lib.sum_f16(x)
+        r = outs[k].get().astype(np.float64)
+        assert np.all(np.abs(r - s) <= TOL * sa)
+        assert np.all(r[0::2] == r[0]) and np.all(r[1::2] == r[1])
+
+
 # ----------------------------------------------------- degenerate cases ---
 
 def test_n_zero_writes_zero():
