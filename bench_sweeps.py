@@ -132,16 +132,16 @@ def time_rotating(timer, ptrs, n, tuning, steps, warmup):
 
 def config2(args, torch, np, B, W):
     """Block x R cells (Section 5.2's configuration experiment) at n = 2^26, uniform [0,1)."""
-    n = 1 << 26
+    n = args.n if args.n != 1 << 28 else 1 << 26     # --n overrides (e.g. 2^20, the size of the paper's experiment)
     x = W.generate("uniform01", n, W.config_seed(2))
-    copies = 16                                     # 2 GiB in rotation: the last-level cache cannot hold it
+    copies = max(16, min(512, (1 << 31) // (2 * n)))  # 2 GiB in rotation: the last-level cache cannot hold it
     bufs = device_buffers(torch, np, x, copies)
     ptrs = [b.data_ptr() for b in bufs]
     ones = torch.ones(1 << 24, dtype=torch.float16, device="cuda")
     timer = Timer(torch, B)
     heat(timer, bufs, n)
     with open_out(args, "config2.txt") as f:
-        emit(f, "# config 2: n=2^26 uniform[0,1), MFMA-chain kernel; rotating %d x 128 MiB buffers (cold) and one buffer (warm, cache-resident)" % copies)
+        emit(f, "# config 2: n=%d uniform[0,1), MFMA-chain kernel; rotating %d x %.3f MiB buffers (cold) and one buffer (warm, cache-resident)" % (n, copies, 2 * n / 2 ** 20))
         emit(f, "# grid: persistent = MFR_GRID_AUTO, one-chain = one chain of R MFMAs per wave (the paper's geometry)")
         emit(f, "# block R grid_mode blocks cold_us cold_Gelem/s cold_GB/s cold_pct warm_us warm_GB/s ones_2p24")
         for grid_mode, gname in ((B.MFR_GRID_AUTO, "persistent"), (B.MFR_GRID_ONE_CHAIN, "one-chain")):

@@ -74,7 +74,7 @@ __global__ void __launch_bounds__(1024) sum_kernel_wide(const SumArgs a)
                                                         (unsigned long long)__double_as_longlong(block_sum),
                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         asm volatile("" : "+v"(prev) : : "memory");
-        is_last = draw_ticket(a.ticket, blockIdx.x, gridDim.x) ? 1u : 0u;
+        is_last = draw_ticket(a.ticket, blockIdx.x, gridDim.x, a.ticket_flat != 0u) ? 1u : 0u;
     }
     __syncthreads();
     if (!is_last) return;

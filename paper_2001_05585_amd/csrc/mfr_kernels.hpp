@@ -53,6 +53,8 @@ struct SumArgs {
     unsigned long long rows;     // rows of this launch
     unsigned long long split_chains;  // MFR_KERNEL_SPLIT: chains [0, split_chains) take the MFMA path ...
     unsigned long long split_waves;   // ... on waves [0, split_waves); the rest is conventional
+    unsigned long long ticket_stride;  // ticket words per row
+    unsigned int ticket_flat;    // nonzero: one ticket counter per row, else two levels
     unsigned int wave_rows;      // nonzero: every wave reduces a row of its own (short rows)
     unsigned int head;           // elements of slot 0 that lie before x
     float *partials;             // gridDim.x per row
@@ -192,25 +194,26 @@ __device__ __forceinline__ double block_sum_f64(const float *partials, unsigned 
     return total;
 }
 
-// Ticket for `blocks` blocks.  Up to kTicketFlat blocks draw from one counter
-// (word 0).  Larger grids draw in two levels, because same-address atomics
-// serialise: word kTicketStride * (1 + g) is the counter of group g of
-// kTicketGroup blocks (counters on separate 64-byte lines), and word 0 the top
-// counter, drawn by the block that completes its group.  Returns true for
-// exactly one caller: the one after which every other block has drawn.
-constexpr unsigned int kTicketFlat = 512;
+// Ticket for `blocks` blocks.  Flat: all blocks draw from one counter (word
+// 0); same-address atomics serialise (about 8 ns each), which is hidden when
+// the blocks finish at different times (long inputs) and exposed when they
+// finish together (short inputs).  Two-level: word kTicketStride * (1 + g) is
+// the counter of group g of kTicketGroup blocks (counters on separate 64-byte
+// lines), and word 0 the top counter, drawn by the block that completes its
+// group.  Returns true for exactly one caller: the one after which every other
+// block has drawn.  The host chooses the form and sizes the counters.
 constexpr unsigned int kTicketGroup = 32;
 constexpr unsigned int kTicketStride = 16;
 
-__host__ __device__ inline unsigned long long ticket_words(unsigned int blocks)
+inline unsigned long long ticket_words(unsigned int blocks, bool flat)
 {
-    if (blocks <= kTicketFlat) return kTicketStride;
+    if (flat) return kTicketStride;
     return (unsigned long long)kTicketStride * (1u + (blocks + kTicketGroup - 1u) / kTicketGroup);
 }
 
-__device__ __forceinline__ bool draw_ticket(unsigned int *tickets, unsigned int block, unsigned int blocks)
+__device__ __forceinline__ bool draw_ticket(unsigned int *tickets, unsigned int block, unsigned int blocks, bool flat)
 {
-    if (blocks <= kTicketFlat) return atomicInc(tickets, blocks - 1u) == blocks - 1u;
+    if (flat) return atomicInc(tickets, blocks - 1u) == blocks - 1u;
     const unsigned int groups = (blocks + kTicketGroup - 1u) / kTicketGroup;
     const unsigned int g = block / kTicketGroup;
     const unsigned int first = g * kTicketGroup;
@@ -219,6 +222,7 @@ __device__ __forceinline__ bool draw_ticket(unsigned int *tickets, unsigned int 
         const unsigned int old = atomicInc(tickets + kTicketStride * (1u + g), size - 1u);
         if (old != size - 1u) return false;
     }
+    if (groups == 1u) return true;
     return atomicInc(tickets, groups - 1u) == groups - 1u;
 }
 
@@ -445,7 +449,7 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
         // the exchange result must be in a register (waits for it) and no later
         // memory operation may be moved above this point
         asm volatile("" : "+v"(prev) : : "memory");
-        is_last = draw_ticket(a.ticket + row * ticket_words(gridDim.x), blockIdx.x, gridDim.x) ? 1u : 0u;
+        is_last = draw_ticket(a.ticket + row * a.ticket_stride, blockIdx.x, gridDim.x, a.ticket_flat != 0u) ? 1u : 0u;
     }
     __syncthreads();
     if (!is_last) return;

@@ -190,6 +190,15 @@ long long grid_blocks_for(const Plan &p, const mfr_tuning &t, int cus, size_t ro
     return (long long)g;
 }
 
+// One counter for all blocks when the grid is small, or when each wave has so
+// much to do that the blocks do not finish together; two levels otherwise.
+bool ticket_flat_for(long long grid, const Plan &p)
+{
+    if (grid <= 64) return true;
+    const unsigned long long per_wave = p.chains / ((unsigned long long)grid * (unsigned)p.waves);
+    return grid <= 512 && per_wave >= 32;
+}
+
 int grow(void **mem, size_t *capacity, size_t need, size_t elem, size_t floor_count, bool zero, hipStream_t stream)
 {
     if (*capacity >= need) return MFR_OK;
@@ -306,9 +315,10 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     if (grid < 1) return MFR_ERR_INVALID_ARG;
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
+    const bool ticket_flat = ticket_flat_for(grid, p);
     Scratch s;
     if (grid > 1) {
-        const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid) * batch;
+        const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid, ticket_flat) * batch;
         const int ss = get_scratch(dev, stream, (size_t)grid * batch, ticket_words, &s);
         if (ss != MFR_OK) return ss;
     }
@@ -336,6 +346,8 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
         p.a.wave_rows = wave_rows ? 1u : 0u;
         p.a.partials = s.partials;
         p.a.ticket = two_launches ? nullptr : s.tickets;
+        p.a.ticket_stride = mfr::ticket_words((unsigned)grid, ticket_flat);
+        p.a.ticket_flat = ticket_flat ? 1u : 0u;
         p.a.out = out + r0;
         const size_t grid_y = (nr + rows_per_block - 1) / rows_per_block;
         const hipError_t e = launch_dtype(dtype, p, dim3((unsigned)grid, (unsigned)grid_y), t, stream);
@@ -437,9 +449,10 @@ int sum_wide_impl(const mfr_half *x, size_t n, double *out, const mfr_tuning *ti
     if (grid < 1) return MFR_ERR_INVALID_ARG;
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
+    const bool ticket_flat = ticket_flat_for(grid, p);
     Scratch s;
     if (grid > 1) {
-        const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid);
+        const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid, ticket_flat);
         const int ss = get_scratch(dev, stream, 2 * (size_t)grid + 2, ticket_words, &s);   // doubles live in the float array
         if (ss != MFR_OK) return ss;
     }
@@ -448,6 +461,7 @@ int sum_wide_impl(const mfr_half *x, size_t n, double *out, const mfr_tuning *ti
     p.a.rows = 1;
     p.a.partials = s.partials;          // hipMalloc'ed: 8-byte aligned
     p.a.ticket = two_launches ? nullptr : s.tickets;
+    p.a.ticket_flat = ticket_flat ? 1u : 0u;
     p.a.out = (float *)out;
     const hipError_t e = mfr::launch_sum_wide(p, dim3((unsigned)grid), t, stream);
     if (e != hipSuccess) return hip_fail(e, "kernel launch");

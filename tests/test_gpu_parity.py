@@ -315,6 +315,31 @@ def test_two_streams_overlap(oracle_lib):
     assert within_tolerance(ra[0], sa_, saa) and within_tolerance(rb[0], sb_, sba)
 
 
+def test_alternating_inputs_never_see_the_previous_calls_partials():
+    # the scratch of a stream is reused by every call: a partial left over from the previous call must
+    # never be read.  Two inputs with different exact sums alternate on one stream.
+    n = (1 << 22) + 640
+    a, b = DeviceInput(W.ones(n)), DeviceInput(W.constant(n, 3.0), 1)
+    for block, R, grid in ((256, 4, 256), (128, 2, 700), (64, 1, 2048), (64, 1, 8192)):
+        for combine in (B.MFR_COMBINE_SINGLE_LAUNCH, B.MFR_COMBINE_TWO_LAUNCHES):
+            t = B.make_tuning(block, R, grid, 0, 0, 0, combine)
+            o = Outputs(1500)
+            for i in range(1500):
+                d = a if i % 2 == 0 else b
+                B.mfr_sum_f16_ex(d.ptr, n, o.ptr(i), t, stream_handle())
+            r = o.get()
+            assert np.all(r[0::2] == float(n)) and np.all(r[1::2] == 3.0 * n), (block, R, grid, combine)
+
+
+def test_single_launch_combine_with_65536_blocks():
+    n = 1 << 25
+    d = DeviceInput(W.ones(n))
+    o = Outputs(6)
+    for i, (grid, combine) in enumerate(((65536, 1), (65536, 2), (65535, 1), (40000, 1), (513, 1), (65537, 1))):
+        B.mfr_sum_f16_ex(d.ptr, n, o.ptr(i), B.make_tuning(64, 1, grid, 0, 1, 0, combine), stream_handle())
+    assert np.all(o.get() == float(n))
+
+
 def test_host_threads_on_their_own_streams(oracle_lib):
     import threading
     inputs = [W.generate("uniform_pm1", (1 << 20) + 17 * k, 200 + k) for k in range(4)]
