@@ -180,6 +180,22 @@ def config5(args, torch, np, B, W):
                     dt = time_rotating(timer, ptrs, n, t, steps, 5)
                     emit(f, "%d %s %d %.2f %.2f %.1f %.2f" % (n, kname, B.mfr_grid_for(n, ptrs[0], t), dt * 1e6,
                                                             n / dt / 1e9, 2 * n / dt / 1e9, 100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS))
+                # context only: PyTorch's own reduction (fp32 accumulation) on the same rotating slices
+                halves = arena.view(torch.float16)
+                stride_e = (ptrs[1] - ptrs[0]) // 2 if len(ptrs) > 1 else 0
+                views = [halves[i * stride_e:i * stride_e + n] for i in range(len(ptrs))]
+                steps = max(10, min(args.steps * 4, int(2e-2 / max(2 * n / 6e12, 4e-6))))
+                for i in range(5):
+                    torch.sum(views[i % len(views)], dtype=torch.float32)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(steps):
+                    torch.sum(views[(i + 5) % len(views)], dtype=torch.float32)
+                e1.record()
+                torch.cuda.synchronize()
+                dt = e0.elapsed_time(e1) * 1e-3 / steps
+                emit(f, "%d %s %d %.2f %.2f %.1f %.2f" % (n, "torch.sum(context)", 0, dt * 1e6, n / dt / 1e9, 2 * n / dt / 1e9,
+                                                        100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS))
 
 
 def types(args, torch, np, B, W):
