@@ -34,7 +34,9 @@ CASES = [
 
 
 def main():
-    lines = ["# config kind n sum sum_abs   (fp64 Kahan oracle, C99 hex floats; seed = 20010558500 + config)"]
+    lines = ["# R(X) = sum_i x_i (paper Section 4, definition of the arithmetic reduction) and sum_i |x_i| of the seeded",
+             "# fp16 workloads, as computed by the CPU oracle (fp64 Kahan); written by tests/golden/make_oracle_sums.py.",
+             "# config kind n sum sum_abs   (C99 hex floats; seed = 20010558500 + config)"]
     for cfg, kind, n in CASES:
         x = W.generate(kind, n, W.config_seed(cfg))
         if n <= 1 << 26:
