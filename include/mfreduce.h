@@ -80,7 +80,7 @@ typedef struct mfr_tuning {
                              from zero before it is folded to an fp32 partial (the paper's R).
                              SHFL kernel: 16-byte loads per lane accumulated per group */
     int grid_blocks;      /* MFR_GRID_AUTO, MFR_GRID_ONE_CHAIN, or an explicit count >= 1 */
-    int kernel;           /* MFR_KERNEL_MFMA or MFR_KERNEL_SHFL */
+    int kernel;           /* MFR_KERNEL_MFMA, MFR_KERNEL_SHFL or MFR_KERNEL_SPLIT */
     int chains_in_flight; /* 1, 2, 4 or 8 independent chains whose loads are issued before
                              any is consumed (memory-level parallelism); chain_R *
                              chains_in_flight must not exceed 16 */
@@ -106,7 +106,10 @@ typedef struct mfr_tuning {
  * IEEE special values propagate (NaN in => NaN; +Inf and -Inf => NaN).
  * Scratch (block partials + a ticket counter) is owned by the library, one
  * per (device, stream), allocated on first use and kept until unload; calls
- * on different streams may overlap, calls on one stream serialise.
+ * on different streams may overlap, calls on one stream serialise.  A call
+ * that has to allocate or enlarge its stream's scratch calls hipMalloc (and
+ * synchronises the stream before freeing a smaller one); later calls with a
+ * grid no larger than before allocate nothing.
  */
 int mfr_sum_f16(const mfr_half *x, size_t n, float *out, hipStream_t stream);
 
