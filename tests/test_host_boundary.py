@@ -31,6 +31,18 @@ def test_library_exports_every_declared_function():
     assert set(names) == set(B.EXPORTS)
 
 
+def test_header_is_plain_c_and_the_library_links(tmp_path):
+    import subprocess
+    exe = str(tmp_path / "c_abi_check")
+    src = os.path.join(ROOT, "tests", "c_abi_check.c")
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    src, "-o", exe, "-L", libdir, "-lmfreduce", "-Wl,-rpath," + libdir,
+                    "-Wl,-rpath-link,/opt/rocm/lib"], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True)
+    assert "c abi ok" in out.stdout
+
+
 def test_version_and_strings():
     assert B.mfr_version() >= 100
     assert B.mfr_strerror(B.MFR_OK) == "success"
