@@ -229,6 +229,9 @@ def main():
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (--gpus 1); the reduction shards trivially "
                          "but no multi-GPU path is part of it")
+    from paper_2001_05585_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):     # load what is built; build only if nothing is
+        build.build()
     if args.traffic:
         traffic(args)
     elif args.sweep:

@@ -12,6 +12,15 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+@pytest.fixture(scope="session", autouse=True)
+def built_library():
+    """The tests load the library that is built; they build it only if nothing is."""
+    from paper_2001_05585_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.LIB_PATH
+
+
 @pytest.fixture(scope="session")
 def oracle_lib():
     import oracle
