@@ -361,6 +361,32 @@ def combine(args, torch, np, B, W):
                 emit(f, "%d %d %d %.2f %.2f" % (block, grid, R * U, res[0], res[1]))
 
 
+def warm(args, torch, np, B, W):
+    """Cache-resident inputs (one buffer re-read): load policy, kernel and geometry over n."""
+    timer = Timer(torch, B)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    with open_out(args, "warm.txt") as f:
+        emit(f, "# one buffer re-read back to back (resident in L2 / last-level cache when it fits); uniform[0,1)")
+        emit(f, "# n MiB kernel nt block R U grid us GB/s")
+        for k in (20, 22, 24, 25, 26, 27):
+            n = 1 << k
+            x = W.generate("uniform01", n, W.config_seed(5))
+            bufs = device_buffers(torch, np, x, 1)
+            rows_ = []
+            for kernel in (0, 1):
+                for nt in (1, 2):
+                    for block, R, U, wpc in ((256, 4, 2, 4), (256, 4, 2, 8), (256, 4, 2, 16), (256, 2, 2, 16), (256, 4, 1, 32),
+                                             (256, 2, 1, 32), (512, 4, 2, 8), (1024, 2, 2, 16), (256, 1, 1, 32), (256, 8, 2, 4)):
+                        grid = cus * wpc // (block // 64)
+                        t = B.make_tuning(block, R, grid, kernel, U, nt)
+                        dt = timer.run(bufs, n, t, args.steps, 10)
+                        rows_.append((dt, kernel, nt, block, R, U, grid))
+            rows_.sort()
+            for dt, kernel, nt, block, R, U, grid in rows_[:6] + [r for r in rows_ if r[1:] == (0, 2, 256, 4, 2, cus)]:
+                emit(f, "%d %.0f %d %d %d %d %d %d %.2f %.1f" % (n, 2 * n / 2 ** 20, kernel, nt, block, R, U, grid, dt * 1e6, 2 * n / dt / 1e9))
+            del bufs
+
+
 def rows(args, torch, np, B, W):
     """Batched form: rows x cols fp16 with rows * cols = 2^28 (512 MiB), 4 rotating buffers."""
     total = 1 << 28
@@ -407,4 +433,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants, "wide": wide, "combine": combine}[args.sweep](args, torch, np, B, W)
+    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants, "wide": wide, "combine": combine, "warm": warm}[args.sweep](args, torch, np, B, W)

@@ -84,7 +84,8 @@ typedef struct mfr_tuning {
     int chains_in_flight; /* 1, 2, 4 or 8 independent chains whose loads are issued before
                              any is consumed (memory-level parallelism); chain_R *
                              chains_in_flight must not exceed 16 */
-    int nontemporal;      /* 0 = library default, 1 = plain loads, 2 = non-temporal loads */
+    int nontemporal;      /* 0 = library default (plain loads for inputs up to 32 MiB, which may be
+                             resident in the L2s; non-temporal loads beyond), 1 = plain, 2 = non-temporal */
     int combine;          /* MFR_COMBINE_* */
     int split_permille;   /* MFR_KERNEL_SPLIT only: thousandths of the domain (and of the waves) that
                              take the MFMA path, 0..1000 (Section 5.3's fraction f); rounded to whole

@@ -72,6 +72,16 @@ constexpr int kDefaultWavesPerCU = 4;          // one wave per SIMD
 constexpr long long kTicketMaxBlocks = 2048;   // AUTO: larger grids combine with a second launch
 constexpr long long kTicketHardMax = 65536;    // single-launch combine is not offered beyond this
 constexpr size_t kMaxRowsPerLaunch = 65535;    // gridDim.y limit
+// Inputs that fit in the eight 4 MiB L2s may be resident there (a reduction often follows the kernel
+// that produced its input): they are read with ordinary loads, which hit in L2 (20 % faster at 32 MiB
+// when resident, 3-6 % slower when not).  Larger inputs stream through with non-temporal loads (8 %
+// faster from HBM).
+constexpr size_t kTemporalBytes = (size_t)32 << 20;
+
+void resolve_load_policy(mfr_tuning *t, size_t bytes)
+{
+    if (t->nontemporal == 0) t->nontemporal = bytes <= kTemporalBytes ? 1 : 2;
+}
 constexpr size_t kWaveRowBytes = 8192;         // rows shorter than this get a wave each when there are many
 constexpr size_t kRows16Bytes = 1536;          // still shorter rows of 16-bit types: 16 rows per MFMA chain
 
@@ -118,8 +128,7 @@ int resolve_tuning(const mfr_tuning *in, int dtype, mfr_tuning *t)
     const int u = z.chains_in_flight;
     if (!(u == 1 || u == 2 || u == 4 || u == 8)) return MFR_ERR_INVALID_ARG;
     if (u * z.chain_R > 16) return MFR_ERR_INVALID_ARG;
-    if (z.nontemporal == 0) z.nontemporal = 2;
-    if (z.nontemporal != 1 && z.nontemporal != 2) return MFR_ERR_INVALID_ARG;
+    if (z.nontemporal < 0 || z.nontemporal > 2) return MFR_ERR_INVALID_ARG;   // 0 is resolved per call size
     if (z.combine < 0 || z.combine > 2) return MFR_ERR_INVALID_ARG;
     *t = z;
     return MFR_OK;
@@ -260,6 +269,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     const int st = resolve_tuning(tin, dtype, &t);
     if (st != MFR_OK) return st;
     const unsigned esize = elem_size(dtype);
+    resolve_load_policy(&t, rows * cols * esize);
     if (!out) return MFR_ERR_INVALID_ARG;
     if (rows > 0 && cols > 0 && !x) return MFR_ERR_INVALID_ARG;
     if (((size_t)x & (esize - 1u)) != 0) return MFR_ERR_INVALID_ARG;
@@ -427,6 +437,7 @@ int sum_wide_impl(const mfr_half *x, size_t n, double *out, const mfr_tuning *ti
     mfr_tuning t;
     const int st = resolve_tuning(&in, MFR_DTYPE_F16, &t);
     if (st != MFR_OK) return st;
+    resolve_load_policy(&t, n * 2);
     if (t.kernel != MFR_KERNEL_MFMA || t.block_threads == 32) return MFR_ERR_INVALID_ARG;
     if (!(t.chain_R == 1 || t.chain_R == 2 || t.chain_R == 4 || t.chain_R == 8)) return MFR_ERR_INVALID_ARG;
     if (!out || ((size_t)out & 7u) != 0) return MFR_ERR_INVALID_ARG;
