@@ -110,7 +110,8 @@ typedef struct mfr_tuning {
  * on different streams may overlap, calls on one stream serialise.  A call
  * that has to allocate or enlarge its stream's scratch calls hipMalloc (and
  * synchronises the stream before freeing a smaller one); later calls with a
- * grid no larger than before allocate nothing.
+ * grid no larger than before allocate nothing, only launch kernels (no memset
+ * nodes), and can therefore be captured into a HIP graph and replayed.
  */
 int mfr_sum_f16(const mfr_half *x, size_t n, float *out, hipStream_t stream);
 

@@ -340,6 +340,39 @@ def test_single_launch_combine_with_65536_blocks():
     assert np.all(o.get() == float(n))
 
 
+def test_calls_can_be_captured_in_a_hip_graph_once_scratch_exists(oracle_lib):
+    # After one warm-up call on a stream (which allocates that stream's scratch) a call only launches
+    # kernels, so it can be captured; the ticket counters reset themselves, so the graph can be replayed.
+    n = (1 << 21) + 9
+    xs = [W.generate("uniform_pm1", n, 700 + i) for i in range(3)]
+    want = [oracle_lib.sum_f16(x) for x in xs]
+    buf = DeviceInput(xs[0], 2)
+    out = Outputs(2)
+    s = torch.cuda.Stream()
+    tuned = B.make_tuning(128, 2, 600, 0, 0, 0, B.MFR_COMBINE_SINGLE_LAUNCH)
+    with torch.cuda.stream(s):
+        B.mfr_sum_f16(buf.ptr, n, out.ptr(0), s.cuda_stream)
+        B.mfr_sum_f16_ex(buf.ptr, n, out.ptr(1), tuned, s.cuda_stream)
+    torch.cuda.synchronize()
+    eager = out.get().copy()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        B.mfr_sum_f16(buf.ptr, n, out.ptr(0), s.cuda_stream)
+        B.mfr_sum_f16_ex(buf.ptr, n, out.ptr(1), tuned, s.cuda_stream)
+    for rep in range(6):
+        i = rep % 3
+        bits = torch.from_numpy(np.ascontiguousarray(xs[i]).view(np.int16)).cuda()
+        buf.tensor[buf.start:buf.start + n] = bits           # eager work between replays
+        out.tensor.fill_(Outputs.SENTINEL)
+        torch.cuda.synchronize()
+        g.replay()
+        r = out.get()
+        sref, saref = want[i]
+        assert abs(float(r[0]) - sref) <= TOL * saref and abs(float(r[1]) - sref) <= TOL * saref, (rep, r, sref)
+        if i == 0:
+            assert np.array_equal(r, eager)
+
+
 def test_host_threads_on_their_own_streams(oracle_lib):
     import threading
     inputs = [W.generate("uniform_pm1", (1 << 20) + 17 * k, 200 + k) for k in range(4)]
