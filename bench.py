@@ -209,8 +209,8 @@ def traffic(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--n", type=int, default=1 << 28)
     ap.add_argument("--buffers", type=int, default=4)
     ap.add_argument("--block", type=int, default=0)
