@@ -81,7 +81,7 @@ def test_config3_normal_2p28_headline(oracle_lib):
                B.make_tuning(256, 1), B.make_tuning(1024, 8, 4096)]
     r = run_all(dev, n, tunings)
     err = np.abs(r - s)
-    print("config 3: gpu=%r oracle=%.6f |err|/sum|x|=%.3g |err|/|sum|=%.3g" % (r[0], s, err[0] / sa, err[0] / abs(s)))
+    print("config 3: gpu=%.6f oracle=%.6f |err|/sum|x|=%.3g |err|/|sum|=%.3g" % (r[0], s, err[0] / sa, err[0] / abs(s)))
     assert (err / sa).max() <= TOL
     # misaligned view of the same buffer (a slice starting at element 1)
     s1, sa1 = oracle_of(oracle_lib, x[1:])
