@@ -104,7 +104,8 @@ typedef struct mfr_tuning {
  * Asynchronous: returns after enqueueing; synchronise the stream before
  * reading *out.  Same (x contents, n, tuning, device) => bit-identical *out:
  * block partials are combined in index order, never with float atomics.
- * IEEE special values propagate (NaN in => NaN; +Inf and -Inf => NaN).
+ * IEEE special values propagate (NaN in => NaN; +Inf and -Inf => NaN);
+ * subnormal inputs contribute their value (not flushed), for every type.
  * Scratch (block partials + a ticket counter) is owned by the library, one
  * per (device, stream), allocated on first use and kept until unload; calls
  * on different streams may overlap, calls on one stream serialise.  A call
