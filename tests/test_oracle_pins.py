@@ -194,6 +194,20 @@ def test_kahan_beats_naive_where_it_matters(oracle_lib):
     assert oracle_lib.sum_f16(x)[0] == want
 
 
+def test_compensation_is_needed_beyond_2p29(oracle_lib):
+    # every fp16 value is a multiple of 2^-24, so plain binary64 sums are exact below 2^29; past that the
+    # low bits are lost without the compensation term: 20000 * 65504 followed by 2^24 copies of 2^-24
+    x = np.concatenate([np.full(20000, 0x7BFF, dtype=np.uint16), np.full(1 << 24, 0x0001, dtype=np.uint16)])
+    want = 20000 * 65504 + 1
+    s, a = oracle_lib.sum_f16(x)
+    assert s == float(want) and a == float(want)
+    assert oracle_lib.sum_f16_naive(x) == float(want - 1)          # the uncompensated sum drops the tail
+    e, ea, _ = oracle_lib.exact_sum_f16(x)
+    assert e == want and ea == want
+    sb, ab, _ = oracle_lib.sum_f16_blocked(x, 3)
+    assert sb == float(want) and ab == float(want)
+
+
 # --------------------------------------- ones-matrix MMA identities ---
 
 def test_mma_two_step_every_entry_is_the_tile_total():
@@ -295,6 +309,9 @@ def test_bf16_and_f32_closed_forms(oracle_lib):
     # wide dynamic range: the small term must survive the cancellation of the huge ones
     wide = np.array([2.0 ** 100, 1.0, -(2.0 ** 100)], dtype=np.float32)
     assert oracle_lib.sum_f32(wide)[0] == 1.0
+    wide = np.array([1.0, 2.0 ** 100, -(2.0 ** 100)], dtype=np.float32)      # the small term comes first
+    assert oracle_lib.sum_f32(wide)[0] == 1.0
+    assert oracle_lib.sum_bf16(W.to_bf16_bits(wide))[0] == 1.0
     inf = np.array([1.0, np.inf, 2.0], dtype=np.float32)
     assert oracle_lib.sum_f32(inf)[0] == math.inf
     assert math.isnan(oracle_lib.sum_f32(np.array([np.inf, -np.inf], dtype=np.float32))[0])
