@@ -47,6 +47,21 @@ class Timer:
         return float(self.out[0].item())
 
 
+def load_context():
+    """ctypes handle of the hipCUB comparison library, or None if it has not been built."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2001_05585_amd", "libmfrcontext.so")
+    if not os.path.exists(path):
+        return None
+    lib = ctypes.CDLL(path)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    for name in ("ctx_hipcub_sum_f16_f32acc", "ctx_hipcub_sum_f16"):
+        fn = getattr(lib, name)
+        fn.argtypes = [vp, sz, vp, vp, ctypes.POINTER(sz), vp]
+        fn.restype = ctypes.c_int
+    return lib
+
+
 def open_out(args, name):
     path = args.out or os.path.join(RESULTS_DIR, name)
     os.makedirs(os.path.dirname(path), exist_ok=True)
@@ -166,6 +181,7 @@ def config5(args, torch, np, B, W):
     arena = torch.from_numpy(x.view(np.int16)).cuda()
     arena_bytes = 2 * nmax
     timer = Timer(torch, B)
+    ctx = load_context()
     heat(timer, [arena], 1 << 28)
     with open_out(args, "config5.txt") as f:
         emit(f, "# config 5: uniform[0,1); inputs rotate through a 2 GiB arena (distinct addresses per call) so that")
@@ -196,6 +212,25 @@ def config5(args, torch, np, B, W):
                 dt = e0.elapsed_time(e1) * 1e-3 / steps
                 emit(f, "%d %s %d %.2f %.2f %.1f %.2f" % (n, "torch.sum(context)", 0, dt * 1e6, n / dt / 1e9, 2 * n / dt / 1e9,
                                                         100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS))
+                # context only: the vendor's device-wide reduction (hipCUB), float and half accumulation
+                if ctx is not None:
+                    import ctypes
+                    for fname, label in (("ctx_hipcub_sum_f16_f32acc", "hipcub_float_acc(context)"), ("ctx_hipcub_sum_f16", "hipcub_half_acc(context)")):
+                        fn = getattr(ctx, fname)
+                        need = ctypes.c_size_t(0)
+                        fn(ptrs[0], n, timer.out.data_ptr(), None, ctypes.byref(need), timer.stream)
+                        temp = torch.empty(max(int(need.value), 256), dtype=torch.uint8, device="cuda")
+                        for i in range(5):
+                            fn(ptrs[i % len(ptrs)], n, timer.out.data_ptr(), temp.data_ptr(), ctypes.byref(need), timer.stream)
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        for i in range(steps):
+                            fn(ptrs[(i + 5) % len(ptrs)], n, timer.out.data_ptr(), temp.data_ptr(), ctypes.byref(need), timer.stream)
+                        e1.record()
+                        torch.cuda.synchronize()
+                        dt = e0.elapsed_time(e1) * 1e-3 / steps
+                        emit(f, "%d %s %d %.2f %.2f %.1f %.2f" % (n, label, 0, dt * 1e6, n / dt / 1e9, 2 * n / dt / 1e9,
+                                                                100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS))
 
 
 def types(args, torch, np, B, W):

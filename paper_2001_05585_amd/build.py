@@ -51,5 +51,21 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     return LIB_PATH
 
 
+CONTEXT_SOURCE = os.path.join(CSRC, "context_hipcub.hip")
+CONTEXT_LIB_PATH = os.path.join(_HERE, "libmfrcontext.so")
+
+
+def build_context(verbose: bool = False) -> str:
+    """The hipCUB comparison reduction (benchmark context only; the library never links it)."""
+    tmp = CONTEXT_LIB_PATH + ".tmp%d" % os.getpid()
+    cmd = [hipcc(), *HIPCC_FLAGS, "-shared", "-o", tmp, CONTEXT_SOURCE]
+    if verbose:
+        print(" ".join(cmd), file=sys.stderr)
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, CONTEXT_LIB_PATH)
+    return CONTEXT_LIB_PATH
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_context(verbose=True))
