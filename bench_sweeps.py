@@ -423,40 +423,59 @@ def warm(args, torch, np, B, W):
 
 
 def rows(args, torch, np, B, W):
-    """Batched form: rows x cols fp16 with rows * cols = 2^28 (512 MiB), 4 rotating buffers."""
-    total = 1 << 28
-    host = torch.from_numpy(W.generate("normal", total, 3).view(np.int16))
+    """Batched form: rows x cols elements filling 512 MiB per call, 4 rotating buffers."""
+    total_bytes = 1 << 29
+    host = torch.from_numpy(W.generate("normal", total_bytes // 2, 3).view(np.int16))
     bufs = [host.cuda() for _ in range(4)]
     timer = Timer(torch, B)
     out = torch.zeros(1 << 23, dtype=torch.float32, device="cuda")
-    with open_out(args, "rows.txt") as f:
-        emit(f, "# rows x cols = 2^28 fp16 (512 MiB per call), 4 rotating buffers; tuning 'default' = library choice")
-        emit(f, "# rows cols tuning us Gelem/s GB/s pct_of_8TB/s")
-        for lr in (0, 4, 8, 12, 14, 16, 17, 18, 19, 20, 21, 22):
-            r, c = 1 << lr, total >> lr
-            cands = [("default", None)]
-            if lr >= 16:
-                cands.append(("default,base+2B", "shifted"))     # rows not 16-byte aligned: one wave per row
-            if args.quick != 1:
-                cands += [("b%d_R%d_U%d" % (b, R, U), B.make_tuning(b, R, 0, 0, U)) for b, R, U in
-                          ((64, 1, 8), (64, 1, 4), (64, 2, 4), (64, 4, 2), (128, 1, 4), (256, 1, 2), (256, 1, 8), (64, 1, 1), (64, 1, 2))]
-            for name, t in cands:
-                off, rr = (2, r - 1) if t == "shifted" else (0, r)
-                t = None if t == "shifted" else t
+    explicit = B.make_tuning()           # all defaults, but explicit: the per-row kernels
+    names = {B.MFR_DTYPE_F16: "f16", B.MFR_DTYPE_BF16: "bf16", B.MFR_DTYPE_F32: "f32"}
 
-                def call(i):
-                    B.mfr_sum_rows_ex(bufs[i % 4].data_ptr() + off, B.MFR_DTYPE_F16, rr, c, c, out.data_ptr(), t, timer.stream)
-                for i in range(5):
-                    call(i)
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for i in range(args.steps):
-                    call(i)
-                e1.record()
-                torch.cuda.synchronize()
-                dt = e0.elapsed_time(e1) * 1e-3 / args.steps
-                gb = 2 * total / dt / 1e9
-                emit(f, "%d %d %s %.2f %.1f %.1f %.1f" % (r, c, name, dt * 1e6, total / dt / 1e9, gb, 100 * gb / HBM_PEAK_GBPS))
+    def measure(f, dtype, r, c, stride, shift_elems, t, label):
+        esize = 4 if dtype == B.MFR_DTYPE_F32 else 2
+        off = shift_elems * esize
+
+        def call(i):
+            B.mfr_sum_rows_ex(bufs[i % 4].data_ptr() + off, dtype, r, c, stride, out.data_ptr(), t, timer.stream)
+        for i in range(5):
+            call(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            call(i)
+        e1.record()
+        torch.cuda.synchronize()
+        dt = e0.elapsed_time(e1) * 1e-3 / args.steps
+        gb = (esize * r * c + 4 * r) / dt / 1e9
+        plan = B.mfr_rows_plan(bufs[0].data_ptr() + off, dtype, r, c, stride, torch.cuda.get_device_properties(0).multi_processor_count)
+        shape = "per-row" if (t is not None or plan is None) else "P%d_D%d_GF%d%s" % (plan[0], plan[1], plan[2], "" if plan[9] else "_masked")
+        emit(f, "%s %d %d %d %d %s %s %.2f %.1f %.1f %.1f" % (names[dtype], r, c, stride, shift_elems, label, shape, dt * 1e6,
+                                                       r * c / dt / 1e9, gb, 100 * gb / HBM_PEAK_GBPS))
+
+    with open_out(args, "rows.txt") as f:
+        emit(f, "# rows x cols filling 512 MiB per call, 4 rotating buffers; 'default' = library choice (t == NULL), 'explicit' = the")
+        emit(f, "# same call with an explicit all-default tuning, which selects the per-row kernels; shift = elements between a")
+        emit(f, "# 16-byte boundary and x; GB/s counts the input and the 4-byte results")
+        emit(f, "# type rows cols stride shift tuning kernel_shape us Gelem/s GB/s pct_of_8TB/s")
+        f16 = B.MFR_DTYPE_F16
+        total = total_bytes // 2
+        for lr in (0, 4, 8, 9, 10, 11, 12, 14, 16, 17, 18, 19, 20, 21, 22, 23):
+            r, c = 1 << lr, total >> lr
+            measure(f, f16, r, c, c, 0, None, "default")
+            if lr >= 4 and args.quick != 2:
+                measure(f, f16, r, c, c, 0, explicit, "explicit")
+            if lr >= 5:
+                measure(f, f16, r - 1, c, c, 1, None, "default")
+        for c, stride in ((100, 100), (100, 104), (1000, 1000), (1001, 1001), (5000, 5000), (5001, 5001), (50000, 50001)):
+            r = total // stride
+            measure(f, f16, r, c, stride, 0, None, "default")
+        for dtype in (B.MFR_DTYPE_BF16, B.MFR_DTYPE_F32):
+            esize = 4 if dtype == B.MFR_DTYPE_F32 else 2
+            n = total_bytes // esize
+            for c in (32, 64, 256, 1024, 4096, 1001):
+                measure(f, dtype, n // c, c, c, 0, None, "default")
+            measure(f, dtype, n // 256 - 1, 256, 256, 1, None, "default")
 
 
 def run(args):

@@ -141,15 +141,24 @@ int mfr_sum_ex(const void *x, int dtype, size_t n, float *out, const mfr_tuning 
 
 /*
  * Batched form: out[r] = sum of x[r * row_stride + c], c in [0, cols), for r in
- * [0, rows) -- one reduction R(X_r) (Section 4) per row, each computed exactly
- * as a single call would (Section 5.2), all rows sharing one launch when the
- * row stride is a multiple of 16 bytes (otherwise one launch per row).
- *   x           device pointer, aligned to the element size
- *   row_stride  distance between rows in elements, >= cols when rows > 1
+ * [0, rows) -- one reduction R(X_r) (Section 4) per row through the same
+ * ones-matrix chains (Sections 4.1, 4.3).
+ *   x           device pointer, aligned to the element size (no more)
+ *   row_stride  distance between rows in elements, >= cols when rows > 1; any
+ *               value, the rows need not share a 16-byte phase
  *   out         device pointer to rows floats
- * rows == 0 does nothing; cols == 0 writes zeros.  With MFR_GRID_AUTO the
- * persistent grid is divided among the rows (many short rows: one block each).
- * grid_blocks in the tuning counts blocks per row.
+ * rows == 0 does nothing; cols == 0 writes zeros.
+ * With t == NULL the library picks the kernel: many rows go through one launch
+ * in which the 16 accumulator columns of a chain are shared out among rows
+ * (mfr_rows_plan shows the shape); few long rows get a grid of blocks each.
+ * That first kernel loads whole 16-byte slots and masks what lies outside a
+ * row, so bytes between the rows (inside [x, x + ((rows - 1) * row_stride +
+ * cols) * element size)) may be read; nothing outside that span is (rows at
+ * either end whose slots would reach outside it are summed one by one).
+ * With explicit tuning every row is reduced exactly as a single call would
+ * (Section 5.2), grid_blocks counting blocks per row and MFR_GRID_AUTO dividing
+ * the persistent grid among the rows; rows then share one launch only if the
+ * row stride is a multiple of 16 bytes (otherwise one launch per row).
  */
 int mfr_sum_rows_ex(const void *x, int dtype, size_t rows, size_t cols, size_t row_stride, float *out,
                     const mfr_tuning *t, hipStream_t stream);
@@ -210,6 +219,28 @@ long long mfr_grid_for(size_t n, size_t x_addr, const mfr_tuning *t);
 int mfr_plan_for(size_t n, size_t x_addr, const mfr_tuning *t, unsigned long long plan[7]);
 /* The same for any element type (a slot holds 8 16-bit or 4 32-bit values). */
 int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *t, unsigned long long plan[7]);
+
+/*
+ * Shape of the many-rows kernel that mfr_sum_rows_ex(..., t == NULL, ...) would
+ * launch on a device with `cus` compute units (inspection only, no device
+ * access).  Returns 1 and fills plan[] if that kernel is chosen, 0 if the rows
+ * go to the per-row kernels instead, negative status on invalid arguments.
+ *   plan[0]  P: adjacent accumulator columns per row (1, 2, 4, 8, 16); a tile holds 16 / P rows
+ *   plan[1]  D: tiles of a row per step        plan[2]  GF: tiles side by side
+ *   plan[3]  iterations (each GF * 16 / P consecutive rows)
+ *   plan[4]  steps per row; step c, tile d gives lane l = 16 q + j the slot
+ *            (j mod P) + P q + 4 P (d + D c) of row j / P of its tile, slots being
+ *            counted from the 16-byte boundary at or below the row's first element
+ *   plan[5], plan[6]  steps [begin, end) made of whole in-row slots only (unmasked 128-bit loads)
+ *   plan[7], plan[8]  rows [begin, end) that this kernel sums: every 16-byte slot
+ *            they touch lies inside the array's span; the few rows before and
+ *            after are summed one by one as single arrays (rows outside the range
+ *            that share a tile with rows inside are replaced by the nearest row
+ *            inside, and not stored)
+ *   plan[9]  1 if every step is unmasked    plan[10] blocks of 256 threads
+ */
+int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row_stride, int cus,
+                  unsigned long long plan[11]);
 
 /* Static text for a status code. */
 const char *mfr_strerror(int status);

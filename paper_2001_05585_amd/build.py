@@ -8,7 +8,7 @@ import sys
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
-SOURCES = [os.path.join(CSRC, f) for f in ("mfreduce.hip", "launch_f16.hip", "launch_bf16.hip", "launch_f32.hip", "recurrence.hip", "launch_wide.hip", "rows16.hip")]
+SOURCES = [os.path.join(CSRC, f) for f in ("mfreduce.hip", "launch_f16.hip", "launch_bf16.hip", "launch_f32.hip", "recurrence.hip", "launch_wide.hip", "rows_tiled_f16.hip", "rows_tiled_bf16.hip", "rows_tiled_f32.hip")]
 BUILD_DIR = os.path.join(_HERE, "_build")
 INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "libmfreduce.so")

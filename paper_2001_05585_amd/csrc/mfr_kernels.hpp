@@ -516,11 +516,27 @@ hipError_t launch_sum_f32(const Plan &p, dim3 grid, const mfr_tuning &t, hipStre
 // Binary64 accumulation mode (launch_wide.hip): fp16 input, double result.
 hipError_t launch_sum_wide(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t stream);
 
-// Many short rows, sixteen row sums per MFMA chain (rows16.hip); 16-bit types,
-// x 16-byte aligned, row_stride a multiple of 8 elements.
-hipError_t launch_rows16(int dtype, const void *x, unsigned long long rows, unsigned long long cols,
-                         unsigned long long row_stride, float *out, unsigned grid, unsigned block,
-                         int tiles_in_flight, hipStream_t stream);
+// Many rows in one launch, the accumulator columns shared out among rows (rows_tiled.hpp); any
+// element type, any alignment, any stride >= cols.  The host fills in the shape.
+struct RowsTiledShape {
+    int log2_p;                  // P = 2^log2_p adjacent accumulator columns per row; 16 / P rows per tile
+    int tiles_per_step;          // D: tiles of a row loaded together
+    int groups;                  // GF: tiles (of different rows) side by side
+    bool all_plain;              // every step consists of whole in-row slots (aligned, cols = 4 P D per_slot batches)
+    unsigned long long iters;    // ceil(rows / (GF * 16 / P))
+    unsigned long long row_lo;   // rows [row_lo, row_hi) go through this kernel: their slots lie inside the
+    unsigned long long row_hi;   // array's span; the host sums the rows before and after one by one
+    unsigned int batches;        // steps per row
+    unsigned int plain_lo;       // steps [plain_lo, plain_hi) are plain
+    unsigned int plain_hi;
+};
+#define MFR_DECLARE_ROWS_TILED(name) \
+    hipError_t name(const void *x, unsigned long long rows, unsigned long long cols, unsigned long long row_stride, \
+                    float *out, const RowsTiledShape &s, unsigned grid, bool nt, hipStream_t stream);
+MFR_DECLARE_ROWS_TILED(launch_rows_tiled_f16)
+MFR_DECLARE_ROWS_TILED(launch_rows_tiled_bf16)
+MFR_DECLARE_ROWS_TILED(launch_rows_tiled_f32)
+#undef MFR_DECLARE_ROWS_TILED
 
 // One level of the recurrence variant (recurrence.hip): a.chains groups of R
 // tiles, one binary16 value out per group; final_out (if not null) receives the

@@ -83,7 +83,16 @@ void resolve_load_policy(mfr_tuning *t, size_t bytes)
     if (t->nontemporal == 0) t->nontemporal = bytes <= kTemporalBytes ? 1 : 2;
 }
 constexpr size_t kWaveRowBytes = 8192;         // rows shorter than this get a wave each when there are many
-constexpr size_t kRows16Bytes = 1536;          // still shorter rows of 16-bit types: 16 rows per MFMA chain
+// The tiled rows kernel takes over from this many rows on; long rows (one row per tile) from
+// fewer, and rows of differing 16-byte phase from fewer still (the alternative is a launch per row).
+constexpr size_t kRowsTiledMinRows = 2048;
+constexpr size_t kRowsTiledMinLongRows = 512;
+constexpr size_t kRowsTiledMinMixedRows = 32;
+// Rows of this many bytes or more are walked one per wave, 4 KiB per step, instead of four side by
+// side, 1 KiB each per step: with a power-of-two row stride the four pieces of a step would fall
+// into the same memory channels.
+constexpr size_t kRowsTiledLongRowBytes = 4096;
+constexpr size_t kRowsTiledMaxRowBytes = 16384;
 
 int default_in_flight(int R)
 {
@@ -253,6 +262,71 @@ hipError_t launch_dtype(int dtype, const Plan &p, dim3 grid, const mfr_tuning &t
     }
 }
 
+// Shape of the tiled rows kernel for rows x cols elements of `esize` bytes at byte address x_addr,
+// rows row_stride elements apart.  Returns false when the other kernels are the better choice:
+// few rows (they cannot fill the device here, a grid per row can), unless the rows differ in their
+// 16-byte phase, which only this kernel handles in one launch.
+bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, size_t row_stride, int cus,
+                     bool same_phase, mfr::RowsTiledShape *s, unsigned *grid)
+{
+    if (rows < 2 || cols == 0) return false;
+    const unsigned long long per_slot = 16u / esize;
+    const unsigned long long stride_bytes = (unsigned long long)row_stride * esize;
+    const bool aligned = (x_addr & 15u) == 0 && (stride_bytes & 15u) == 0;
+    const unsigned long long row_bytes = (unsigned long long)cols * esize + (aligned ? 0u : 14u);
+    // rows this long are streamed as well or better by a grid of blocks per row
+    if (same_phase && row_bytes > kRowsTiledMaxRowBytes) return false;
+    int lp = 0;
+    while (lp < 4 && (64ull << lp) < row_bytes) ++lp;
+    int d = 1, gf = 8;
+    if (rows >= kRowsTiledMinRows && row_bytes < kRowsTiledLongRowBytes) {
+        if (lp == 4) gf = 4;
+    } else if ((lp == 4 && rows >= kRowsTiledMinLongRows) || (!same_phase && rows >= kRowsTiledMinMixedRows)) {
+        lp = 4; d = 4; gf = 1;
+    } else {
+        return false;
+    }
+    const unsigned long long p = 1ull << lp;
+    const unsigned long long rows_per_iter = (unsigned long long)gf * (16ull / p);
+    const unsigned long long slots_per_step = 4ull * p * (unsigned)d;
+    const unsigned long long max_slots = ((aligned ? 0ull : per_slot - 1ull) + cols + per_slot - 1ull) / per_slot;
+    const unsigned long long batches = (max_slots + slots_per_step - 1ull) / slots_per_step;
+    const unsigned long long plain_hi = (cols / per_slot) / slots_per_step;
+    if (batches > 0xffffffffull) return false;
+    s->log2_p = lp;
+    s->tiles_per_step = d;
+    s->groups = gf;
+    s->iters = (rows + rows_per_iter - 1ull) / rows_per_iter;
+    s->batches = (unsigned int)batches;
+    s->plain_lo = aligned ? 0u : 1u;
+    s->plain_hi = (unsigned int)plain_hi;
+    if (s->plain_hi < s->plain_lo) s->plain_hi = s->plain_lo;
+    s->all_plain = aligned && plain_hi == batches;
+    // Rows whose first slot would start before x (r * stride_bytes < gap) and rows whose last slot
+    // would end past the span are not for this kernel.
+    const unsigned long long gap = (16u - (x_addr & 15u)) & 15u;
+    unsigned long long head_rows = gap == 0 ? 0ull : (gap + stride_bytes - 1ull) / stride_bytes;
+    if (head_rows > rows) head_rows = rows;
+    const unsigned long long row_bytes_exact = (unsigned long long)cols * esize;
+    const unsigned long long span_end = x_addr + (rows - 1ull) * stride_bytes + row_bytes_exact;
+    unsigned long long tail_rows = 0;
+    while (tail_rows < rows) {
+        const unsigned long long r = rows - 1ull - tail_rows;
+        const unsigned long long row_end = x_addr + r * stride_bytes + row_bytes_exact;
+        if (((row_end + 15ull) & ~15ull) <= span_end) break;
+        ++tail_rows;
+    }
+    if (head_rows + tail_rows >= rows) return false;
+    s->row_lo = head_rows;
+    s->row_hi = rows - tail_rows;
+    // 256-thread blocks: one wave per SIMD; two when steps are masked (their arithmetic then overlaps
+    // the other wave's loads)
+    unsigned long long g = (unsigned long long)cus * (s->all_plain ? 1u : 2u);
+    if (g * 4ull > s->iters) g = (s->iters + 3ull) / 4ull;
+    *grid = (unsigned)g;
+    return true;
+}
+
 int fill_zero(float *out, size_t count, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)((count + 255) / 256);
@@ -289,18 +363,27 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     // rows can share one launch when they all have the same 16-byte phase
     const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
 
-    // Many short rows of a 16-bit type with aligned rows: sixteen rows per MFMA chain.
-    if (tin == nullptr && rows >= (size_t)info.cus * 16 && cols * esize < kRows16Bytes && esize == 2 &&
-        ((size_t)x & 15u) == 0 && (row_stride & 7u) == 0) {
-        const size_t groups = (rows + 15) / 16;
-        const size_t tiles = (cols + 31) / 32;
-        const int in_flight = tiles >= 8 ? 8 : (tiles >= 4 ? 4 : (tiles >= 2 ? 2 : 1));
-        size_t grid = (size_t)info.cus;                      // 256-thread blocks: one wave per SIMD
-        if (grid * 4 > groups) grid = (groups + 3) / 4;
-        const hipError_t e = mfr::launch_rows16(dtype, x, rows, cols, row_stride, out, (unsigned)grid, 256, in_flight,
-                                                stream);
-        if (e != hipSuccess) return hip_fail(e, "rows16 launch");
-        return MFR_OK;
+    // Many rows: tiles shared out among rows, one launch for any alignment and stride.
+    if (tin == nullptr) {
+        mfr::RowsTiledShape shape;
+        unsigned grid = 0;
+        if (plan_rows_tiled((size_t)x, esize, rows, cols, row_stride, info.cus, same_phase, &shape, &grid)) {
+            const bool nt = t.nontemporal == 2;
+            const hipError_t e =
+                dtype == MFR_DTYPE_F16 ? mfr::launch_rows_tiled_f16(x, rows, cols, row_stride, out, shape, grid, nt, stream)
+                : dtype == MFR_DTYPE_BF16 ? mfr::launch_rows_tiled_bf16(x, rows, cols, row_stride, out, shape, grid, nt, stream)
+                                          : mfr::launch_rows_tiled_f32(x, rows, cols, row_stride, out, shape, grid, nt, stream);
+            if (e != hipSuccess) return hip_fail(e, "rows_tiled launch");
+            // the few rows at either end whose 16-byte slots would reach outside the array: one by one
+            for (size_t r = 0; r < rows; ++r) {
+                if (r == shape.row_lo) r = shape.row_hi;        // skip what the launch above covers
+                if (r >= rows) break;
+                const int se = sum_rows_impl((const char *)x + r * row_stride * esize, dtype, 1, cols, cols, out + r,
+                                             nullptr, stream);
+                if (se != MFR_OK) return se;
+            }
+            return MFR_OK;
+        }
     }
 
     // Many short rows: every wave reduces a row of its own (no cross-wave or
@@ -601,6 +684,31 @@ int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *tin, unsig
 int mfr_plan_for(size_t n, size_t x_addr, const mfr_tuning *tin, unsigned long long plan[7])
 {
     return mfr_plan_ex(n, x_addr, MFR_DTYPE_F16, tin, plan);
+}
+
+int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row_stride, int cus,
+                  unsigned long long plan[11])
+{
+    if (!valid_dtype(dtype) || !plan || cus < 1) return -MFR_ERR_INVALID_ARG;
+    const unsigned esize = elem_size(dtype);
+    if ((x_addr & (esize - 1u)) || cols > ((size_t)1 << 60) || rows > ((size_t)1 << 40)) return -MFR_ERR_INVALID_ARG;
+    if (rows > 1 && row_stride < cols) return -MFR_ERR_INVALID_ARG;
+    const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
+    mfr::RowsTiledShape s;
+    unsigned grid = 0;
+    if (!plan_rows_tiled(x_addr, esize, rows, cols, row_stride, cus, same_phase, &s, &grid)) return 0;
+    plan[0] = 1ull << s.log2_p;
+    plan[1] = (unsigned long long)s.tiles_per_step;
+    plan[2] = (unsigned long long)s.groups;
+    plan[3] = s.iters;
+    plan[4] = s.batches;
+    plan[5] = s.plain_lo;
+    plan[6] = s.plain_hi;
+    plan[7] = s.row_lo;
+    plan[8] = s.row_hi;
+    plan[9] = s.all_plain ? 1ull : 0ull;
+    plan[10] = grid;
+    return 1;
 }
 
 const char *mfr_strerror(int status)

@@ -1,0 +1,193 @@
+"""GPU parity of the many-rows kernel (accumulator columns shared out among rows)
+against the CPU oracle, through mfr_sum_rows_ex with library defaults.
+
+Integer-valued inputs (every partial sum exact in fp32): bit-exact.  Random
+inputs: |gpu - oracle| <= 1e-5 * sum |x_i| per row.  The gaps between rows and
+the bytes around the array hold NaN, so that a value read from outside a row
+and not masked shows up in that row's sum."""
+import math
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2001_05585_amd import binding as B            # noqa: E402
+from paper_2001_05585_amd import workloads as W          # noqa: E402
+from gpu_util import Outputs, stream_handle              # noqa: E402
+
+TOL = 1e-5
+F16, BF16, F32 = B.MFR_DTYPE_F16, B.MFR_DTYPE_BF16, B.MFR_DTYPE_F32
+NAN = {F16: 0x7E00, BF16: 0x7FC0, F32: 0x7FC00000}
+STORAGE = {F16: np.uint16, BF16: np.uint16, F32: np.uint32}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU; the HIP path has no fallback")
+    B.lib()
+
+
+def cus():
+    return torch.cuda.get_device_properties(0).multi_processor_count
+
+
+def encode(dtype, values):
+    """float32 values -> storage bits of the element type (values are exactly representable)."""
+    v = np.asarray(values, dtype=np.float32)
+    if dtype == F16:
+        return v.astype(np.float16).view(np.uint16)
+    if dtype == BF16:
+        return W.to_bf16_bits(v)
+    return v.view(np.uint32)
+
+
+class RowsInput:
+    """rows x cols values laid out with a stride, NaN in the gaps and around the array, shifted by
+    `shift` elements from a 16-byte boundary."""
+
+    def __init__(self, dtype, bits2d, stride, shift):
+        rows, cols = bits2d.shape
+        st = STORAGE[dtype]
+        guard = 64
+        span = (rows - 1) * stride + cols
+        buf = np.full(span + 2 * guard + 16, NAN[dtype], dtype=st)
+        start = guard + shift
+        idx = (np.arange(rows)[:, None] * stride + np.arange(cols)[None, :]).ravel() + start
+        buf[idx] = bits2d.ravel()
+        self.tensor = torch.from_numpy(buf.view(np.int16 if st == np.uint16 else np.int32)).cuda()
+        assert self.tensor.data_ptr() % 16 == 0
+        self.ptr = self.tensor.data_ptr() + buf.itemsize * start
+
+
+def call(dtype, inp, rows, cols, stride, tuning=None):
+    o = Outputs(rows + 1)
+    B.mfr_sum_rows_ex(inp.ptr, dtype, rows, cols, stride, o.ptr(0), tuning, stream_handle())
+    r = o.get()
+    assert r[rows] == Outputs.SENTINEL            # nothing written past out[rows)
+    return r[:rows]
+
+
+def expect_plan(dtype, inp, rows, cols, stride, **want):
+    plan = B.mfr_rows_plan(inp.ptr, dtype, rows, cols, stride, cus())
+    assert plan is not None, "the many-rows kernel should be chosen for this shape"
+    names = dict(P=0, D=1, GF=2, all_plain=9)
+    for k, v in want.items():
+        assert plan[names[k]] == v, (k, plan)
+    return plan
+
+
+# (rows, cols, stride, shift) chosen to reach every kernel shape, masked and unmasked
+INT_CASES = [
+    (4096, 32, 32, 0), (4099, 64, 64, 0), (4100, 128, 128, 0), (2050, 256, 256, 0), (2048, 512, 512, 0),
+    (2048, 1024, 1024, 0), (2049, 4096, 4096, 0), (600, 2048, 2048, 0),             # unmasked steps only
+    (5003, 1, 1, 0), (5003, 1, 1, 1), (5003, 7, 7, 3), (5003, 31, 33, 0), (5003, 33, 40, 0), (4001, 64, 64, 1),
+    (4001, 65, 72, 0), (4001, 100, 100, 0), (4001, 129, 131, 5), (3000, 255, 256, 0), (3000, 300, 304, 7),
+    (2500, 500, 500, 2), (2100, 1001, 1001, 0), (2100, 1536, 1544, 4), (2049, 3000, 3001, 0),
+    (700, 2500, 2504, 0), (513, 4097, 4099, 6),                                      # long rows from 512 rows on
+    (33, 1001, 1001, 0), (100, 37, 39, 1), (1000, 5, 5, 0), (40, 20000, 20001, 0),   # phases differ, few rows
+]
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16, F32])
+@pytest.mark.parametrize("rows,cols,stride,shift", INT_CASES)
+def test_integer_rows_bit_exact(dtype, rows, cols, stride, shift, oracle_lib):
+    vals = W.small_integers(rows * cols, seed=rows * 31 + cols, lo=-4, hi=4).astype(np.float32).reshape(rows, cols)
+    inp = RowsInput(dtype, encode(dtype, vals).reshape(rows, cols), stride, shift)
+    expect_plan(dtype, inp, rows, cols, stride)
+    want = vals.astype(np.float64).sum(axis=1)
+    got = call(dtype, inp, rows, cols, stride).astype(np.float64)
+    bad = np.nonzero(got != want)[0]
+    assert bad.size == 0, (rows, cols, stride, shift, bad[:5], got[bad[:5]], want[bad[:5]])
+
+
+def test_shapes_reach_every_kernel_shape():
+    seen = set()
+    for dtype in (F16, F32):
+        for rows, cols, stride, shift in INT_CASES:
+            esize = 2 if dtype != F32 else 4
+            plan = B.mfr_rows_plan((1 << 20) + shift * esize, dtype, rows, cols, stride, 256)
+            assert plan is not None
+            seen.add((plan[0], plan[1], plan[2], plan[9]))
+    for p, d, gf in ((1, 1, 8), (2, 1, 8), (4, 1, 8), (8, 1, 8), (16, 1, 4), (16, 4, 1)):
+        assert (p, d, gf, 0) in seen, (p, d, gf)
+        assert (p, d, gf, 1) in seen, (p, d, gf)
+
+
+@pytest.mark.parametrize("dtype,kind", [(F16, "normal"), (F16, "uniform01"), (BF16, "normal"), (F32, "uniform_pm1")])
+@pytest.mark.parametrize("rows,cols,stride,shift", [(4096, 64, 64, 0), (3001, 100, 104, 1), (2048, 1024, 1024, 0),
+                                                    (2051, 777, 777, 0), (600, 3000, 3000, 3)])
+def test_random_rows_within_tolerance(dtype, kind, rows, cols, stride, shift, oracle_lib):
+    seed = 7000 + rows + cols
+    if dtype == F16:
+        bits = W.generate(kind, rows * cols, seed).view(np.uint16)
+    elif dtype == BF16:
+        bits = W.generate_bf16(kind, rows * cols, seed)
+    else:
+        bits = W.generate_f32(kind, rows * cols, seed).view(np.uint32)
+    bits2d = bits.reshape(rows, cols)
+    inp = RowsInput(dtype, bits2d, stride, shift)
+    expect_plan(dtype, inp, rows, cols, stride)
+    s, sa = oracle_lib.sum_rows(bits2d if dtype != F16 else bits2d.view(np.float16), {F16: "f16", BF16: "bf16", F32: "f32"}[dtype])
+    got = call(dtype, inp, rows, cols, stride).astype(np.float64)
+    assert (np.abs(got - s) <= TOL * sa).all(), np.max(np.abs(got - s) / sa)
+    # the per-row kernels (explicit tuning) agree to the same bound
+    if (stride * bits.itemsize) % 16 == 0:
+        got2 = call(dtype, inp, rows, cols, stride, B.make_tuning(256, 2)).astype(np.float64)
+        assert (np.abs(got2 - s) <= TOL * sa).all()
+
+
+def test_special_values_stay_in_their_row():
+    rows, cols, stride = 4100, 96, 100
+    vals = np.ones((rows, cols), dtype=np.float32)
+    bits = encode(F16, vals).reshape(rows, cols).copy()
+    bits[7, cols - 1] = 0x7C00          # +Inf
+    bits[8, 0] = 0xFC00                 # -Inf
+    bits[4000, 5] = 0x7E00              # NaN
+    bits[4099, 0] = 0x7C00; bits[4099, 1] = 0xFC00
+    inp = RowsInput(F16, bits, stride, 3)
+    got = call(F16, inp, rows, cols, stride).astype(np.float64)
+    assert got[7] == math.inf and got[8] == -math.inf and math.isnan(got[4000]) and math.isnan(got[4099])
+    keep = np.ones(rows, dtype=bool); keep[[7, 8, 4000, 4099]] = False
+    assert np.all(got[keep] == cols)
+
+
+def test_sparse_diagonals_every_column_position():
+    # a few nonzero values per row among zeros: diagonals that start at rows around the first, a middle
+    # and the last iteration and run through every column, each diagonal with its own power of two
+    rows, cols, stride = 2600, 75, 77
+    bases = (0, 1, 15, 16, 127, 128, 1300, 2470, 2524, 2599)
+    for dtype, shift in ((F16, 5), (F16, 0), (F32, 1)):
+        vals = np.zeros((rows, cols), dtype=np.float32)
+        for i, r0 in enumerate(bases):
+            k = np.arange(cols)
+            vals[(r0 + k) % rows, k] += 2.0 ** i
+        inp = RowsInput(dtype, encode(dtype, vals).reshape(rows, cols), stride, shift)
+        got = call(dtype, inp, rows, cols, stride).astype(np.float64)
+        want = vals.astype(np.float64).sum(axis=1)
+        assert np.array_equal(got, want), (dtype, shift, np.nonzero(got != want)[0][:5])
+
+
+def test_same_result_at_every_alignment():
+    rows, cols = 2304, 200
+    vals = W.small_integers(rows * cols, seed=99, lo=-4, hi=4).astype(np.float32).reshape(rows, cols)
+    want = vals.astype(np.float64).sum(axis=1)
+    for dtype in (F16, F32):
+        per_slot = 8 if dtype == F16 else 4
+        for shift in range(per_slot):
+            for stride in (cols, cols + 1, cols + per_slot):
+                inp = RowsInput(dtype, encode(dtype, vals).reshape(rows, cols), stride, shift)
+                got = call(dtype, inp, rows, cols, stride).astype(np.float64)
+                assert np.array_equal(got, want), (dtype, shift, stride)
+
+
+def test_more_rows_than_a_grid_dimension_and_tiny_rows():
+    rows = 70001
+    for cols, stride in ((8, 8), (3, 3), (1, 2)):
+        vals = W.small_integers(rows * cols, seed=cols, lo=-4, hi=4).astype(np.float32).reshape(rows, cols)
+        inp = RowsInput(F16, encode(F16, vals).reshape(rows, cols), stride, 0)
+        got = call(F16, inp, rows, cols, stride).astype(np.float64)
+        assert np.array_equal(got, vals.astype(np.float64).sum(axis=1)), (cols, stride)

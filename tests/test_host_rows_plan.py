@@ -1,0 +1,148 @@
+"""Host logic of the many-rows kernel, checked without a GPU.
+
+``mfr_rows_plan`` returns the shape the library would launch; the kernel's
+index arithmetic (documented with that call) is replayed here per lane, and the
+test checks what the kernel relies on for memory safety and for correctness:
+
+* every element of every row is kept by exactly one (step, tile, lane),
+* the slots of unmasked steps lie wholly inside their row,
+* every whole-slot load of a masked step (including the substitute slot of a
+  lane past the row's end) lies inside the array's span, for the rows the
+  kernel is given; the rows it is not given are few,
+* rows map to store lanes one to one.
+"""
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from paper_2001_05585_amd import binding as B
+
+ESIZE = {B.MFR_DTYPE_F16: 2, B.MFR_DTYPE_BF16: 2, B.MFR_DTYPE_F32: 4}
+
+
+def replay(x_addr, dtype, rows, cols, stride, cus=256):
+    plan = B.mfr_rows_plan(x_addr, dtype, rows, cols, stride, cus)
+    if plan is None:
+        return None
+    P, D, GF, iters, batches, plain_lo, plain_hi, row_lo, row_hi, all_plain, grid = plan
+    es = ESIZE[dtype]
+    E = 16 // es
+    RPT = 16 // P
+    rpi = GF * RPT
+    assert iters == -(-rows // rpi)
+    assert 1 <= grid <= cus * (1 if all_plain else 2) and grid * 4 >= min(iters, cus * 4) - 3
+    span = ((rows - 1) * stride + cols) * es
+    lane = np.arange(64)
+    j, q = lane & 15, lane >> 4
+    part, row_local = j & (P - 1), j // P
+    s_lane = part + P * q
+    covered = np.zeros((rows, cols), dtype=np.int32)
+    stored = np.zeros(rows, dtype=np.int32)
+    if all_plain:
+        assert plain_lo == 0 and plain_hi == batches and row_lo == 0 and row_hi == rows
+    assert 0 <= row_lo < row_hi <= rows
+    assert row_lo <= 8 and rows - row_hi <= 8         # only rows within 16 bytes of either end are left out
+    for it in range(iters):
+        for u in range(GF):
+            r_raw = (it * GF + u) * RPT + row_local
+            r = np.clip(r_raw, row_lo, row_hi - 1)
+            off = r * stride * es
+            ph = (x_addr + off) & 15
+            slot0 = off - ph                       # byte offset of the row's first slot from x
+            head = ph // es
+            vend = head + cols
+            for cb in range(batches):
+                plain = plain_lo <= cb < plain_hi
+                for d in range(D):
+                    s = s_lane + 4 * P * (d + D * cb)
+                    rel = slot0 + 16 * s
+                    e0 = E * s
+                    if plain:
+                        # unmasked 128-bit load: the slot must be whole and inside the row
+                        assert np.all(e0 >= head) and np.all(e0 + E <= vend), (it, u, cb, d)
+                        assert np.all(rel >= 0) and np.all(rel + 16 <= span)
+                        lo, hi = np.zeros(64, int), np.full(64, E)
+                    else:
+                        inside = e0 < vend
+                        addr = np.where(inside, rel, slot0)
+                        assert np.all(addr >= 0) and np.all(addr + 16 <= span), (it, u, cb, d)
+                        lo = np.clip(head - e0, 0, E)
+                        hi = np.clip(vend - e0, 0, E)
+                    for ln in range(64):
+                        if not (row_lo <= r_raw[ln] < row_hi):
+                            continue
+                        for t in range(lo[ln], hi[ln]):
+                            c = e0[ln] + t - head[ln]
+                            assert 0 <= c < cols
+                            covered[r[ln], c] += 1
+            # store lanes: part 0, q == u mod 4
+            mine = (part == 0) & (q == (u & 3)) & (r_raw >= row_lo) & (r_raw < row_hi)
+            for ln in np.nonzero(mine)[0]:
+                stored[r_raw[ln]] += 1
+    assert np.all(covered[row_lo:row_hi] == 1) and not covered[:row_lo].any() and not covered[row_hi:].any()
+    assert np.all(stored[row_lo:row_hi] == 1) and not stored[:row_lo].any() and not stored[row_hi:].any()
+    return plan
+
+
+SHAPES = [
+    # (x_addr low bits, rows, cols, stride) -- many rows so that the tiled kernel is chosen
+    (0, 2048, 64, 64), (0, 2048, 32, 32), (0, 2048, 128, 128), (0, 2048, 256, 256), (0, 2048, 512, 512),
+    (0, 2048, 1024, 1024), (0, 2100, 100, 100), (2, 2049, 64, 64), (14, 2048, 64, 72), (6, 2048, 7, 7),
+    (0, 2048, 1, 1), (2, 2048, 1, 1), (0, 2048, 3, 5), (8, 2500, 33, 40), (0, 2048, 1001, 1001),
+    (4, 2048, 520, 523), (0, 600, 700, 704), (2, 600, 5000, 5001), (0, 40, 33, 37), (6, 33, 3, 3),
+]
+
+
+@pytest.mark.parametrize("dtype", [B.MFR_DTYPE_F16, B.MFR_DTYPE_F32])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_replay_of_listed_shapes(dtype, shape):
+    low, rows, cols, stride = shape
+    es = ESIZE[dtype]
+    x_addr = (1 << 20) + (low // es) * es
+    if cols * rows > 1_500_000:
+        rows = max(2048 if rows >= 2048 else rows, 1_500_000 // cols // 16 * 16)
+    plan = replay(x_addr, dtype, rows, cols, stride)
+    assert plan is not None
+
+
+def test_aligned_power_of_two_rows_are_unmasked():
+    for cols, P in ((32, 1), (64, 2), (128, 4), (256, 8), (512, 16), (1024, 16), (4096, 16)):
+        plan = B.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F16, 4096, cols, cols, 256)
+        assert plan is not None and plan[0] == P and plan[9] == 1, (cols, plan)
+    # binary32: a slot holds four values
+    plan = B.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F32, 4096, 64, 64, 256)
+    assert plan[0] == 4 and plan[9] == 1
+
+
+def test_choice_between_kernels():
+    f16 = B.MFR_DTYPE_F16
+    assert B.mfr_rows_plan(1 << 20, f16, 1, 1000, 1000, 256) is None          # one row: the single-sum path
+    assert B.mfr_rows_plan(1 << 20, f16, 100, 1 << 20, 1 << 20, 256) is None   # few long rows: a grid per row
+    assert B.mfr_rows_plan(1 << 20, f16, 100, 64, 64, 256) is None
+    assert B.mfr_rows_plan(1 << 20, f16, 100, 1001, 1001, 256) is not None     # phases differ: one launch all the same
+    assert B.mfr_rows_plan(1 << 20, f16, 600, 4096, 4096, 256) is not None     # long rows from 512 rows on
+    assert B.mfr_rows_plan(1 << 20, f16, 4096, 8, 8, 256) is not None
+    assert B.mfr_rows_plan(1 << 20, f16, 4096, 16384, 16384, 256) is None      # rows beyond 16 KiB: a grid per row ...
+    assert B.mfr_rows_plan(1 << 20, f16, 4096, 16385, 16385, 256) is not None  # ... unless their phases differ
+
+
+def test_invalid_arguments():
+    plan = (B.ctypes.c_ulonglong * 11)()
+    L = B.lib()
+    assert L.mfr_rows_plan(1 << 20, 9, 4096, 64, 64, 256, plan) == -B.MFR_ERR_INVALID_ARG
+    assert L.mfr_rows_plan((1 << 20) + 1, B.MFR_DTYPE_F16, 4096, 64, 64, 256, plan) == -B.MFR_ERR_INVALID_ARG
+    assert L.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F16, 4096, 64, 63, 256, plan) == -B.MFR_ERR_INVALID_ARG
+    assert L.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F16, 4096, 64, 64, 0, plan) == -B.MFR_ERR_INVALID_ARG
+    assert L.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F16, 4096, 64, 64, 256, None) == -B.MFR_ERR_INVALID_ARG
+
+
+@settings(max_examples=60, deadline=None)
+@given(dtype=st.sampled_from([B.MFR_DTYPE_F16, B.MFR_DTYPE_BF16, B.MFR_DTYPE_F32]),
+       low=st.integers(0, 7), rows=st.integers(32, 2300), cols=st.integers(1, 300), gap=st.integers(0, 9),
+       cus=st.sampled_from([1, 8, 256]))
+def test_replay_of_random_shapes(dtype, low, rows, cols, gap, cus):
+    es = ESIZE[dtype]
+    x_addr = (1 << 20) + (low * 2 // es) * es
+    if rows * cols > 200_000:
+        cols = max(1, 200_000 // rows)
+    replay(x_addr, dtype, rows, cols, cols + gap, cus)
