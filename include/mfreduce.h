@@ -151,10 +151,11 @@ int mfr_sum_ex(const void *x, int dtype, size_t n, float *out, const mfr_tuning 
  * With t == NULL the library picks the kernel: many rows go through one launch
  * in which the 16 accumulator columns of a chain are shared out among rows
  * (mfr_rows_plan shows the shape); few long rows get a grid of blocks each.
- * That first kernel loads whole 16-byte slots and masks what lies outside a
- * row, so bytes between the rows (inside [x, x + ((rows - 1) * row_stride +
- * cols) * element size)) may be read; nothing outside that span is (rows at
- * either end whose slots would reach outside it are summed one by one).
+ * That first kernel loads 16-byte slots counted from each row's first element
+ * and masks what lies past the row's end, so bytes after a row (in the gap or
+ * in the next rows, inside [x, x + ((rows - 1) * row_stride + cols) * element
+ * size)) may be read; nothing outside that span is (the last rows, whose final
+ * slot would reach past it, are summed one by one).
  * With explicit tuning every row is reduced exactly as a single call would
  * (Section 5.2), grid_blocks counting blocks per row and MFR_GRID_AUTO dividing
  * the persistent grid among the rows; rows then share one launch only if the
@@ -230,13 +231,15 @@ int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *t, unsigne
  *   plan[3]  iterations (each GF * 16 / P consecutive rows)
  *   plan[4]  steps per row; step c, tile d gives lane l = 16 q + j the slot
  *            (j mod P) + P q + 4 P (d + D c) of row j / P of its tile, slots being
- *            counted from the 16-byte boundary at or below the row's first element
- *   plan[5], plan[6]  steps [begin, end) made of whole in-row slots only (unmasked 128-bit loads)
- *   plan[7], plan[8]  rows [begin, end) that this kernel sums: every 16-byte slot
- *            they touch lies inside the array's span; the few rows before and
- *            after are summed one by one as single arrays (rows outside the range
- *            that share a tile with rows inside are replaced by the nearest row
- *            inside, and not stored)
+ *            counted from the row's own first element (128-bit loads at element
+ *            alignment)
+ *   plan[5], plan[6]  steps [begin, end) made of whole in-row slots only; begin is 0
+ *            and at most the last step is left out: its slots are masked, and a
+ *            slot wholly past the row's end is replaced by the row's first slot
+ *   plan[7], plan[8]  rows [begin, end) that this kernel sums (begin is 0): no slot
+ *            of theirs reaches past the array's span; the few rows after them are
+ *            summed one by one as single arrays (in a tile that holds rows of both
+ *            kinds they are replaced by row end - 1, and not stored)
  *   plan[9]  1 if every step is unmasked    plan[10] blocks of 256 threads
  */
 int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row_stride, int cus,

@@ -522,13 +522,12 @@ struct RowsTiledShape {
     int log2_p;                  // P = 2^log2_p adjacent accumulator columns per row; 16 / P rows per tile
     int tiles_per_step;          // D: tiles of a row loaded together
     int groups;                  // GF: tiles (of different rows) side by side
-    bool all_plain;              // every step consists of whole in-row slots (aligned, cols = 4 P D per_slot batches)
+    bool all_plain;              // every step consists of whole in-row slots (cols = a whole number of steps)
     unsigned long long iters;    // ceil(rows / (GF * 16 / P))
-    unsigned long long row_lo;   // rows [row_lo, row_hi) go through this kernel: their slots lie inside the
-    unsigned long long row_hi;   // array's span; the host sums the rows before and after one by one
+    unsigned long long row_hi;   // rows [0, row_hi) go through this kernel: their slots lie inside the array's
+                                 // span; the host sums the rows after them one by one
     unsigned int batches;        // steps per row
-    unsigned int plain_lo;       // steps [plain_lo, plain_hi) are plain
-    unsigned int plain_hi;
+    unsigned int plain_hi;       // steps [0, plain_hi) are plain; at most the last step is not
 };
 #define MFR_DECLARE_ROWS_TILED(name) \
     hipError_t name(const void *x, unsigned long long rows, unsigned long long cols, unsigned long long row_stride, \

@@ -269,11 +269,11 @@ hipError_t launch_dtype(int dtype, const Plan &p, dim3 grid, const mfr_tuning &t
 bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, size_t row_stride, int cus,
                      bool same_phase, mfr::RowsTiledShape *s, unsigned *grid)
 {
+    (void)x_addr;                        // slots are counted from each row's first element: no phase
     if (rows < 2 || cols == 0) return false;
     const unsigned long long per_slot = 16u / esize;
     const unsigned long long stride_bytes = (unsigned long long)row_stride * esize;
-    const bool aligned = (x_addr & 15u) == 0 && (stride_bytes & 15u) == 0;
-    const unsigned long long row_bytes = (unsigned long long)cols * esize + (aligned ? 0u : 14u);
+    const unsigned long long row_bytes = (unsigned long long)cols * esize;
     // rows this long are streamed as well or better by a grid of blocks per row
     if (same_phase && row_bytes > kRowsTiledMaxRowBytes) return false;
     int lp = 0;
@@ -289,39 +289,26 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     const unsigned long long p = 1ull << lp;
     const unsigned long long rows_per_iter = (unsigned long long)gf * (16ull / p);
     const unsigned long long slots_per_step = 4ull * p * (unsigned)d;
-    const unsigned long long max_slots = ((aligned ? 0ull : per_slot - 1ull) + cols + per_slot - 1ull) / per_slot;
-    const unsigned long long batches = (max_slots + slots_per_step - 1ull) / slots_per_step;
-    const unsigned long long plain_hi = (cols / per_slot) / slots_per_step;
+    const unsigned long long slots = (cols + per_slot - 1ull) / per_slot;
+    const unsigned long long batches = (slots + slots_per_step - 1ull) / slots_per_step;
+    const unsigned long long plain_hi = (cols / per_slot) / slots_per_step;       // >= batches - 1
     if (batches > 0xffffffffull) return false;
     s->log2_p = lp;
     s->tiles_per_step = d;
     s->groups = gf;
     s->iters = (rows + rows_per_iter - 1ull) / rows_per_iter;
     s->batches = (unsigned int)batches;
-    s->plain_lo = aligned ? 0u : 1u;
     s->plain_hi = (unsigned int)plain_hi;
-    if (s->plain_hi < s->plain_lo) s->plain_hi = s->plain_lo;
-    s->all_plain = aligned && plain_hi == batches;
-    // Rows whose first slot would start before x (r * stride_bytes < gap) and rows whose last slot
-    // would end past the span are not for this kernel.
-    const unsigned long long gap = (16u - (x_addr & 15u)) & 15u;
-    unsigned long long head_rows = gap == 0 ? 0ull : (gap + stride_bytes - 1ull) / stride_bytes;
-    if (head_rows > rows) head_rows = rows;
-    const unsigned long long row_bytes_exact = (unsigned long long)cols * esize;
-    const unsigned long long span_end = x_addr + (rows - 1ull) * stride_bytes + row_bytes_exact;
+    s->all_plain = plain_hi == batches;
+    // Rows whose last slot would end past the array's span are not for this kernel: row r reads
+    // bytes [r * stride, r * stride + 16 * slots) from x, the span ends at (rows - 1) * stride + row_bytes.
+    const unsigned long long span = (rows - 1ull) * stride_bytes + row_bytes;
     unsigned long long tail_rows = 0;
-    while (tail_rows < rows) {
-        const unsigned long long r = rows - 1ull - tail_rows;
-        const unsigned long long row_end = x_addr + r * stride_bytes + row_bytes_exact;
-        if (((row_end + 15ull) & ~15ull) <= span_end) break;
-        ++tail_rows;
-    }
-    if (head_rows + tail_rows >= rows) return false;
-    s->row_lo = head_rows;
+    while (tail_rows < rows && (rows - 1ull - tail_rows) * stride_bytes + 16ull * slots > span) ++tail_rows;
+    if (tail_rows >= rows) return false;
     s->row_hi = rows - tail_rows;
-    // 256-thread blocks: one wave per SIMD; two when steps are masked (their arithmetic then overlaps
-    // the other wave's loads)
-    unsigned long long g = (unsigned long long)cus * (s->all_plain ? 1u : 2u);
+    // 256-thread blocks: one wave per SIMD
+    unsigned long long g = (unsigned long long)cus;
     if (g * 4ull > s->iters) g = (s->iters + 3ull) / 4ull;
     *grid = (unsigned)g;
     return true;
@@ -374,10 +361,8 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
                 : dtype == MFR_DTYPE_BF16 ? mfr::launch_rows_tiled_bf16(x, rows, cols, row_stride, out, shape, grid, nt, stream)
                                           : mfr::launch_rows_tiled_f32(x, rows, cols, row_stride, out, shape, grid, nt, stream);
             if (e != hipSuccess) return hip_fail(e, "rows_tiled launch");
-            // the few rows at either end whose 16-byte slots would reach outside the array: one by one
-            for (size_t r = 0; r < rows; ++r) {
-                if (r == shape.row_lo) r = shape.row_hi;        // skip what the launch above covers
-                if (r >= rows) break;
+            // the few rows at the end whose last 16-byte slot would reach past the array: one by one
+            for (size_t r = shape.row_hi; r < rows; ++r) {
                 const int se = sum_rows_impl((const char *)x + r * row_stride * esize, dtype, 1, cols, cols, out + r,
                                              nullptr, stream);
                 if (se != MFR_OK) return se;
@@ -702,9 +687,9 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
     plan[2] = (unsigned long long)s.groups;
     plan[3] = s.iters;
     plan[4] = s.batches;
-    plan[5] = s.plain_lo;
+    plan[5] = 0;
     plan[6] = s.plain_hi;
-    plan[7] = s.row_lo;
+    plan[7] = 0;
     plan[8] = s.row_hi;
     plan[9] = s.all_plain ? 1ull : 0ull;
     plan[10] = grid;

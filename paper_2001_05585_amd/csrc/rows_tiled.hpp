@@ -23,56 +23,66 @@
 // are issued before step s is consumed (two register buffers), so that a wave
 // always has loads in flight.
 //
-// Rows may start at any element (any 16-byte phase, any stride >= cols): a
-// row's slots are counted from the 16-byte boundary at or below its first
-// element, and slots that are only partly inside the row are masked after loading
-// (the bytes outside belong to the gap or to the neighbouring rows, inside the
-// array's span).  The few rows at either end whose slots could reach outside
-// the span [x, x + span) are left out: the kernel stores rows [row_lo, row_hi)
-// only and the host sums the others with the single-row kernel.  Steps in
-// which every slot is whole ("plain") run without masks.
+// A row's slots are counted from its own first element, wherever that lies:
+// the 128-bit loads need no more than the element's alignment (the device
+// serves unaligned vector loads), so rows of any 16-byte phase and any stride
+// >= cols look alike and nothing before a row's start is ever read.  Only the
+// last step of a row can hold slots that are partly or wholly past the row's
+// end; their position is the same for every row, so each lane prepares, once,
+// the byte offsets and the bit masks of its slots in that step (a slot wholly
+// past the end is replaced by the row's first slot and masked to zero).  The
+// bytes masked away belong to the gap or to the next rows, inside the array's
+// span; the few rows at the end whose last slot would reach past the span are
+// left out -- the kernel stores rows [0, row_hi) and the host sums the others
+// with the single-array kernel.
 #pragma once
 #include "mfr_kernels.hpp"
-
-#include <type_traits>
 
 namespace mfr {
 
 struct RowsArgs {
     const char *x;                   // first element of row 0
-    unsigned long long span;         // bytes from x to one past the last element of the last row
     unsigned long long rows;
     unsigned long long cols;
     unsigned long long stride_bytes;
     unsigned long long iters;        // ceil(rows / rows per iteration)
-    unsigned long long row_lo;       // rows [row_lo, row_hi) are summed here: all their slots lie inside the span
-    unsigned long long row_hi;
+    unsigned long long row_hi;       // rows [0, row_hi) are summed here: all their slots lie inside the span
     unsigned int batches;            // steps per row
-    unsigned int plain_lo;           // steps [plain_lo, plain_hi) consist of whole in-row slots only
-    unsigned int plain_hi;
+    unsigned int plain_hi;           // steps [0, plain_hi) consist of whole in-row slots; plain_hi >= batches - 1
     float *out;
 };
 
-// Keep elements [lo, hi) of a slot, zero the rest (lo, hi already clamped to 0 .. per_slot).
-template <int DT>
-__device__ __forceinline__ uint4v mask_slot(uint4v v, int lo, int hi)
+// a 16-byte slot at element alignment
+typedef uint4v slot_unaligned __attribute__((aligned(2)));
+
+template <bool NT>
+__device__ __forceinline__ uint4v load_slot_at(const char *p)
 {
-    const unsigned km = hi > lo ? ((1u << hi) - (1u << lo)) : 0u;     // bit t set: element t stays
+    if constexpr (NT) return __builtin_nontemporal_load((const slot_unaligned *)p);
+    else return *(const slot_unaligned *)p;
+}
+
+// Bit mask that keeps the first `hi` elements of a slot (0 <= hi <= per_slot).
+template <int DT>
+__device__ __forceinline__ uint4v keep_first(int hi)
+{
+    const unsigned km = (1u << hi) - 1u;                               // bit t set: element t stays
+    uint4v m;
     if constexpr (ElemTraits<DT>::per_slot == 8) {
-        unsigned m[4];
+        unsigned w[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const unsigned a = (unsigned)(-(int)((km >> (2 * i)) & 1u)), b = (unsigned)(-(int)((km >> (2 * i + 1)) & 1u));
-            m[i] = (a & 0xffffu) | (b & 0xffff0000u);
+            w[i] = (a & 0xffffu) | (b & 0xffff0000u);
         }
-        v.x &= m[0]; v.y &= m[1]; v.z &= m[2]; v.w &= m[3];
+        m.x = w[0]; m.y = w[1]; m.z = w[2]; m.w = w[3];
     } else {
-        v.x &= (unsigned)(-(int)(km & 1u));
-        v.y &= (unsigned)(-(int)((km >> 1) & 1u));
-        v.z &= (unsigned)(-(int)((km >> 2) & 1u));
-        v.w &= (unsigned)(-(int)((km >> 3) & 1u));
+        m.x = (unsigned)(-(int)(km & 1u));
+        m.y = (unsigned)(-(int)((km >> 1) & 1u));
+        m.z = (unsigned)(-(int)((km >> 2) & 1u));
+        m.w = (unsigned)(-(int)((km >> 3) & 1u));
     }
-    return v;
+    return m;
 }
 
 template <int LP>
@@ -86,14 +96,13 @@ __device__ __forceinline__ float fold_columns(float v)
 }
 
 // DT: element type.  LP: log2 P.  D: tiles of a row per step.  GF: groups side by side.
-// ALLPLAIN: the host guarantees that every step is plain (aligned rows of a whole number of steps).
+// ALLPLAIN: every step consists of whole in-row slots (cols is a multiple of the elements per step).
 // NT: non-temporal loads and stores.
 template <int DT, int LP, int D, int GF, bool ALLPLAIN, bool NT>
 __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 {
     constexpr unsigned P = 1u << LP, RPT = 16u / P;
-    constexpr int E = (int)ElemTraits<DT>::per_slot;
-    constexpr int LOG_ES = E == 8 ? 1 : 2;
+    constexpr long long E = (long long)ElemTraits<DT>::per_slot;
     const unsigned lane = threadIdx.x & 63u;
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const unsigned wpb = blockDim.x >> 6;
@@ -103,61 +112,57 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
     const unsigned part = j & (P - 1u), row_local = j >> LP;
     const unsigned s_lane = part + P * q;          // this lane's slot inside a tile's 4 P slots per row
 
-    // Row of this lane in group u of iteration `it`: byte offset of its first element from x, and
-    // the bytes of its first slot that lie before it.  Rows outside [row_lo, row_hi) are replaced by
-    // the nearest row inside (their sums are not stored).
-    auto row_of = [&](unsigned long long it, int u, unsigned long long &off, unsigned &ph) {
-        unsigned long long r = (it * GF + u) * RPT + row_local;
-        r = r < a.row_lo ? a.row_lo : (r < a.row_hi ? r : a.row_hi - 1ull);
-        off = r * a.stride_bytes;
-        ph = (unsigned)(((unsigned long long)a.x + off) & 15ull);
-    };
+    // The last step of a row, if it is not plain: byte offset of each of this lane's slots from the
+    // row's start (0 for a slot wholly past the end) and the mask of the elements inside the row.
+    unsigned long long last_off[D];
+    uint4v last_keep[D];
+    if constexpr (!ALLPLAIN) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const unsigned long long s = s_lane + 4ull * P * ((unsigned)d + (unsigned long long)D * (a.batches - 1u));
+            long long left = (long long)a.cols - E * (long long)s;          // elements of the row from this slot on
+            left = left < 0 ? 0 : (left > E ? E : left);
+            last_off[d] = left > 0 ? 16ull * s : 0ull;
+            last_keep[d] = keep_first<DT>((int)left);
+        }
+    }
 
-    // Loads of one step.  Without ALLPLAIN a slot may lie past the row's end: it is replaced by the
-    // row's first slot (and masked to zero later).  Plain and masked steps share this code, so that
-    // the stream of loads does not depend on control flow.
-    auto issue = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], unsigned (&phase)[GF]) {
+    // Byte offset from x of the row of this lane in group u of iteration `it`.  Rows from row_hi on
+    // are replaced by row row_hi - 1 (their sums are not stored).
+    auto row_offset = [&](unsigned long long it, int u) {
+        unsigned long long r = (it * GF + u) * RPT + row_local;
+        r = r < a.row_hi ? r : a.row_hi - 1ull;
+        return r * a.stride_bytes;
+    };
+    auto is_plain = [&](unsigned cb) { return ALLPLAIN || cb < a.plain_hi; };
+
+    // Loads of one step.  The address of a slot is chosen by a select, not by a branch, so that the
+    // stream of loads does not depend on control flow.
+    auto issue = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D]) {
+        const bool plain = is_plain(cb);
 #pragma unroll
         for (int u = 0; u < GF; ++u) {
-            unsigned long long off; unsigned ph;
-            row_of(it, u, off, ph);
-            phase[u] = ph;                                                       // kept for the masks
-            const long long slot0 = (long long)off - (long long)ph;              // first slot of the row, from x
-            const long long vend = (long long)(ph >> LOG_ES) + (long long)a.cols;  // row end in slot-relative elements
+            const char *row = a.x + row_offset(it, u);
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                const unsigned s = s_lane + 4u * P * ((unsigned)d + (unsigned)D * cb);
-                const long long rel = slot0 + 16ll * s;
-                if constexpr (ALLPLAIN) {
-                    v[u][d] = load_slot<NT>((const uint4v *)(a.x + rel));
-                } else {
-                    const bool inside = (long long)E * s < vend;
-                    v[u][d] = load_slot<NT>((const uint4v *)(a.x + (inside ? rel : slot0)));
-                }
+                unsigned long long rel = 16ull * (s_lane + 4ull * P * ((unsigned)d + (unsigned long long)D * cb));
+                if constexpr (!ALLPLAIN) rel = plain ? rel : last_off[d];
+                v[u][d] = load_slot_at<NT>(row + rel);
             }
         }
     };
-    auto is_plain = [&](unsigned cb) { return ALLPLAIN || (cb >= a.plain_lo && cb < a.plain_hi); };
 
     float4v acc[GF];                                                 // C_0 = 0
 #pragma unroll
     for (int u = 0; u < GF; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    auto consume = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], const unsigned (&phase)[GF]) {
+    auto consume = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D]) {
         if constexpr (!ALLPLAIN) {
             if (!is_plain(cb)) {
 #pragma unroll
-                for (int u = 0; u < GF; ++u) {
-                    const long long head = (long long)(phase[u] >> LOG_ES), vend = head + (long long)a.cols;
+                for (int u = 0; u < GF; ++u)
 #pragma unroll
-                    for (int d = 0; d < D; ++d) {
-                        const long long e0 = (long long)E * (s_lane + 4u * P * ((unsigned)d + (unsigned)D * cb));
-                        long long lo = head - e0, hi = vend - e0;
-                        lo = lo < 0 ? 0 : (lo > E ? E : lo);
-                        hi = hi < 0 ? 0 : (hi > E ? E : hi);
-                        v[u][d] = mask_slot<DT>(v[u][d], (int)lo, (int)hi);
-                    }
-                }
+                    for (int d = 0; d < D; ++d) v[u][d] &= last_keep[d];
             }
         }
 #pragma unroll
@@ -174,7 +179,7 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
                 for (int u = 1; u < 4 && 4 * h + u < GF; ++u) val = q == (unsigned)u ? acc[4 * h + u].x : val;
                 val = fold_columns<LP>(val);
                 const unsigned long long r = (it * GF + 4u * h + q) * RPT + row_local;
-                if (part == 0u && 4u * h + q < (unsigned)GF && r >= a.row_lo && r < a.row_hi) {
+                if (part == 0u && 4u * h + q < (unsigned)GF && r < a.row_hi) {
                     // a store instruction covers 64 / P rows; streaming stores pay only for whole 128-byte lines
                     if constexpr (NT && LP <= 1) __builtin_nontemporal_store(val, a.out + r);
                     else a.out[r] = val;
@@ -194,30 +199,29 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
         if (++cb == a.batches) { cb = 0u; it += W; }
     };
     uint4v v0[GF][D], v1[GF][D];
-    unsigned ph0[GF], ph1[GF];
     unsigned long long it0 = w, it1 = w;
     unsigned cb0 = 0u, cb1 = 0u;
     unsigned long long k = 0;                   // step held in v0
-    issue(it0, cb0, v0, ph0);
+    issue(it0, cb0, v0);
     while (k + 2ull < steps) {
         it1 = it0; cb1 = cb0; advance(it1, cb1);
-        issue(it1, cb1, v1, ph1);
+        issue(it1, cb1, v1);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it0, cb0, v0, ph0);
+        consume(it0, cb0, v0);
         it0 = it1; cb0 = cb1; advance(it0, cb0);
-        issue(it0, cb0, v0, ph0);
+        issue(it0, cb0, v0);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it1, cb1, v1, ph1);
+        consume(it1, cb1, v1);
         k += 2ull;
     }
     if (k + 1ull < steps) {
         it1 = it0; cb1 = cb0; advance(it1, cb1);
-        issue(it1, cb1, v1, ph1);
+        issue(it1, cb1, v1);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it0, cb0, v0, ph0);
-        consume(it1, cb1, v1, ph1);
+        consume(it0, cb0, v0);
+        consume(it1, cb1, v1);
     } else {
-        consume(it0, cb0, v0, ph0);
+        consume(it0, cb0, v0);
     }
 }
 
@@ -244,15 +248,12 @@ hipError_t launch_rows_tiled_dt(const void *x, unsigned long long rows, unsigned
     constexpr unsigned esize = 16u / ElemTraits<DT>::per_slot;
     RowsArgs a;
     a.x = (const char *)x;
-    a.span = ((rows - 1ull) * row_stride + cols) * esize;
     a.rows = rows;
     a.cols = cols;
     a.stride_bytes = row_stride * esize;
     a.iters = s.iters;
-    a.row_lo = s.row_lo;
     a.row_hi = s.row_hi;
     a.batches = s.batches;
-    a.plain_lo = s.plain_lo;
     a.plain_hi = s.plain_hi;
     a.out = out;
     const int key = s.log2_p * 100 + s.tiles_per_step * 10 + s.groups;

@@ -6,9 +6,9 @@ test checks what the kernel relies on for memory safety and for correctness:
 
 * every element of every row is kept by exactly one (step, tile, lane),
 * the slots of unmasked steps lie wholly inside their row,
-* every whole-slot load of a masked step (including the substitute slot of a
-  lane past the row's end) lies inside the array's span, for the rows the
-  kernel is given; the rows it is not given are few,
+* every load of the masked last step (including the substitute slot of a lane
+  past the row's end) lies inside the array's span, for the rows the kernel is
+  given; the rows it is not given are few,
 * rows map to store lanes one to one.
 """
 import numpy as np
@@ -30,7 +30,7 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
     RPT = 16 // P
     rpi = GF * RPT
     assert iters == -(-rows // rpi)
-    assert 1 <= grid <= cus * (1 if all_plain else 2) and grid * 4 >= min(iters, cus * 4) - 3
+    assert 1 <= grid <= cus and grid * 4 >= min(iters, cus * 4) - 3
     span = ((rows - 1) * stride + cols) * es
     lane = np.arange(64)
     j, q = lane & 15, lane >> 4
@@ -38,49 +38,45 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
     s_lane = part + P * q
     covered = np.zeros((rows, cols), dtype=np.int32)
     stored = np.zeros(rows, dtype=np.int32)
+    assert plain_lo == 0 and row_lo == 0
+    assert batches - 1 <= plain_hi <= batches          # at most the last step is masked
+    assert all_plain == (1 if plain_hi == batches else 0)
     if all_plain:
-        assert plain_lo == 0 and plain_hi == batches and row_lo == 0 and row_hi == rows
-    assert 0 <= row_lo < row_hi <= rows
-    assert row_lo <= 8 and rows - row_hi <= 8         # only rows within 16 bytes of either end are left out
+        assert row_hi == rows
+    assert 0 < row_hi <= rows and rows - row_hi <= 8    # only rows within 16 bytes of the end are left out
     for it in range(iters):
         for u in range(GF):
             r_raw = (it * GF + u) * RPT + row_local
-            r = np.clip(r_raw, row_lo, row_hi - 1)
-            off = r * stride * es
-            ph = (x_addr + off) & 15
-            slot0 = off - ph                       # byte offset of the row's first slot from x
-            head = ph // es
-            vend = head + cols
+            r = np.minimum(r_raw, row_hi - 1)
+            off = r * stride * es                  # byte offset of the row's first element from x
             for cb in range(batches):
-                plain = plain_lo <= cb < plain_hi
+                plain = cb < plain_hi
                 for d in range(D):
                     s = s_lane + 4 * P * (d + D * cb)
-                    rel = slot0 + 16 * s
+                    rel = off + 16 * s
                     e0 = E * s
                     if plain:
-                        # unmasked 128-bit load: the slot must be whole and inside the row
-                        assert np.all(e0 >= head) and np.all(e0 + E <= vend), (it, u, cb, d)
-                        assert np.all(rel >= 0) and np.all(rel + 16 <= span)
-                        lo, hi = np.zeros(64, int), np.full(64, E)
+                        # the slot must be whole and inside the row
+                        assert np.all(e0 + E <= cols), (it, u, cb, d)
+                        assert np.all(rel + 16 <= span)
+                        hi = np.full(64, E)
                     else:
-                        inside = e0 < vend
-                        addr = np.where(inside, rel, slot0)
+                        hi = np.clip(cols - e0, 0, E)
+                        addr = np.where(hi > 0, rel, off)      # a slot past the end is replaced by the first slot
                         assert np.all(addr >= 0) and np.all(addr + 16 <= span), (it, u, cb, d)
-                        lo = np.clip(head - e0, 0, E)
-                        hi = np.clip(vend - e0, 0, E)
                     for ln in range(64):
-                        if not (row_lo <= r_raw[ln] < row_hi):
+                        if r_raw[ln] >= row_hi:
                             continue
-                        for t in range(lo[ln], hi[ln]):
-                            c = e0[ln] + t - head[ln]
+                        for t in range(hi[ln]):
+                            c = e0[ln] + t
                             assert 0 <= c < cols
                             covered[r[ln], c] += 1
             # store lanes: part 0, q == u mod 4
-            mine = (part == 0) & (q == (u & 3)) & (r_raw >= row_lo) & (r_raw < row_hi)
+            mine = (part == 0) & (q == (u & 3)) & (r_raw < row_hi)
             for ln in np.nonzero(mine)[0]:
                 stored[r_raw[ln]] += 1
-    assert np.all(covered[row_lo:row_hi] == 1) and not covered[:row_lo].any() and not covered[row_hi:].any()
-    assert np.all(stored[row_lo:row_hi] == 1) and not stored[:row_lo].any() and not stored[row_hi:].any()
+    assert np.all(covered[:row_hi] == 1) and not covered[row_hi:].any()
+    assert np.all(stored[:row_hi] == 1) and not stored[row_hi:].any()
     return plan
 
 
@@ -105,13 +101,16 @@ def test_replay_of_listed_shapes(dtype, shape):
     assert plan is not None
 
 
-def test_aligned_power_of_two_rows_are_unmasked():
+def test_power_of_two_rows_are_unmasked_at_any_alignment():
     for cols, P in ((32, 1), (64, 2), (128, 4), (256, 8), (512, 16), (1024, 16), (4096, 16)):
         plan = B.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F16, 4096, cols, cols, 256)
         assert plan is not None and plan[0] == P and plan[9] == 1, (cols, plan)
     # binary32: a slot holds four values
     plan = B.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F32, 4096, 64, 64, 256)
     assert plan[0] == 4 and plan[9] == 1
+    # slots are counted from each row's first element: the base address and the stride do not matter
+    plan = B.mfr_rows_plan((1 << 20) + 6, B.MFR_DTYPE_F16, 4096, 64, 67, 256)
+    assert plan[0] == 2 and plan[9] == 1 and plan[8] == 4096
 
 
 def test_choice_between_kernels():
