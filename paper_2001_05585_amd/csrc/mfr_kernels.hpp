@@ -50,12 +50,10 @@ struct SumArgs {
     unsigned long long epi1;
     unsigned long long slots;    // total slots covering [x, x + n)
     unsigned long long row_slots;  // distance between rows in slots (rows share the 16-byte phase)
-    unsigned long long rows;     // rows of this launch
     unsigned long long split_chains;  // MFR_KERNEL_SPLIT: chains [0, split_chains) take the MFMA path ...
     unsigned long long split_waves;   // ... on waves [0, split_waves); the rest is conventional
     unsigned long long ticket_stride;  // ticket words per row
     unsigned int ticket_flat;    // nonzero: one ticket counter per row, else two levels
-    unsigned int wave_rows;      // nonzero: every wave reduces a row of its own (short rows)
     unsigned int head;           // elements of slot 0 that lie before x
     float *partials;             // gridDim.x per row
     unsigned int *ticket;        // one per row; nullptr = two-launch combine
@@ -378,15 +376,11 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
     const unsigned lane = threadIdx.x & 63u;
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform
     const unsigned wpb = (blockDim.x + 63u) >> 6;
-    // Normal mode: the gridDim.x blocks of row blockIdx.y share that row.
-    // Wave-row mode (short rows): wave `wave` of block blockIdx.y owns row
-    // blockIdx.y * wpb + wave and nothing is combined across waves.
-    const bool wave_rows = a.wave_rows != 0u;
-    const unsigned long long W = wave_rows ? 1ull : (unsigned long long)gridDim.x * wpb;
-    const unsigned long long w = wave_rows ? 0ull : (unsigned long long)blockIdx.x * wpb + wave;
+    // The gridDim.x blocks of row blockIdx.y share that row.
+    const unsigned long long W = (unsigned long long)gridDim.x * wpb;
+    const unsigned long long w = (unsigned long long)blockIdx.x * wpb + wave;
 
-    const unsigned long long row = wave_rows ? (unsigned long long)blockIdx.y * wpb + wave : blockIdx.y;
-    if (row >= a.rows) return;          // whole waves only (wave-row mode); no barrier follows for them
+    const unsigned long long row = blockIdx.y;
     const uint4v *base = a.base + row * a.row_slots;
     const void *x = (const char *)a.x + row * a.row_slots * 16ull;
 
@@ -403,11 +397,6 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
             partial = wave64_sum(stream_chains<MFR_KERNEL_SHFL, DT, R, U, NT, HALF>(a, base, x, lane, C1 + (w - W1),
                                                                                   a.chains, W - W1, w == W - 1));
         }
-    }
-
-    if (wave_rows) {
-        if (lane == 0) a.out[row] = partial;
-        return;
     }
 
     // Level 2: one value per block from its wave partials.

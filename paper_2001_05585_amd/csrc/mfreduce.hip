@@ -82,10 +82,9 @@ void resolve_load_policy(mfr_tuning *t, size_t bytes)
 {
     if (t->nontemporal == 0) t->nontemporal = bytes <= kTemporalBytes ? 1 : 2;
 }
-constexpr size_t kWaveRowBytes = 8192;         // rows shorter than this get a wave each when there are many
 // The tiled rows kernel takes over from this many rows on; long rows (one row per tile) from
 // fewer, and rows of differing 16-byte phase from fewer still (the alternative is a launch per row).
-constexpr size_t kRowsTiledMinRows = 2048;
+constexpr size_t kRowsTiledMinRows = 1024;
 constexpr size_t kRowsTiledMinLongRows = 512;
 constexpr size_t kRowsTiledMinMixedRows = 32;
 // Rows of this many bytes or more are walked one per wave, 4 KiB per step, instead of four side by
@@ -371,25 +370,11 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
         }
     }
 
-    // Many short rows: every wave reduces a row of its own (no cross-wave or
-    // cross-block combine); chosen by the library only, with its own geometry.
-    const bool wave_rows = same_phase && tin == nullptr && cols * esize < kWaveRowBytes &&
-                           rows >= (size_t)info.cus * 4;
-    if (wave_rows) {
-        // one chain covers the whole row where possible, so that all of a row's
-        // loads are in flight together
-        size_t tiles = cols * esize / 1024;
-        t.block_threads = 256;
-        t.chain_R = tiles < 1 ? 1 : (tiles > 8 ? 8 : (int)tiles);
-        t.chains_in_flight = 1;
-    }
-    const size_t rows_per_block = wave_rows ? (size_t)t.block_threads / 64 : 1;
-    const size_t batch = !same_phase ? 1
-                         : (rows < kMaxRowsPerLaunch * rows_per_block ? rows : kMaxRowsPerLaunch * rows_per_block);
+    const size_t batch = !same_phase ? 1 : (rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch);
 
     Plan p;
     plan_region(cols, (size_t)x, esize, t, &p);
-    const long long grid = wave_rows ? 1 : grid_blocks_for(p, t, info.cus, batch);
+    const long long grid = grid_blocks_for(p, t, info.cus, batch);
     if (grid < 1) return MFR_ERR_INVALID_ARG;
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
@@ -420,15 +405,12 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
             p.a.split_waves = w1;
             p.a.split_chains = c1;
         }
-        p.a.rows = nr;
-        p.a.wave_rows = wave_rows ? 1u : 0u;
         p.a.partials = s.partials;
         p.a.ticket = two_launches ? nullptr : s.tickets;
         p.a.ticket_stride = mfr::ticket_words((unsigned)grid, ticket_flat);
         p.a.ticket_flat = ticket_flat ? 1u : 0u;
         p.a.out = out + r0;
-        const size_t grid_y = (nr + rows_per_block - 1) / rows_per_block;
-        const hipError_t e = launch_dtype(dtype, p, dim3((unsigned)grid, (unsigned)grid_y), t, stream);
+        const hipError_t e = launch_dtype(dtype, p, dim3((unsigned)grid, (unsigned)nr), t, stream);
         if (e != hipSuccess) return hip_fail(e, "kernel launch");
         if (grid > 1 && two_launches) {
             hipLaunchKernelGGL(combine_kernel, dim3((unsigned)nr), dim3(grid > 4096 ? 1024 : 256), 0, stream,
@@ -537,7 +519,6 @@ int sum_wide_impl(const mfr_half *x, size_t n, double *out, const mfr_tuning *ti
     }
     p.a.base = (const uint4v *)((size_t)x & ~(size_t)15);
     p.a.x = x;
-    p.a.rows = 1;
     p.a.partials = s.partials;          // hipMalloc'ed: 8-byte aligned
     p.a.ticket = two_launches ? nullptr : s.tickets;
     p.a.ticket_flat = ticket_flat ? 1u : 0u;

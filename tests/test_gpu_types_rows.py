@@ -183,8 +183,8 @@ def test_rows_integer_inputs_bit_exact(rows, cols, stride, oracle_lib):
 
 
 @pytest.mark.parametrize("cols", [5, 37, 512, 1000, 3000, 4095])
-def test_many_short_rows_one_wave_each(cols, oracle_lib):
-    # library defaults + many short rows: every wave reduces a row of its own
+def test_many_short_rows_with_padded_stride(cols, oracle_lib):
+    # library defaults + many short rows: the many-rows kernel, rows 16-byte aligned or shifted by 3 elements
     rows = 2051
     stride = (cols + 7) // 8 * 8 + 8
     flat = W.small_integers(rows * stride + 16, seed=cols)
@@ -202,8 +202,8 @@ def test_many_short_rows_one_wave_each(cols, oracle_lib):
 
 
 @pytest.mark.parametrize("cols", [1, 5, 31, 32, 33, 37, 64, 65, 100, 128, 129, 256, 700, 767])
-def test_many_short_rows_sixteen_per_mfma_chain(cols, oracle_lib):
-    # library defaults, >= 4096 rows, 16-byte aligned rows of a 16-bit type: 16 row sums per MFMA chain
+def test_many_short_rows_library_default(cols, oracle_lib):
+    # library defaults, >= 4096 rows of a 16-bit type: the accumulator columns of a chain shared out among rows
     rows = 5003
     stride = (cols + 7) // 8 * 8 + (8 if cols % 16 else 0)
     flat = W.small_integers(rows * stride + 16, seed=cols + 1)
