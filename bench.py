@@ -206,6 +206,43 @@ def traffic(args):
                       "copy_bytes_read": 2 * n, "copy_bytes_written": 2 * n, "result": float(out[0].item())}))
 
 
+ROWS_TRAFFIC_SHAPES = (
+    # (dtype name, cols, stride, shift in elements); rows fill 512 MiB
+    ("f16", 32, 32, 0), ("f16", 64, 64, 0), ("f16", 100, 100, 0), ("f16", 256, 256, 0), ("f16", 1001, 1001, 0),
+    ("f16", 1024, 1024, 0), ("f16", 4096, 4096, 0), ("f16", 256, 256, 1), ("f32", 256, 256, 0),
+)
+
+
+def traffic_rows(args):
+    """The same kind of run for the many-rows kernel: each shape four times on rotating buffers, in
+    the order of ROWS_TRAFFIC_SHAPES, then the calibration copy."""
+    import numpy as np
+    import torch
+    from paper_2001_05585_amd import binding as B
+    from paper_2001_05585_amd import workloads as W
+    torch.cuda.set_device(0)
+    n = 1 << 28
+    x = W.generate("normal", n, W.config_seed(3))
+    bufs = make_buffers(torch, np, x, 4)
+    dst = torch.empty_like(bufs[0])
+    out = torch.zeros(1 << 23, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    shapes = []
+    for name, cols, stride, shift in ROWS_TRAFFIC_SHAPES:
+        dtype, esize = (B.MFR_DTYPE_F32, 4) if name == "f32" else (B.MFR_DTYPE_F16, 2)
+        rows = (2 * n // esize) // stride - (1 if shift else 0)
+        for i in range(4):
+            B.mfr_sum_rows_ex(bufs[i].data_ptr() + shift * esize, dtype, rows, cols, stride, out.data_ptr(), None, stream)
+        torch.cuda.synchronize()
+        shapes.append({"type": name, "rows": rows, "cols": cols, "stride": stride, "shift": shift, "launches": 4,
+                       "bytes_read": rows * cols * esize, "bytes_written": rows * 4})
+    for i in range(4):
+        torch.mul(bufs[i % len(bufs)], 1, out=dst)       # elementwise copy kernel of known size
+    torch.cuda.synchronize()
+    print(json.dumps({"mode": "traffic-rows", "shapes": shapes, "copy_launches": 4, "copy_bytes_read": 2 * n,
+                      "copy_bytes_written": 2 * n}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -222,6 +259,7 @@ def main():
     ap.add_argument("--combine", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic", action="store_true", help="short run for rocprofv3 --pmc counters")
+    ap.add_argument("--traffic-rows", action="store_true", help="the same for the many-rows kernel")
     ap.add_argument("--sweep", choices=["config2", "config5", "tune", "types", "rows", "tune_f32", "split", "variants", "wide", "combine", "warm"], default=None)
     ap.add_argument("--quick", type=int, default=0, help="sweeps: keep every k-th combination")
     ap.add_argument("--out", default=None, help="file for sweep tables (default: <results folder>/<sweep>.txt)")
@@ -234,6 +272,8 @@ def main():
         build.build()
     if args.traffic:
         traffic(args)
+    elif args.traffic_rows:
+        traffic_rows(args)
     elif args.sweep:
         import bench_sweeps
         bench_sweeps.run(args)
