@@ -197,7 +197,15 @@ int mfr_sum_f16_f64_ex(const mfr_half *x, size_t n, double *out, const mfr_tunin
  */
 int mfr_sum_f16_recurrence(const mfr_half *x, size_t n, float *out, int chain_R, hipStream_t stream);
 
-/* The geometry mfr_sum_f16 uses.  Any pointer may be NULL. */
+/*
+ * The geometry mfr_sum_f16 uses.  Any pointer may be NULL.
+ * The environment variables MFR_BLOCK (32 .. 1024, a power of two) and MFR_R
+ * (1 .. 8), read once per process, replace the built-in default block size and
+ * chain length wherever a call leaves them to the library (the B and R of
+ * Section 5.2 without recompiling the caller); if either is set to anything
+ * else, this call and every call that relies on the default return
+ * MFR_ERR_INVALID_ARG.  block 32 is for binary16 only.
+ */
 int mfr_get_default_tuning(int *block_threads, int *chain_R, int *grid_blocks);
 
 /* Number of blocks a call with this tuning would launch for n elements whose

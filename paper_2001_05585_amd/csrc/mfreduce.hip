@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -78,6 +79,36 @@ constexpr size_t kMaxRowsPerLaunch = 65535;    // gridDim.y limit
 // faster from HBM).
 constexpr size_t kTemporalBytes = (size_t)32 << 20;
 
+// The default block size and chain length, after the optional environment override (MFR_BLOCK,
+// MFR_R; read once per process).  `valid` is false if a variable is set to something unusable:
+// every call that relies on the default then fails, rather than silently running another geometry.
+struct DefaultGeometry {
+    int block;
+    int chain_R;      // 0: the per-type default
+    bool valid;
+};
+
+const DefaultGeometry &default_geometry()
+{
+    static const DefaultGeometry g = [] {
+        DefaultGeometry d = {kDefaultBlock, 0, true};
+        if (const char *e = getenv("MFR_BLOCK")) {
+            char *end = nullptr;
+            const long v = strtol(e, &end, 10);
+            if (end == e || *end != '\0' || !(v == 32 || v == 64 || v == 128 || v == 256 || v == 512 || v == 1024)) d.valid = false;
+            else d.block = (int)v;
+        }
+        if (const char *e = getenv("MFR_R")) {
+            char *end = nullptr;
+            const long v = strtol(e, &end, 10);
+            if (end == e || *end != '\0' || v < 1 || v > 8) d.valid = false;
+            else d.chain_R = (int)v;
+        }
+        return d;
+    }();
+    return g;
+}
+
 void resolve_load_policy(mfr_tuning *t, size_t bytes)
 {
     if (t->nontemporal == 0) t->nontemporal = bytes <= kTemporalBytes ? 1 : 2;
@@ -121,8 +152,12 @@ int resolve_tuning(const mfr_tuning *in, int dtype, mfr_tuning *t)
     memset(&z, 0, sizeof z);
     if (in) z = *in;
     if (!valid_dtype(dtype)) return MFR_ERR_INVALID_ARG;
-    if (z.block_threads == 0) z.block_threads = kDefaultBlock;
-    if (z.chain_R == 0) z.chain_R = dtype == MFR_DTYPE_F32 ? kDefaultR_f32 : kDefaultR;
+    if (z.block_threads == 0 || z.chain_R == 0) {
+        const DefaultGeometry &g = default_geometry();
+        if (!g.valid) return MFR_ERR_INVALID_ARG;
+        if (z.block_threads == 0) z.block_threads = g.block;
+        if (z.chain_R == 0) z.chain_R = g.chain_R ? g.chain_R : (dtype == MFR_DTYPE_F32 ? kDefaultR_f32 : kDefaultR);
+    }
     if (!valid_block(z.block_threads)) return MFR_ERR_INVALID_ARG;
     if (z.block_threads == 32 && dtype != MFR_DTYPE_F16) return MFR_ERR_INVALID_ARG;
     if (z.chain_R < 1 || z.chain_R > 8) return MFR_ERR_INVALID_ARG;
@@ -605,8 +640,10 @@ int mfr_sum_f16_recurrence(const mfr_half *x, size_t n, float *out, int chain_R,
 
 int mfr_get_default_tuning(int *block_threads, int *chain_R, int *grid_blocks)
 {
-    if (block_threads) *block_threads = kDefaultBlock;
-    if (chain_R) *chain_R = kDefaultR;
+    const DefaultGeometry &g = default_geometry();
+    if (!g.valid) return MFR_ERR_INVALID_ARG;
+    if (block_threads) *block_threads = g.block;
+    if (chain_R) *chain_R = g.chain_R ? g.chain_R : kDefaultR;
     if (grid_blocks) *grid_blocks = MFR_GRID_AUTO;
     return MFR_OK;
 }
@@ -690,6 +727,6 @@ const char *mfr_strerror(int status)
 
 const char *mfr_last_hip_error(void) { return g_hip_error; }
 
-int mfr_version(void) { return 200; }
+int mfr_version(void) { return 300; }
 
 }  // extern "C"

@@ -454,3 +454,30 @@ def test_odd_pointer_is_rejected():
     d = DeviceInput(W.ones(64))
     o = Outputs(1)
     assert B.lib().mfr_sum_f16(d.ptr + 1, 8, o.ptr(0), None) == B.MFR_ERR_INVALID_ARG
+
+
+def test_environment_override_reaches_the_default_entry():
+    # MFR_BLOCK / MFR_R are read once per process: run in a fresh interpreter
+    import os
+    import subprocess
+    import sys
+    code = (
+        "import numpy as np, torch\n"
+        "from paper_2001_05585_amd import binding as B, workloads as W\n"
+        "x = torch.from_numpy(W.generate('normal', (1 << 22) + 5, 11).view(np.int16)).cuda()\n"
+        "o = torch.zeros(2, dtype=torch.float32, device='cuda')\n"
+        "s = torch.cuda.current_stream().cuda_stream\n"
+        "B.mfr_sum_f16(x.data_ptr(), x.numel(), o.data_ptr(), s)\n"
+        "B.mfr_sum_f16_ex(x.data_ptr(), x.numel(), o.data_ptr() + 4, B.make_tuning(64, 2), s)\n"
+        "torch.cuda.synchronize()\n"
+        "r = o.cpu().numpy().view(np.uint32)\n"
+        "print(B.mfr_get_default_tuning(), int(r[0]), int(r[1]), B.mfr_grid_for(x.numel(), x.data_ptr(), None))\n")
+    env = dict(os.environ, MFR_BLOCK="64", MFR_R="2")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], env=env, cwd=root, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    fields = r.stdout.strip().splitlines()[-1]
+    assert fields.startswith("(64, 2, 0)"), fields
+    bits_default, bits_explicit, grid = [int(v) for v in fields.split(")")[1].split()]
+    assert bits_default == bits_explicit            # the default entry ran the overridden geometry
+    assert grid == 4 * torch.cuda.get_device_properties(0).multi_processor_count   # 64-thread blocks: four per CU

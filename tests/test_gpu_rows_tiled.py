@@ -191,3 +191,21 @@ def test_more_rows_than_a_grid_dimension_and_tiny_rows():
         inp = RowsInput(F16, encode(F16, vals).reshape(rows, cols), stride, 0)
         got = call(F16, inp, rows, cols, stride).astype(np.float64)
         assert np.array_equal(got, vals.astype(np.float64).sum(axis=1)), (cols, stride)
+
+
+def test_repeat_calls_are_bit_identical_and_streams_do_not_interfere():
+    rows, cols, stride = 6000, 333, 340
+    bits = W.generate("normal", rows * cols, 4242).view(np.uint16).reshape(rows, cols)
+    inp = RowsInput(F16, bits, stride, 2)
+    first = call(F16, inp, rows, cols, stride).view(np.uint32).copy()
+    for _ in range(30):
+        assert np.array_equal(call(F16, inp, rows, cols, stride).view(np.uint32), first)
+    # two streams at once, each with its own output
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    o1, o2 = Outputs(rows), Outputs(rows)
+    torch.cuda.synchronize()
+    for _ in range(10):
+        B.mfr_sum_rows_ex(inp.ptr, F16, rows, cols, stride, o1.ptr(0), None, s1.cuda_stream)
+        B.mfr_sum_rows_ex(inp.ptr, F16, rows, cols, stride, o2.ptr(0), None, s2.cuda_stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(o1.get().view(np.uint32), first) and np.array_equal(o2.get().view(np.uint32), first)

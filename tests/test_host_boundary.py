@@ -156,3 +156,43 @@ def test_grid_for_one_chain_geometry():
     assert B.mfr_grid_for(0, 0, None) == 1
     assert B.mfr_grid_for(1 << 20, 0, B.make_tuning(256, 1, 7)) == 7
     assert B.mfr_grid_for(1 << 20, 0, B.make_tuning(100, 1, 7)) == -1
+
+
+def _in_fresh_process(env, code):
+    """Run `code` in a new interpreter (the library reads the environment once per process)."""
+    import subprocess
+    import sys
+    full = dict(os.environ)
+    full.update(env)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    return subprocess.run([sys.executable, "-c", code], env=full, cwd=root, capture_output=True, text=True, timeout=120)
+
+
+def test_environment_override_of_the_default_geometry():
+    code = ("from paper_2001_05585_amd import binding as B\n"
+            "print(B.mfr_get_default_tuning())\n"
+            "print(B.mfr_plan_for(1 << 20, 4096, None))\n")
+    base = _in_fresh_process({"MFR_BLOCK": "", "MFR_R": ""}, "import os\nos.environ.pop('MFR_BLOCK'); os.environ.pop('MFR_R')\n" + code)
+    assert base.returncode == 0, base.stderr
+    assert base.stdout.splitlines()[0] == "(256, 4, 0)"
+    r = _in_fresh_process({"MFR_BLOCK": "512", "MFR_R": "2"}, code)
+    assert r.returncode == 0, r.stderr
+    lines = r.stdout.splitlines()
+    assert lines[0] == "(512, 2, 0)"
+    # 2^20 halves = 2048 tiles of 64 slots: chains of R = 2 tiles instead of 4
+    assert eval(lines[1])[3] == 1024 and eval(base.stdout.splitlines()[1])[3] == 512
+    # explicit tuning is not affected
+    r = _in_fresh_process({"MFR_BLOCK": "512", "MFR_R": "2"},
+                          "from paper_2001_05585_amd import binding as B\n"
+                          "print(B.mfr_plan_for(1 << 20, 4096, B.make_tuning(128, 8))[3])\n")
+    assert r.stdout.strip() == "256"
+    for bad in ({"MFR_BLOCK": "100"}, {"MFR_R": "9"}, {"MFR_R": "four"}, {"MFR_BLOCK": "256x"}):
+        r = _in_fresh_process(bad, "from paper_2001_05585_amd import binding as B\n"
+                                   "import ctypes\n"
+                                   "b = ctypes.c_int()\n"
+                                   "print(B.lib().mfr_get_default_tuning(ctypes.byref(b), None, None))\n"
+                                   "plan = (ctypes.c_ulonglong * 7)()\n"
+                                   "print(B.lib().mfr_plan_for(1 << 20, 4096, None, plan))\n"
+                                   "print(B.lib().mfr_plan_for(1 << 20, 4096, ctypes.byref(B.make_tuning(128, 8)), plan))\n")
+        assert r.returncode == 0, r.stderr
+        assert r.stdout.split() == [str(B.MFR_ERR_INVALID_ARG), str(B.MFR_ERR_INVALID_ARG), str(B.MFR_OK)], (bad, r.stdout)
