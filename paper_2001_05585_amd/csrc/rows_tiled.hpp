@@ -127,12 +127,23 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
         }
     }
 
-    // Byte offset from x of the row of this lane in group u of iteration `it`.  Rows from row_hi on
-    // are replaced by row row_hi - 1 (their sums are not stored).
-    auto row_offset = [&](unsigned long long it, int u) {
-        unsigned long long r = (it * GF + u) * RPT + row_local;
-        r = r < a.row_hi ? r : a.row_hi - 1ull;
-        return r * a.stride_bytes;
+    // Byte offsets from x of this lane's rows in the GF groups of iteration `it`.  An iteration that
+    // lies wholly below row_hi needs one scalar product and an add per group; the last one replaces
+    // rows from row_hi on by row row_hi - 1 (their sums are not stored).
+    const unsigned long long lane_off = (unsigned long long)row_local * a.stride_bytes;
+    auto row_offsets = [&](unsigned long long it, unsigned long long (&off)[GF]) {
+        const unsigned long long first = it * (unsigned long long)(GF * RPT);          // wave-uniform
+        if (first + GF * RPT <= a.row_hi) {
+#pragma unroll
+            for (int u = 0; u < GF; ++u) off[u] = (first + (unsigned)u * RPT) * a.stride_bytes + lane_off;
+        } else {
+#pragma unroll
+            for (int u = 0; u < GF; ++u) {
+                unsigned long long r = first + (unsigned)u * RPT + row_local;
+                r = r < a.row_hi ? r : a.row_hi - 1ull;
+                off[u] = r * a.stride_bytes;
+            }
+        }
     };
     auto is_plain = [&](unsigned cb) { return ALLPLAIN || cb < a.plain_hi; };
 
@@ -140,9 +151,11 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
     // stream of loads does not depend on control flow.
     auto issue = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D]) {
         const bool plain = is_plain(cb);
+        unsigned long long off[GF];
+        row_offsets(it, off);
 #pragma unroll
         for (int u = 0; u < GF; ++u) {
-            const char *row = a.x + row_offset(it, u);
+            const char *row = a.x + off[u];
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 unsigned long long rel = 16ull * (s_lane + 4ull * P * ((unsigned)d + (unsigned long long)D * cb));
