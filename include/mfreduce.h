@@ -145,7 +145,8 @@ int mfr_sum_ex(const void *x, int dtype, size_t n, float *out, const mfr_tuning 
  * ones-matrix chains (Sections 4.1, 4.3).
  *   x           device pointer, aligned to the element size (no more)
  *   row_stride  distance between rows in elements, >= cols when rows > 1; any
- *               value, the rows need not share a 16-byte phase
+ *               value, the rows need not share a 16-byte phase; the whole span
+ *               (rows - 1) * row_stride + cols must be below 2^60 elements
  *   out         device pointer to rows floats
  * rows == 0 does nothing; cols == 0 writes zeros.
  * With t == NULL the library picks the kernel: many rows go through one launch

@@ -296,6 +296,16 @@ hipError_t launch_dtype(int dtype, const Plan &p, dim3 grid, const mfr_tuning &t
     }
 }
 
+// The array's span (rows - 1) * row_stride + cols must stay below 2^60 elements, so that byte
+// offsets cannot wrap.
+bool span_fits(size_t rows, size_t cols, size_t row_stride)
+{
+    const unsigned long long limit = 1ull << 60;
+    if (cols > limit) return false;
+    if (rows <= 1) return true;
+    return row_stride <= (limit - cols) / (rows - 1);
+}
+
 // Shape of the tiled rows kernel for rows x cols elements of `esize` bytes at byte address x_addr,
 // rows row_stride elements apart.  Returns false when the other kernels are the better choice:
 // few rows (they cannot fill the device here, a grid per row can), unless the rows differ in their
@@ -370,6 +380,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     if (((size_t)x & (esize - 1u)) != 0) return MFR_ERR_INVALID_ARG;
     if (cols > ((size_t)1 << 60) || rows > ((size_t)1 << 40)) return MFR_ERR_INVALID_ARG;
     if (rows > 1 && row_stride < cols) return MFR_ERR_INVALID_ARG;
+    if (!span_fits(rows, cols, row_stride)) return MFR_ERR_INVALID_ARG;
     if (rows == 0) return MFR_OK;
 
     int dev = 0;
@@ -696,6 +707,7 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
     const unsigned esize = elem_size(dtype);
     if ((x_addr & (esize - 1u)) || cols > ((size_t)1 << 60) || rows > ((size_t)1 << 40)) return -MFR_ERR_INVALID_ARG;
     if (rows > 1 && row_stride < cols) return -MFR_ERR_INVALID_ARG;
+    if (!span_fits(rows, cols, row_stride)) return -MFR_ERR_INVALID_ARG;
     const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
     mfr::RowsTiledShape s;
     unsigned grid = 0;

@@ -139,6 +139,7 @@ def test_typed_and_batched_entries_reject_bad_arguments():
     assert L.mfr_sum_ex(4096, -1, 5, 4096, None, None) == INV
     assert L.mfr_sum_f32(None, 5, 4096, None) == INV
     assert L.mfr_sum_rows_ex(4096, 0, 4, 100, 99, 4096, None, None) == INV   # stride < cols
+    assert L.mfr_sum_rows_ex(4096, 0, 4096, 100, 1 << 50, 4096, None, None) == INV   # span beyond 2^60 elements
     assert L.mfr_sum_rows_ex(None, 0, 4, 100, 100, 4096, None, None) == INV
     assert L.mfr_sum_rows_ex(4096, 0, 4, 100, 100, None, None, None) == INV
     assert L.mfr_sum_rows_ex(4096, 0, 0, 100, 100, 4096, None, None) == B.MFR_OK   # no rows: nothing to do

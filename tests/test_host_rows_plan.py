@@ -133,6 +133,8 @@ def test_invalid_arguments():
     assert L.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F16, 4096, 64, 63, 256, plan) == -B.MFR_ERR_INVALID_ARG
     assert L.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F16, 4096, 64, 64, 0, plan) == -B.MFR_ERR_INVALID_ARG
     assert L.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F16, 4096, 64, 64, 256, None) == -B.MFR_ERR_INVALID_ARG
+    assert L.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F16, 4096, 64, 1 << 50, 256, plan) == -B.MFR_ERR_INVALID_ARG   # span wraps
+    assert L.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F16, 4096, 64, 1 << 40, 256, plan) == 1
 
 
 @settings(max_examples=60, deadline=None)
