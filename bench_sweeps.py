@@ -460,7 +460,7 @@ def rows(args, torch, np, B, W):
         emit(f, "# type rows cols stride shift tuning kernel_shape us Gelem/s GB/s pct_of_8TB/s")
         f16 = B.MFR_DTYPE_F16
         total = total_bytes // 2
-        for lr in (0, 4, 8, 9, 10, 11, 12, 14, 16, 17, 18, 19, 20, 21, 22, 23):
+        for lr in (0, 1, 2, 3, 4, 5, 6, 8, 9, 10, 11, 12, 14, 16, 17, 18, 19, 20, 21, 22, 23):
             r, c = 1 << lr, total >> lr
             measure(f, f16, r, c, c, 0, None, "default")
             if lr >= 4 and args.quick != 2:

@@ -123,6 +123,7 @@ constexpr size_t kRowsTiledMinMixedRows = 32;
 // into the same memory channels.
 constexpr size_t kRowsTiledLongRowBytes = 4096;
 constexpr size_t kRowsTiledMaxRowBytes = 16384;
+constexpr size_t kFewRows = 64;                // up to this many rows share the grid with several blocks each
 
 int default_in_flight(int R)
 {
@@ -232,7 +233,7 @@ long long grid_blocks_for(const Plan &p, const mfr_tuning &t, int cus, size_t ro
         int per_cu = kDefaultWavesPerCU / p.waves;
         if (per_cu < 1) per_cu = 1;
         g = (unsigned long long)cus * (unsigned)per_cu;
-        if (rows > 1) g = (g + rows - 1) / rows;
+        if (rows > 1) g = g / rows;              // rounded down: a second round of blocks costs more than idle CUs
         if (g > need) g = need;
     } else {
         g = (unsigned long long)t.grid_blocks;
@@ -416,6 +417,14 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
         }
     }
 
+    // Rows that share the grid have few waves each, so the chains a wave has in flight together lie
+    // close to each other (a power-of-two distance when the rows are): one chain of 8 tiles, i.e.
+    // 8 KiB contiguous per wave, instead of two chains of 4 (84 % against 78 % of the HBM peak for
+    // 16 rows of 32 MiB).
+    if (tin == nullptr && rows > 1 && rows <= kFewRows && same_phase && dtype != MFR_DTYPE_F32) {
+        t.chain_R = 8;
+        t.chains_in_flight = 1;
+    }
     const size_t batch = !same_phase ? 1 : (rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch);
 
     Plan p;
