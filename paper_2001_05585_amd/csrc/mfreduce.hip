@@ -243,6 +243,30 @@ long long grid_blocks_for(const Plan &p, const mfr_tuning &t, int cus, size_t ro
     return (long long)g;
 }
 
+// Block size for `rows` rows sharing the persistent grid (one wave per SIMD in all): the CUs hold
+// cus * 256 / block blocks; a row gets floor(that / rows) of them (at least one).  Fewest rounds of
+// blocks first, then the fullest round; a smaller block must fill more than a tenth better to win.
+int block_threads_for_rows(size_t rows, int cus)
+{
+    int best_block = 256;
+    unsigned long long best_rounds = 0;
+    double best_fill = 0.0;
+    for (int block = 256; block >= 64; block /= 2) {
+        const unsigned long long slots = (unsigned long long)cus * (256u / (unsigned)block);
+        unsigned long long g = slots / rows;
+        if (g < 1) g = 1;
+        const unsigned long long blocks = g * rows;
+        const unsigned long long rounds = (blocks + slots - 1) / slots;
+        const double fill = (double)blocks / (double)(rounds * slots);
+        if (block == 256 || rounds < best_rounds || (rounds == best_rounds && fill > best_fill + 0.1)) {
+            best_block = block;
+            best_rounds = rounds;
+            best_fill = fill;
+        }
+    }
+    return best_block;
+}
+
 // One counter for all blocks when the grid is small, or when each wave has so
 // much to do that the blocks do not finish together; two levels otherwise.
 bool ticket_flat_for(long long grid, const Plan &p)
@@ -425,6 +449,9 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
         t.chain_R = 8;
         t.chains_in_flight = 1;
     }
+    // Row counts that do not divide the CUs well: smaller blocks, more of them per CU, fill the
+    // device in one round (300 rows: 86 % with 64-thread blocks against 70 % with 256-thread ones).
+    if (tin == nullptr && rows > 1 && same_phase) t.block_threads = block_threads_for_rows(rows, info.cus);
     const size_t batch = !same_phase ? 1 : (rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch);
 
     Plan p;

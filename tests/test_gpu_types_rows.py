@@ -170,7 +170,8 @@ def rows_call(dev_ptr, dtype, rows, cols, stride, tuning=None):
 
 @pytest.mark.parametrize("rows,cols,stride", [(1, 5000, 5000), (7, 4096, 4096), (33, 1000, 1000), (64, 777, 784),
                                               (5, 100003, 100008), (300, 512, 512), (3, 1, 8), (1000, 37, 40),
-                                              (9, 2049, 2051), (4, 65536 + 7, 65536 + 7)])
+                                              (9, 2049, 2051), (4, 65536 + 7, 65536 + 7),
+                                              (150, 30011, 30016), (300, 9001, 9008), (31, 40000, 40000)])
 def test_rows_integer_inputs_bit_exact(rows, cols, stride, oracle_lib):
     flat = W.small_integers(rows * stride + 16, seed=rows * 1000 + cols)
     for shift in (0, 3):
