@@ -159,8 +159,10 @@ int mfr_sum_ex(const void *x, int dtype, size_t n, float *out, const mfr_tuning 
  * slot would reach past it, are summed one by one).
  * With explicit tuning every row is reduced exactly as a single call would
  * (Section 5.2), grid_blocks counting blocks per row and MFR_GRID_AUTO dividing
- * the persistent grid among the rows; rows then share one launch only if the
- * row stride is a multiple of 16 bytes (otherwise one launch per row).
+ * the persistent grid among the rows (rounded down), all rows in one launch (up
+ * to 65535 rows per launch).  Rows whose stride is a multiple of 16 bytes are read
+ * in aligned 16-byte slots; otherwise every row is addressed from its own first
+ * element with 128-bit loads at element alignment.
  */
 int mfr_sum_rows_ex(const void *x, int dtype, size_t rows, size_t cols, size_t row_stride, float *out,
                     const mfr_tuning *t, hipStream_t stream);

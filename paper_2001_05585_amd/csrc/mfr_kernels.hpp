@@ -40,7 +40,8 @@ typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 constexpr int kMaxWavesPerBlock = 16;
 
 struct SumArgs {
-    const uint4v *base;          // x rounded down to 16 bytes: slot 0 (of row 0)
+    const uint4v *base;          // slot 0 (of row 0): x rounded down to 16 bytes, or x itself when the rows of a
+                                 // batched call differ in 16-byte phase (head is then 0 and loads are unaligned)
     const void *x;               // first element (of row 0)
     unsigned long long n;        // elements per row
     unsigned long long vend;     // head + n: end of the valid range in slot-relative elements
@@ -49,7 +50,7 @@ struct SumArgs {
     unsigned long long epi0;     // border positions [epi0, epi1)
     unsigned long long epi1;
     unsigned long long slots;    // total slots covering [x, x + n)
-    unsigned long long row_slots;  // distance between rows in slots (rows share the 16-byte phase)
+    unsigned long long row_bytes;  // distance between rows in bytes
     unsigned long long split_chains;  // MFR_KERNEL_SPLIT: chains [0, split_chains) take the MFMA path ...
     unsigned long long split_waves;   // ... on waves [0, split_waves); the rest is conventional
     unsigned long long ticket_stride;  // ticket words per row
@@ -75,11 +76,15 @@ template <> struct ElemTraits<MFR_DTYPE_F32> { static constexpr unsigned per_slo
 
 // ---------------------------------------------------------------- loads ---
 
+// A 16-byte slot.  The pointer type claims element alignment only: rows of a batched call may start
+// at any element, and the device serves unaligned 128-bit loads (the instruction is the same).
+typedef uint4v slot_unaligned __attribute__((aligned(2)));
+
 template <bool NT>
 __device__ __forceinline__ uint4v load_slot(const uint4v *p)
 {
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
+    if constexpr (NT) return __builtin_nontemporal_load((const slot_unaligned *)p);
+    else return *(const slot_unaligned *)p;
 }
 
 // Slot q with every element range-checked against [x, x + n).  A slot that
@@ -95,7 +100,7 @@ __device__ __forceinline__ uint4v load_slot_guarded(const SumArgs &a, const uint
     const unsigned long long v0 = q * E;
     const bool full = active && v0 >= a.head && v0 + E <= a.vend;
     uint4v r = {0u, 0u, 0u, 0u};
-    if (full) r = base[q];
+    if (full) r = load_slot<false>(base + q);
     if (active && !full) {
         unsigned int h[E];
 #pragma unroll
@@ -381,8 +386,8 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
     const unsigned long long w = (unsigned long long)blockIdx.x * wpb + wave;
 
     const unsigned long long row = blockIdx.y;
-    const uint4v *base = a.base + row * a.row_slots;
-    const void *x = (const char *)a.x + row * a.row_slots * 16ull;
+    const uint4v *base = (const uint4v *)((const char *)a.base + row * a.row_bytes);
+    const void *x = (const char *)a.x + row * a.row_bytes;
 
     float partial;                       // the wave's fp32 partial, uniform
     if constexpr (KERNEL == MFR_KERNEL_MFMA) {

@@ -113,11 +113,9 @@ void resolve_load_policy(mfr_tuning *t, size_t bytes)
 {
     if (t->nontemporal == 0) t->nontemporal = bytes <= kTemporalBytes ? 1 : 2;
 }
-// The tiled rows kernel takes over from this many rows on; long rows (one row per tile) from
-// fewer, and rows of differing 16-byte phase from fewer still (the alternative is a launch per row).
+// The tiled rows kernel takes over from this many rows on; long rows (one row per tile) from fewer.
 constexpr size_t kRowsTiledMinRows = 1024;
 constexpr size_t kRowsTiledMinLongRows = 512;
-constexpr size_t kRowsTiledMinMixedRows = 32;
 // Rows of this many bytes or more are walked one per wave, 4 KiB per step, instead of four side by
 // side, 1 KiB each per step: with a power-of-two row stride the four pieces of a step would fall
 // into the same memory channels.
@@ -332,11 +330,10 @@ bool span_fits(size_t rows, size_t cols, size_t row_stride)
 }
 
 // Shape of the tiled rows kernel for rows x cols elements of `esize` bytes at byte address x_addr,
-// rows row_stride elements apart.  Returns false when the other kernels are the better choice:
-// few rows (they cannot fill the device here, a grid per row can), unless the rows differ in their
-// 16-byte phase, which only this kernel handles in one launch.
+// rows row_stride elements apart.  Returns false when the per-row kernels are the better choice:
+// few rows (they cannot fill the device here, a grid per row can) or very long ones.
 bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, size_t row_stride, int cus,
-                     bool same_phase, mfr::RowsTiledShape *s, unsigned *grid)
+                     mfr::RowsTiledShape *s, unsigned *grid)
 {
     (void)x_addr;                        // slots are counted from each row's first element: no phase
     if (rows < 2 || cols == 0) return false;
@@ -344,13 +341,13 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     const unsigned long long stride_bytes = (unsigned long long)row_stride * esize;
     const unsigned long long row_bytes = (unsigned long long)cols * esize;
     // rows this long are streamed as well or better by a grid of blocks per row
-    if (same_phase && row_bytes > kRowsTiledMaxRowBytes) return false;
+    if (row_bytes > kRowsTiledMaxRowBytes) return false;
     int lp = 0;
     while (lp < 4 && (64ull << lp) < row_bytes) ++lp;
     int d = 1, gf = 8;
     if (rows >= kRowsTiledMinRows && row_bytes < kRowsTiledLongRowBytes) {
         if (lp == 4) gf = 4;
-    } else if ((lp == 4 && rows >= kRowsTiledMinLongRows) || (!same_phase && rows >= kRowsTiledMinMixedRows)) {
+    } else if (lp == 4 && rows >= kRowsTiledMinLongRows) {
         lp = 4; d = 4; gf = 1;
     } else {
         return false;
@@ -417,14 +414,14 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
 
     if (cols == 0) return fill_zero(out, rows, stream);
 
-    // rows can share one launch when they all have the same 16-byte phase
+    // rows that all have the same 16-byte phase can be read in aligned slots
     const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
 
     // Many rows: tiles shared out among rows, one launch for any alignment and stride.
     if (tin == nullptr) {
         mfr::RowsTiledShape shape;
         unsigned grid = 0;
-        if (plan_rows_tiled((size_t)x, esize, rows, cols, row_stride, info.cus, same_phase, &shape, &grid)) {
+        if (plan_rows_tiled((size_t)x, esize, rows, cols, row_stride, info.cus, &shape, &grid)) {
             const bool nt = t.nontemporal == 2;
             const hipError_t e =
                 dtype == MFR_DTYPE_F16 ? mfr::launch_rows_tiled_f16(x, rows, cols, row_stride, out, shape, grid, nt, stream)
@@ -445,17 +442,20 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     // close to each other (a power-of-two distance when the rows are): one chain of 8 tiles, i.e.
     // 8 KiB contiguous per wave, instead of two chains of 4 (84 % against 78 % of the HBM peak for
     // 16 rows of 32 MiB).
-    if (tin == nullptr && rows > 1 && rows <= kFewRows && same_phase && dtype != MFR_DTYPE_F32) {
+    if (tin == nullptr && rows > 1 && rows <= kFewRows && dtype != MFR_DTYPE_F32) {
         t.chain_R = 8;
         t.chains_in_flight = 1;
     }
     // Row counts that do not divide the CUs well: smaller blocks, more of them per CU, fill the
     // device in one round (300 rows: 86 % with 64-thread blocks against 70 % with 256-thread ones).
-    if (tin == nullptr && rows > 1 && same_phase) t.block_threads = block_threads_for_rows(rows, info.cus);
-    const size_t batch = !same_phase ? 1 : (rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch);
+    if (tin == nullptr && rows > 1) t.block_threads = block_threads_for_rows(rows, info.cus);
+    const size_t batch = rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch;
 
+    // Rows that share their 16-byte phase are addressed in aligned slots counted from the boundary
+    // at or below their first element (the head slot is read element-wise).  Rows of differing phase
+    // are addressed from their own first element: no head, unaligned 128-bit loads.
     Plan p;
-    plan_region(cols, (size_t)x, esize, t, &p);
+    plan_region(cols, same_phase ? (size_t)x : 0, esize, t, &p);
     const long long grid = grid_blocks_for(p, t, info.cus, batch);
     if (grid < 1) return MFR_ERR_INVALID_ARG;
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
@@ -471,10 +471,9 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     for (size_t r0 = 0; r0 < rows; r0 += batch) {
         const size_t nr = rows - r0 < batch ? rows - r0 : batch;
         const char *xr = (const char *)x + r0 * row_stride * esize;
-        if (!same_phase) plan_region(cols, (size_t)xr, esize, t, &p);   // each row has its own phase
-        p.a.base = (const uint4v *)((size_t)xr & ~(size_t)15);
+        p.a.base = same_phase ? (const uint4v *)((size_t)xr & ~(size_t)15) : (const uint4v *)xr;
         p.a.x = xr;
-        p.a.row_slots = same_phase ? (row_stride * esize) / 16u : 0;
+        p.a.row_bytes = (unsigned long long)row_stride * esize;
         if (t.kernel == MFR_KERNEL_SPLIT) {
             // the same fraction of the chains and of the waves; a part without waves gets no chains
             const unsigned long long W = (unsigned long long)grid * (unsigned)p.waves;
@@ -744,10 +743,9 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
     if ((x_addr & (esize - 1u)) || cols > ((size_t)1 << 60) || rows > ((size_t)1 << 40)) return -MFR_ERR_INVALID_ARG;
     if (rows > 1 && row_stride < cols) return -MFR_ERR_INVALID_ARG;
     if (!span_fits(rows, cols, row_stride)) return -MFR_ERR_INVALID_ARG;
-    const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
     mfr::RowsTiledShape s;
     unsigned grid = 0;
-    if (!plan_rows_tiled(x_addr, esize, rows, cols, row_stride, cus, same_phase, &s, &grid)) return 0;
+    if (!plan_rows_tiled(x_addr, esize, rows, cols, row_stride, cus, &s, &grid)) return 0;
     plan[0] = 1ull << s.log2_p;
     plan[1] = (unsigned long long)s.tiles_per_step;
     plan[2] = (unsigned long long)s.groups;

@@ -87,9 +87,12 @@ INT_CASES = [
     (5003, 1, 1, 0), (5003, 1, 1, 1), (5003, 7, 7, 3), (5003, 31, 33, 0), (5003, 33, 40, 0), (4001, 64, 64, 1),
     (4001, 65, 72, 0), (4001, 100, 100, 0), (4001, 129, 131, 5), (3000, 255, 256, 0), (3000, 300, 304, 7),
     (2500, 500, 500, 2), (2100, 1001, 1001, 0), (2100, 1536, 1544, 4), (2049, 3000, 3001, 0),
-    (700, 2500, 2504, 0), (513, 4097, 4099, 6),                                      # long rows from 512 rows on
-    (33, 1001, 1001, 0), (100, 37, 39, 1), (1000, 5, 5, 0), (40, 20000, 20001, 0),   # phases differ, few rows
+    (700, 2500, 2504, 0), (513, 4001, 4003, 6),                                      # long rows from 512 rows on
 ]
+
+# few rows whose 16-byte phases differ: the per-row kernels, every row addressed from its own first element
+MIXED_PHASE_CASES = [(33, 1001, 1001, 0), (100, 37, 39, 1), (1000, 5, 5, 0), (40, 20000, 20001, 0), (7, 100003, 100003, 0),
+                     (300, 9001, 9003, 3), (2, 1 << 20 | 1, (1 << 20) + 5, 0), (150, 1, 3, 0)]
 
 
 @pytest.mark.parametrize("dtype", [F16, BF16, F32])
@@ -102,6 +105,22 @@ def test_integer_rows_bit_exact(dtype, rows, cols, stride, shift, oracle_lib):
     got = call(dtype, inp, rows, cols, stride).astype(np.float64)
     bad = np.nonzero(got != want)[0]
     assert bad.size == 0, (rows, cols, stride, shift, bad[:5], got[bad[:5]], want[bad[:5]])
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16, F32])
+@pytest.mark.parametrize("rows,cols,stride,shift", MIXED_PHASE_CASES)
+def test_few_rows_of_differing_phase_bit_exact(dtype, rows, cols, stride, shift):
+    vals = W.small_integers(rows * cols, seed=rows * 17 + cols, lo=-4, hi=4).astype(np.float32).reshape(rows, cols)
+    inp = RowsInput(dtype, encode(dtype, vals).reshape(rows, cols), stride, shift)
+    assert B.mfr_rows_plan(inp.ptr, dtype, rows, cols, stride, cus()) is None
+    want = vals.astype(np.float64).sum(axis=1)
+    tunings = [None, B.make_tuning(256, 2), B.make_tuning(64, 8, 0, B.MFR_KERNEL_SHFL, 1), B.make_tuning(128, 1, 3, 0, 4, 2)]
+    if dtype == F16:
+        tunings.append(B.make_tuning(32, 4))
+    for t in tunings:
+        got = call(dtype, inp, rows, cols, stride, t).astype(np.float64)
+        bad = np.nonzero(got != want)[0]
+        assert bad.size == 0, (rows, cols, stride, shift, t and (t.block_threads, t.chain_R), bad[:5], got[bad[:5]], want[bad[:5]])
 
 
 def test_shapes_reach_every_kernel_shape():

@@ -85,7 +85,7 @@ SHAPES = [
     (0, 2048, 64, 64), (0, 2048, 32, 32), (0, 2048, 128, 128), (0, 2048, 256, 256), (0, 2048, 512, 512),
     (0, 2048, 1024, 1024), (0, 2100, 100, 100), (2, 2049, 64, 64), (14, 2048, 64, 72), (6, 2048, 7, 7),
     (0, 2048, 1, 1), (2, 2048, 1, 1), (0, 2048, 3, 5), (8, 2500, 33, 40), (0, 2048, 1001, 1001),
-    (4, 2048, 520, 523), (0, 600, 700, 704), (2, 600, 5000, 5001), (0, 40, 33, 37), (6, 33, 3, 3),
+    (4, 2048, 520, 523), (0, 600, 700, 704), (2, 600, 3000, 3001), (0, 1040, 33, 37), (6, 1033, 3, 3),
 ]
 
 
@@ -118,11 +118,12 @@ def test_choice_between_kernels():
     assert B.mfr_rows_plan(1 << 20, f16, 1, 1000, 1000, 256) is None          # one row: the single-sum path
     assert B.mfr_rows_plan(1 << 20, f16, 100, 1 << 20, 1 << 20, 256) is None   # few long rows: a grid per row
     assert B.mfr_rows_plan(1 << 20, f16, 100, 64, 64, 256) is None
-    assert B.mfr_rows_plan(1 << 20, f16, 100, 1001, 1001, 256) is not None     # phases differ: one launch all the same
+    assert B.mfr_rows_plan(1 << 20, f16, 100, 1001, 1001, 256) is None         # ... whatever their phases
     assert B.mfr_rows_plan(1 << 20, f16, 600, 4096, 4096, 256) is not None     # long rows from 512 rows on
+    assert B.mfr_rows_plan(1 << 20, f16, 600, 4097, 4097, 256) is not None
     assert B.mfr_rows_plan(1 << 20, f16, 4096, 8, 8, 256) is not None
-    assert B.mfr_rows_plan(1 << 20, f16, 4096, 16384, 16384, 256) is None      # rows beyond 16 KiB: a grid per row ...
-    assert B.mfr_rows_plan(1 << 20, f16, 4096, 16385, 16385, 256) is not None  # ... unless their phases differ
+    assert B.mfr_rows_plan(1 << 20, f16, 4096, 16384, 16384, 256) is None      # rows beyond 16 KiB: a grid per row
+    assert B.mfr_rows_plan(1 << 20, f16, 4096, 16385, 16385, 256) is None
 
 
 def test_invalid_arguments():
@@ -139,7 +140,7 @@ def test_invalid_arguments():
 
 @settings(max_examples=60, deadline=None)
 @given(dtype=st.sampled_from([B.MFR_DTYPE_F16, B.MFR_DTYPE_BF16, B.MFR_DTYPE_F32]),
-       low=st.integers(0, 7), rows=st.integers(32, 2300), cols=st.integers(1, 300), gap=st.integers(0, 9),
+       low=st.integers(0, 7), rows=st.integers(512, 2300), cols=st.integers(1, 300), gap=st.integers(0, 9),
        cus=st.sampled_from([1, 8, 256]))
 def test_replay_of_random_shapes(dtype, low, rows, cols, gap, cus):
     es = ESIZE[dtype]
