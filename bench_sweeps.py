@@ -237,7 +237,7 @@ def types(args, torch, np, B, W):
     """512 MiB of each element type through both kernels (default tuning), rotating 4 buffers."""
     timer = Timer(torch, B)
     with open_out(args, "types.txt") as f:
-        emit(f, "# 512 MiB per call, normal(0,1), 4 rotating buffers, default tuning; GB/s = bytes / time")
+        emit(f, "# 512 MiB per call, normal(0,1), 4 rotating buffers, default tuning, 0.5 s of calls before the timed ones; GB/s = bytes / time")
         emit(f, "# dtype n kernel us Gelem/s GB/s pct_of_8TB/s")
         for dtype, name, esize in ((B.MFR_DTYPE_F16, "f16", 2), (B.MFR_DTYPE_BF16, "bf16", 2), (B.MFR_DTYPE_F32, "f32", 4)):
             n = (1 << 29) // esize
@@ -253,8 +253,12 @@ def types(args, torch, np, B, W):
 
                 def call(i):
                     B.mfr_sum_ex(bufs[i % 4].data_ptr(), dtype, n, timer.out.data_ptr(), t, timer.stream)
-                for i in range(20):
-                    call(i)
+                # freshly allocated buffers run slow at first: half a second of calls before the timed ones
+                t0 = time.perf_counter()
+                while time.perf_counter() - t0 < 0.5:
+                    for i in range(50):
+                        call(i)
+                    torch.cuda.synchronize()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 for i in range(args.steps):
