@@ -99,7 +99,8 @@ def tune(args, torch, np, B, W):
         combos = []
         for kernel in (0, 1):
             for block in (64, 128, 256, 512, 1024):
-                for R, U in ((1, 1), (1, 2), (1, 4), (1, 8), (2, 1), (2, 2), (2, 4), (2, 8), (4, 1), (4, 2), (4, 4), (8, 1), (8, 2)):
+                for R, U in ((1, 1), (1, 2), (1, 4), (1, 8), (2, 1), (2, 2), (2, 4), (2, 8), (3, 1), (3, 2), (3, 4), (4, 1), (4, 2), (4, 4),
+                             (5, 1), (5, 2), (6, 1), (6, 2), (7, 1), (7, 2), (8, 1), (8, 2)):
                     waves = block // 64
                     if R * U * 1 < 2:
                         continue

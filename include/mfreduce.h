@@ -78,12 +78,15 @@ typedef struct mfr_tuning {
                              32 lanes contribute zeros (gfx950 has no 32-wide wavefront) */
     int chain_R;          /* 1..8.  MFMA kernel: MFMAs accumulated into one accumulator tile
                              from zero before it is folded to an fp32 partial (the paper's R).
-                             SHFL kernel: 16-byte loads per lane accumulated per group */
+                             SHFL kernel: 16-byte loads per lane accumulated per group.
+                             Default: 3 (MFMA, SPLIT), 6 (SHFL), 8 for binary32 input */
     int grid_blocks;      /* MFR_GRID_AUTO, MFR_GRID_ONE_CHAIN, or an explicit count >= 1 */
     int kernel;           /* MFR_KERNEL_MFMA, MFR_KERNEL_SHFL or MFR_KERNEL_SPLIT */
     int chains_in_flight; /* 1, 2, 4 or 8 independent chains whose loads are issued before
                              any is consumed (memory-level parallelism); chain_R *
-                             chains_in_flight must not exceed 16 */
+                             chains_in_flight must not exceed 16.  Default: the largest of these with
+                             chain_R * chains_in_flight <= 8 (two chains of three tiles, 6 KiB of loads
+                             per wave, by default) */
     int nontemporal;      /* 0 = library default (plain loads for inputs up to 32 MiB, which may be
                              resident in the L2s; non-temporal loads beyond), 1 = plain, 2 = non-temporal */
     int combine;          /* MFR_COMBINE_* */

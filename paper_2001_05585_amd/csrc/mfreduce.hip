@@ -67,7 +67,10 @@ DeviceInfo g_devices[64];
 std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
 
 constexpr int kDefaultBlock = 256;
-constexpr int kDefaultR = 4;
+// Six KiB of loads in flight per wave (two chains of three tiles), one wave per SIMD, is where the
+// chip streams fastest: 75.7 us for 512 MiB against 77.2 us with eight KiB and 89 us with four.
+constexpr int kDefaultR = 3;
+constexpr int kDefaultR_shfl = 6;              // the conventional kernel: one group of six loads
 constexpr int kDefaultR_f32 = 8;               // four MFMAs per tile: one long chain overlaps them with the loads
 constexpr int kDefaultWavesPerCU = 4;          // one wave per SIMD
 constexpr long long kTicketMaxBlocks = 2048;   // AUTO: larger grids combine with a second launch
@@ -121,7 +124,6 @@ constexpr size_t kRowsTiledMinLongRows = 512;
 // into the same memory channels.
 constexpr size_t kRowsTiledLongRowBytes = 4096;
 constexpr size_t kRowsTiledMaxRowBytes = 16384;
-constexpr size_t kFewRows = 64;                // up to this many rows share the grid with several blocks each
 
 int default_in_flight(int R)
 {
@@ -155,7 +157,9 @@ int resolve_tuning(const mfr_tuning *in, int dtype, mfr_tuning *t)
         const DefaultGeometry &g = default_geometry();
         if (!g.valid) return MFR_ERR_INVALID_ARG;
         if (z.block_threads == 0) z.block_threads = g.block;
-        if (z.chain_R == 0) z.chain_R = g.chain_R ? g.chain_R : (dtype == MFR_DTYPE_F32 ? kDefaultR_f32 : kDefaultR);
+        if (z.chain_R == 0)
+            z.chain_R = g.chain_R ? g.chain_R
+                        : (dtype == MFR_DTYPE_F32 ? kDefaultR_f32 : (z.kernel == MFR_KERNEL_SHFL ? kDefaultR_shfl : kDefaultR));
     }
     if (!valid_block(z.block_threads)) return MFR_ERR_INVALID_ARG;
     if (z.block_threads == 32 && dtype != MFR_DTYPE_F16) return MFR_ERR_INVALID_ARG;
@@ -438,14 +442,6 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
         }
     }
 
-    // Rows that share the grid have few waves each, so the chains a wave has in flight together lie
-    // close to each other (a power-of-two distance when the rows are): one chain of 8 tiles, i.e.
-    // 8 KiB contiguous per wave, instead of two chains of 4 (84 % against 78 % of the HBM peak for
-    // 16 rows of 32 MiB).
-    if (tin == nullptr && rows > 1 && rows <= kFewRows && dtype != MFR_DTYPE_F32) {
-        t.chain_R = 8;
-        t.chains_in_flight = 1;
-    }
     // Row counts that do not divide the CUs well: smaller blocks, more of them per CU, fill the
     // device in one round (300 rows: 86 % with 64-thread blocks against 70 % with 256-thread ones).
     if (tin == nullptr && rows > 1) t.block_threads = block_threads_for_rows(rows, info.cus);

@@ -175,13 +175,13 @@ def test_environment_override_of_the_default_geometry():
             "print(B.mfr_plan_for(1 << 20, 4096, None))\n")
     base = _in_fresh_process({"MFR_BLOCK": "", "MFR_R": ""}, "import os\nos.environ.pop('MFR_BLOCK'); os.environ.pop('MFR_R')\n" + code)
     assert base.returncode == 0, base.stderr
-    assert base.stdout.splitlines()[0] == "(256, 4, 0)"
+    assert base.stdout.splitlines()[0] == "(256, 3, 0)"
     r = _in_fresh_process({"MFR_BLOCK": "512", "MFR_R": "2"}, code)
     assert r.returncode == 0, r.stderr
     lines = r.stdout.splitlines()
     assert lines[0] == "(512, 2, 0)"
-    # 2^20 halves = 2048 tiles of 64 slots: chains of R = 2 tiles instead of 4
-    assert eval(lines[1])[3] == 1024 and eval(base.stdout.splitlines()[1])[3] == 512
+    # 2^20 halves = 2048 tiles of 64 slots: chains of R = 2 tiles instead of 3
+    assert eval(lines[1])[3] == 1024 and eval(base.stdout.splitlines()[1])[3] == 682
     # explicit tuning is not affected
     r = _in_fresh_process({"MFR_BLOCK": "512", "MFR_R": "2"},
                           "from paper_2001_05585_amd import binding as B\n"
