@@ -99,8 +99,8 @@ def tune(args, torch, np, B, W):
         combos = []
         for kernel in (0, 1):
             for block in (64, 128, 256, 512, 1024):
-                for R, U in ((1, 1), (1, 2), (1, 4), (1, 8), (2, 1), (2, 2), (2, 4), (2, 8), (3, 1), (3, 2), (3, 4), (4, 1), (4, 2), (4, 4),
-                             (5, 1), (5, 2), (6, 1), (6, 2), (7, 1), (7, 2), (8, 1), (8, 2)):
+                for R, U in ((1, 1), (1, 2), (1, 3), (1, 4), (1, 6), (1, 8), (2, 1), (2, 2), (2, 3), (2, 4), (2, 6), (2, 8),
+                             (3, 1), (3, 2), (3, 3), (3, 4), (4, 1), (4, 2), (4, 3), (4, 4), (5, 1), (5, 2), (6, 1), (6, 2), (7, 1), (7, 2), (8, 1), (8, 2)):
                     waves = block // 64
                     if R * U * 1 < 2:
                         continue
@@ -361,8 +361,8 @@ def wide(args, torch, np, B, W):
     with open_out(args, "wide.txt") as f:
         emit(f, "# n=2^28 uniform[0,1), 4 rotating buffers; mode R U us Gelem/s GB/s pct_of_8TB/s result")
         dt = timer.run(bufs, n, None, args.steps, 10)
-        emit(f, "fp32_partials 4 2 %.2f %.1f %.1f %.1f %r" % (dt * 1e6, n / dt / 1e9, 2 * n / dt / 1e9, 100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS, timer.result()))
-        for R, U in ((1, 8), (2, 4), (4, 2), (8, 1)):
+        emit(f, "fp32_partials 3 2 %.2f %.1f %.1f %.1f %r" % (dt * 1e6, n / dt / 1e9, 2 * n / dt / 1e9, 100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS, timer.result()))
+        for R, U in ((1, 6), (1, 8), (2, 3), (2, 4), (3, 2), (4, 2), (6, 1), (8, 1)):
             t = B.make_tuning(256, R, 0, 0, U)
 
             def call(i):

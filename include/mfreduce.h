@@ -82,11 +82,12 @@ typedef struct mfr_tuning {
                              Default: 3 (MFMA, SPLIT), 6 (SHFL), 8 for binary32 input */
     int grid_blocks;      /* MFR_GRID_AUTO, MFR_GRID_ONE_CHAIN, or an explicit count >= 1 */
     int kernel;           /* MFR_KERNEL_MFMA, MFR_KERNEL_SHFL or MFR_KERNEL_SPLIT */
-    int chains_in_flight; /* 1, 2, 4 or 8 independent chains whose loads are issued before
+    int chains_in_flight; /* 1, 2, 3, 4, 6 or 8 independent chains whose loads are issued before
                              any is consumed (memory-level parallelism); chain_R *
-                             chains_in_flight must not exceed 16.  Default: the largest of these with
-                             chain_R * chains_in_flight <= 8 (two chains of three tiles, 6 KiB of loads
-                             per wave, by default) */
+                             chains_in_flight must not exceed 16.  Default: the count that brings
+                             chain_R * chains_in_flight closest to 6 tiles (6 KiB of loads per wave, the
+                             measured optimum), the larger count on a tie: 6, 3, 2, 2, 1, 1, 1, 1 for
+                             chain_R = 1..8 */
     int nontemporal;      /* 0 = library default (plain loads for inputs up to 32 MiB, which may be
                              resident in the L2s; non-temporal loads beyond), 1 = plain, 2 = non-temporal */
     int combine;          /* MFR_COMBINE_* */
@@ -183,7 +184,7 @@ int mfr_sum_f16_rows(const mfr_half *x, size_t rows, size_t cols, size_t row_str
  * up to 2^53.  (Sections 2.2 and 5.4 discuss the precision of fp32 partials.)
  *   out   device pointer to one double, 8-byte aligned.
  *   t     as for mfr_sum_f16_ex; kernel must be MFR_KERNEL_MFMA, block_threads
- *         >= 64, chain_R in {1, 2, 4, 8} (default 1).
+ *         >= 64, chain_R 1..8 (default 1, with six chains in flight).
  */
 int mfr_sum_f16_f64(const mfr_half *x, size_t n, double *out, hipStream_t stream);
 int mfr_sum_f16_f64_ex(const mfr_half *x, size_t n, double *out, const mfr_tuning *t, hipStream_t stream);

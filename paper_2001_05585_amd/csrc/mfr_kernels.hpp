@@ -493,11 +493,11 @@ hipError_t launch_k(const Plan &p, dim3 grid, const mfr_tuning &t, hipStream_t s
 #define MFR_CASE(R_, U_) \
     case (R_) * 16 + (U_): return launch_ru<KERNEL, DT, R_, U_>(p, grid, nt, stream);
     switch (t.chain_R * 16 + t.chains_in_flight) {
-        MFR_CASE(1, 1) MFR_CASE(1, 2) MFR_CASE(1, 4) MFR_CASE(1, 8)
-        MFR_CASE(2, 1) MFR_CASE(2, 2) MFR_CASE(2, 4) MFR_CASE(2, 8)
-        MFR_CASE(3, 1) MFR_CASE(3, 2) MFR_CASE(3, 4)
-        MFR_CASE(4, 1) MFR_CASE(4, 2) MFR_CASE(4, 4)
-        MFR_CASE(5, 1) MFR_CASE(5, 2)
+        MFR_CASE(1, 1) MFR_CASE(1, 2) MFR_CASE(1, 3) MFR_CASE(1, 4) MFR_CASE(1, 6) MFR_CASE(1, 8)
+        MFR_CASE(2, 1) MFR_CASE(2, 2) MFR_CASE(2, 3) MFR_CASE(2, 4) MFR_CASE(2, 6) MFR_CASE(2, 8)
+        MFR_CASE(3, 1) MFR_CASE(3, 2) MFR_CASE(3, 3) MFR_CASE(3, 4)
+        MFR_CASE(4, 1) MFR_CASE(4, 2) MFR_CASE(4, 3) MFR_CASE(4, 4)
+        MFR_CASE(5, 1) MFR_CASE(5, 2) MFR_CASE(5, 3)
         MFR_CASE(6, 1) MFR_CASE(6, 2)
         MFR_CASE(7, 1) MFR_CASE(7, 2)
         MFR_CASE(8, 1) MFR_CASE(8, 2)

@@ -125,13 +125,12 @@ constexpr size_t kRowsTiledMinLongRows = 512;
 constexpr size_t kRowsTiledLongRowBytes = 4096;
 constexpr size_t kRowsTiledMaxRowBytes = 16384;
 
+// Chains in flight that bring R * U closest to 6 tiles (6 KiB of loads per wave,
+// the measured optimum), the larger count on a tie.
 int default_in_flight(int R)
 {
-    int u = 8 / R;
-    if (u >= 8) return 8;
-    if (u >= 4) return 4;
-    if (u >= 2) return 2;
-    return 1;
+    static const int kByR[9] = {0, 6, 3, 2, 2, 1, 1, 1, 1};
+    return kByR[R < 1 ? 1 : (R > 8 ? 8 : R)];
 }
 
 bool valid_block(int b)
@@ -172,7 +171,7 @@ int resolve_tuning(const mfr_tuning *in, int dtype, mfr_tuning *t)
     if (z.kernel != MFR_KERNEL_SPLIT && z.split_permille != 0) return MFR_ERR_INVALID_ARG;
     if (z.chains_in_flight == 0) z.chains_in_flight = default_in_flight(z.chain_R);
     const int u = z.chains_in_flight;
-    if (!(u == 1 || u == 2 || u == 4 || u == 8)) return MFR_ERR_INVALID_ARG;
+    if (!(u == 1 || u == 2 || u == 3 || u == 4 || u == 6 || u == 8)) return MFR_ERR_INVALID_ARG;
     if (u * z.chain_R > 16) return MFR_ERR_INVALID_ARG;
     if (z.nontemporal < 0 || z.nontemporal > 2) return MFR_ERR_INVALID_ARG;   // 0 is resolved per call size
     if (z.combine < 0 || z.combine > 2) return MFR_ERR_INVALID_ARG;
@@ -566,7 +565,6 @@ int sum_wide_impl(const mfr_half *x, size_t n, double *out, const mfr_tuning *ti
     if (st != MFR_OK) return st;
     resolve_load_policy(&t, n * 2);
     if (t.kernel != MFR_KERNEL_MFMA || t.block_threads == 32) return MFR_ERR_INVALID_ARG;
-    if (!(t.chain_R == 1 || t.chain_R == 2 || t.chain_R == 4 || t.chain_R == 8)) return MFR_ERR_INVALID_ARG;
     if (!out || ((size_t)out & 7u) != 0) return MFR_ERR_INVALID_ARG;
     if (n > 0 && !x) return MFR_ERR_INVALID_ARG;
     if (((size_t)x & 1u) != 0 || n > ((size_t)1 << 60)) return MFR_ERR_INVALID_ARG;

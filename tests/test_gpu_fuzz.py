@@ -23,7 +23,7 @@ def random_tuning(rng, dtype):
     kernel = int(rng.choice([0, 1, 2] if dtype == B.MFR_DTYPE_F16 else [0, 1]))
     blocks = [64, 128, 256, 512, 1024] + ([32] if dtype == B.MFR_DTYPE_F16 and kernel != 2 else [])
     R = int(rng.integers(1, 9))
-    us = [u for u in (1, 2, 4, 8) if u * R <= 16]
+    us = [u for u in (1, 2, 3, 4, 6, 8) if u * R <= 16]
     grid = int(rng.choice([0, -1, 1, 2, 3, 17, 100, 513, 3000]))
     return B.make_tuning(int(rng.choice(blocks)), R, grid, kernel, int(rng.choice(us)), int(rng.integers(0, 3)),
                          int(rng.integers(0, 3)), int(rng.integers(0, 1001)) if kernel == 2 else 0)

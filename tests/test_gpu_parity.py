@@ -190,7 +190,7 @@ def test_in_flight_and_nontemporal_variants_agree():
     tunings = []
     for kernel in KERNELS:
         for R in range(1, 9):
-            for U in (1, 2, 4, 8):
+            for U in (1, 2, 3, 4, 6, 8):
                 if R * U <= 16:
                     for nt in (1, 2):
                         tunings.append(B.make_tuning(256, R, 0, kernel, U, nt))

@@ -35,7 +35,7 @@ class Out64:
 
 def wide_tunings():
     out = [None]
-    for R, U in ((1, 1), (1, 8), (2, 4), (4, 2), (8, 1), (8, 2)):
+    for R, U in ((1, 1), (1, 6), (1, 8), (2, 3), (2, 4), (3, 2), (4, 2), (5, 3), (7, 1), (8, 2)):
         for block, grid, combine in ((256, 0, 0), (64, 3, 1), (1024, 0, 2), (128, -1, 0), (512, 700, 0)):
             out.append(B.make_tuning(block, R, grid, 0, U, 0, combine))
     return out
@@ -127,7 +127,7 @@ def test_wide_argument_checks_and_zero():
     assert L.mfr_sum_f16_f64(None, 64, o.ptr(0), None) == INV
     assert L.mfr_sum_f16_f64(d.ptr, 64, None, None) == INV
     import ctypes
-    for kw in (dict(kernel=1), dict(block_threads=32), dict(chain_R=3), dict(kernel=2, split_permille=10)):
+    for kw in (dict(kernel=1), dict(block_threads=32), dict(chain_R=9), dict(chain_R=3, chains_in_flight=6), dict(kernel=2, split_permille=10)):
         t = B.make_tuning(**kw)
         assert L.mfr_sum_f16_f64_ex(d.ptr, 64, o.ptr(0), ctypes.byref(t), None) == INV
     B.mfr_sum_f16_f64(d.ptr, 0, o.ptr(0), stream_handle())

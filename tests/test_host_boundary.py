@@ -67,7 +67,7 @@ def test_invalid_arguments_are_rejected_before_any_hip_call():
         assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, R, 0, 0, None) == INV
     assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, 1, -2, 0, None) == INV
     assert L.mfr_sum_f16_tuned(4096, 5, 4096, 256, 1, 0, 3, None) == INV
-    for kw in (dict(chains_in_flight=3), dict(chains_in_flight=16), dict(chain_R=8, chains_in_flight=4),
+    for kw in (dict(chains_in_flight=5), dict(chains_in_flight=7), dict(chains_in_flight=16), dict(chain_R=3, chains_in_flight=6), dict(chain_R=8, chains_in_flight=4),
                dict(nontemporal=3), dict(kernel=-1), dict(block_threads=100), dict(combine=3), dict(combine=-1),
                dict(kernel=2, split_permille=1001), dict(kernel=2, split_permille=-1), dict(kernel=0, split_permille=500),
                dict(kernel=2, block_threads=32)):
