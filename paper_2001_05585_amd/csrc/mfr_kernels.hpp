@@ -40,8 +40,7 @@ typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 constexpr int kMaxWavesPerBlock = 16;
 
 struct SumArgs {
-    const uint4v *base;          // slot 0 (of row 0): x rounded down to 16 bytes, or x itself when the rows of a
-                                 // batched call differ in 16-byte phase (head is then 0 and loads are unaligned)
+    const uint4v *base;          // slot 0 (of row 0): x rounded down to 16 bytes
     const void *x;               // first element (of row 0)
     unsigned long long n;        // elements per row
     unsigned long long vend;     // head + n: end of the valid range in slot-relative elements
@@ -56,10 +55,38 @@ struct SumArgs {
     unsigned long long ticket_stride;  // ticket words per row
     unsigned int ticket_flat;    // nonzero: one ticket counter per row, else two levels
     unsigned int head;           // elements of slot 0 that lie before x
+    unsigned int per_row_phase;  // nonzero: the rows of a batched call differ in 16-byte phase; each block then
+                                 // derives base, head, vend, main0, chains, epi0, epi1 and slots of its row
+                                 // itself (the values above are those of a row that starts on a boundary)
     float *partials;             // gridDim.x per row
     unsigned int *ticket;        // one per row; nullptr = two-launch combine
     float *out;                  // one per row
 };
+
+// Slot arithmetic of one array of n elements whose first element lies `head` elements past a
+// 16-byte boundary: slot 0 is the (partial) head slot, full slots [main0, main0 + chains *
+// chain_slots) form the chains, the border positions [epi0, epi1) take the rest (position `slots`
+// stands for the head slot).  Used by the host for a single array and for rows of equal phase,
+// and by each block of the kernel for its own row when the phases differ.
+__host__ __device__ inline void region_fields(unsigned long long n, unsigned int head, unsigned int per_slot,
+                                              unsigned int chain_slots, SumArgs *a)
+{
+    const unsigned long long vend = (unsigned long long)head + n;
+    const unsigned long long slots = (vend + per_slot - 1ull) / per_slot;
+    const unsigned long long s0 = head ? 1ull : 0ull;
+    const unsigned long long s1 = vend / per_slot;             // slots that end at or before vend
+    const unsigned long long full = s1 > s0 ? s1 - s0 : 0ull;
+    const unsigned long long chains = full / chain_slots;
+    a->head = head;
+    a->n = n;
+    a->vend = vend;
+    a->main0 = s0;
+    a->chains = chains;
+    a->epi0 = s0 + chains * chain_slots;
+    a->epi1 = slots + s0;
+    if (a->epi0 > a->epi1) a->epi0 = a->epi1;                  // n smaller than the head slot
+    a->slots = slots;
+}
 
 struct Plan {
     SumArgs a;
@@ -391,7 +418,7 @@ __device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *bas
 // waves, the rest of the domain through the conventional path on the other
 // waves, all in the same pass.
 template <int KERNEL, int DT, int R, int U, bool NT, bool HALF>
-__global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
+__global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
 {
     const unsigned lane = threadIdx.x & 63u;
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // wave-uniform
@@ -400,9 +427,22 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs a)
     const unsigned long long W = (unsigned long long)gridDim.x * wpb;
     const unsigned long long w = (unsigned long long)blockIdx.x * wpb + wave;
 
+    SumArgs a = launch_args;             // as seen by this block's row
     const unsigned long long row = blockIdx.y;
+    const char *x = (const char *)a.x + row * a.row_bytes;
     const uint4v *base = (const uint4v *)((const char *)a.base + row * a.row_bytes);
-    const void *x = (const char *)a.x + row * a.row_bytes;
+    if (launch_args.per_row_phase) {
+        // rows of differing 16-byte phase: the slot arithmetic of this row (all wave-uniform)
+        const unsigned int before = (unsigned int)((size_t)x & 15u);
+        base = (const uint4v *)(x - before);
+        region_fields(launch_args.n, before / (16u / ElemTraits<DT>::per_slot), ElemTraits<DT>::per_slot,
+                      (HALF ? 32u : 64u) * (unsigned)R, &a);
+        if constexpr (KERNEL == MFR_KERNEL_SPLIT) {
+            // the host split the chains of a row that starts on a boundary; this row may have one fewer
+            if (launch_args.split_chains >= launch_args.chains || launch_args.split_chains > a.chains)
+                a.split_chains = a.chains;
+        }
+    }
 
     float partial;                       // the wave's fp32 partial, uniform
     if constexpr (KERNEL == MFR_KERNEL_MFMA) {

@@ -29,8 +29,8 @@ __global__ void __launch_bounds__(1024) combine_kernel(const float *partials, un
 
 __global__ void store_zero_kernel(float *out, unsigned long long count)
 {
-    const unsigned long long i = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) out[i] = 0.f;
+    const unsigned long long step = (unsigned long long)gridDim.x * blockDim.x;
+    for (unsigned long long i = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += step) out[i] = 0.f;
 }
 
 thread_local char g_hip_error[256] = "";
@@ -186,25 +186,9 @@ void plan_region(size_t n, size_t x_addr, unsigned esize, const mfr_tuning &t, P
     p->half = t.block_threads == 32;
     p->threads = p->half ? 64 : t.block_threads;
     p->waves = p->threads / 64;
-    const unsigned long long per_slot = 16u / esize;
-    const unsigned long long ts = p->half ? 32ull : 64ull;
-    const unsigned int head = (unsigned int)((x_addr & 15u) / esize);
-    const unsigned long long vend = (unsigned long long)head + n;
-    const unsigned long long slots = (vend + per_slot - 1ull) / per_slot;
-    const unsigned long long s0 = head ? 1ull : 0ull;
-    const unsigned long long s1 = vend / per_slot;             // slots that end at or before vend
-    const unsigned long long full = s1 > s0 ? s1 - s0 : 0ull;
-    const unsigned long long chains = full / (ts * (unsigned)t.chain_R);
-    p->a.head = head;
-    p->a.n = n;
-    p->a.vend = vend;
-    p->a.main0 = s0;
-    p->a.chains = chains;
-    p->a.epi0 = s0 + chains * ts * (unsigned)t.chain_R;
-    p->a.epi1 = slots + (head ? 1ull : 0ull);
-    if (p->a.epi0 > p->a.epi1) p->a.epi0 = p->a.epi1;          // n smaller than the head slot
-    p->a.slots = slots;
-    p->chains = chains;
+    const unsigned int ts = p->half ? 32u : 64u;
+    mfr::region_fields(n, (unsigned int)((x_addr & 15u) / esize), 16u / esize, ts * (unsigned)t.chain_R, &p->a);
+    p->chains = p->a.chains;
 }
 
 int device_info(int dev, DeviceInfo *out)
@@ -385,7 +369,8 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
 
 int fill_zero(float *out, size_t count, hipStream_t stream)
 {
-    const unsigned blocks = (unsigned)((count + 255) / 256);
+    const size_t want = (count + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 65536 ? want : 65536);      // the kernel strides over the rest
     hipLaunchKernelGGL(store_zero_kernel, dim3(blocks), dim3(256), 0, stream, out, (unsigned long long)count);
     MFR_HIP(hipGetLastError());
     return MFR_OK;
@@ -399,7 +384,6 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     const int st = resolve_tuning(tin, dtype, &t);
     if (st != MFR_OK) return st;
     const unsigned esize = elem_size(dtype);
-    resolve_load_policy(&t, rows * cols * esize);
     if (!out) return MFR_ERR_INVALID_ARG;
     if (rows > 0 && cols > 0 && !x) return MFR_ERR_INVALID_ARG;
     if (((size_t)x & (esize - 1u)) != 0) return MFR_ERR_INVALID_ARG;
@@ -407,6 +391,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     if (rows > 1 && row_stride < cols) return MFR_ERR_INVALID_ARG;
     if (!span_fits(rows, cols, row_stride)) return MFR_ERR_INVALID_ARG;
     if (rows == 0) return MFR_OK;
+    resolve_load_policy(&t, rows * cols * esize);      // rows * cols <= the span < 2^60: no overflow
 
     int dev = 0;
     MFR_HIP(hipGetDevice(&dev));
@@ -446,11 +431,13 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     if (tin == nullptr && rows > 1) t.block_threads = block_threads_for_rows(rows, info.cus);
     const size_t batch = rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch;
 
-    // Rows that share their 16-byte phase are addressed in aligned slots counted from the boundary
-    // at or below their first element (the head slot is read element-wise).  Rows of differing phase
-    // are addressed from their own first element: no head, unaligned 128-bit loads.
+    // Rows are addressed in aligned slots counted from the boundary at or below their first element
+    // (the head slot is read element-wise).  Rows that share their 16-byte phase share the slot
+    // arithmetic done here; rows of differing phase are planned as if they started on a boundary
+    // (which gives the largest number of chains), and each block redoes the arithmetic for its row.
     Plan p;
     plan_region(cols, same_phase ? (size_t)x : 0, esize, t, &p);
+    p.a.per_row_phase = same_phase ? 0u : 1u;
     const long long grid = grid_blocks_for(p, t, info.cus, batch);
     if (grid < 1) return MFR_ERR_INVALID_ARG;
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
@@ -466,7 +453,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     for (size_t r0 = 0; r0 < rows; r0 += batch) {
         const size_t nr = rows - r0 < batch ? rows - r0 : batch;
         const char *xr = (const char *)x + r0 * row_stride * esize;
-        p.a.base = same_phase ? (const uint4v *)((size_t)xr & ~(size_t)15) : (const uint4v *)xr;
+        p.a.base = (const uint4v *)((size_t)xr & ~(size_t)15);
         p.a.x = xr;
         p.a.row_bytes = (unsigned long long)row_stride * esize;
         if (t.kernel == MFR_KERNEL_SPLIT) {

@@ -90,7 +90,7 @@ INT_CASES = [
     (700, 2500, 2504, 0), (513, 4001, 4003, 6),                                      # long rows from 512 rows on
 ]
 
-# few rows whose 16-byte phases differ: the per-row kernels, every row addressed from its own first element
+# few rows whose 16-byte phases differ: the per-row kernels, every block doing the slot arithmetic of its own row
 MIXED_PHASE_CASES = [(33, 1001, 1001, 0), (100, 37, 39, 1), (1000, 5, 5, 0), (40, 20000, 20001, 0), (7, 100003, 100003, 0),
                      (300, 9001, 9003, 3), (2, 1 << 20 | 1, (1 << 20) + 5, 0), (150, 1, 3, 0)]
 
@@ -117,6 +117,9 @@ def test_few_rows_of_differing_phase_bit_exact(dtype, rows, cols, stride, shift)
     tunings = [None, B.make_tuning(256, 2), B.make_tuning(64, 8, 0, B.MFR_KERNEL_SHFL, 1), B.make_tuning(128, 1, 3, 0, 4, 2)]
     if dtype == F16:
         tunings.append(B.make_tuning(32, 4))
+        # split kernel: the chains of a row that starts off a boundary can be one fewer than the host planned
+        tunings += [B.make_tuning(256, 2, 0, B.MFR_KERNEL_SPLIT, 0, 0, 0, f) for f in (0, 500, 1000)]
+        tunings.append(B.make_tuning(64, 1, 1, B.MFR_KERNEL_SPLIT, 1, 0, 0, 999))
     for t in tunings:
         got = call(dtype, inp, rows, cols, stride, t).astype(np.float64)
         bad = np.nonzero(got != want)[0]
