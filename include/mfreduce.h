@@ -155,7 +155,9 @@ int mfr_sum_ex(const void *x, int dtype, size_t n, float *out, const mfr_tuning 
  * rows == 0 does nothing; cols == 0 writes zeros.
  * With t == NULL the library picks the kernel: many rows go through one launch
  * in which the 16 accumulator columns of a chain are shared out among rows
- * (mfr_rows_plan shows the shape); few long rows get a grid of blocks each.
+ * (mfr_rows_plan shows the shape); few rows, rows of 16 KiB or more, and rows
+ * of a 16-bit type of 4 KiB or more that start 2 bytes off a 4-byte boundary
+ * get a grid of blocks (or one block) each.
  * That first kernel loads 16-byte slots counted from each row's first element
  * and masks what lies past the row's end, so bytes after a row (in the gap or
  * in the next rows, inside [x, x + ((rows - 1) * row_stride + cols) * element
@@ -164,9 +166,9 @@ int mfr_sum_ex(const void *x, int dtype, size_t n, float *out, const mfr_tuning 
  * With explicit tuning every row is reduced exactly as a single call would
  * (Section 5.2), grid_blocks counting blocks per row and MFR_GRID_AUTO dividing
  * the persistent grid among the rows (rounded down), all rows in one launch (up
- * to 65535 rows per launch).  Rows whose stride is a multiple of 16 bytes are read
- * in aligned 16-byte slots; otherwise every row is addressed from its own first
- * element with 128-bit loads at element alignment.
+ * to 65535 rows per launch).  Every row is read in aligned 16-byte slots, its
+ * first and last partial slot element by element, whatever its 16-byte phase;
+ * nothing outside a row is read.
  */
 int mfr_sum_rows_ex(const void *x, int dtype, size_t rows, size_t cols, size_t row_stride, float *out,
                     const mfr_tuning *t, hipStream_t stream);

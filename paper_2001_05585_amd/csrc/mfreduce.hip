@@ -228,11 +228,14 @@ long long grid_blocks_for(const Plan &p, const mfr_tuning &t, int cus, size_t ro
     return (long long)g;
 }
 
-// Block size for `rows` rows sharing the persistent grid (one wave per SIMD in all): the CUs hold
-// cus * 256 / block blocks; a row gets floor(that / rows) of them (at least one).  Fewest rounds of
-// blocks first, then the fullest round; a smaller block must fill more than a tenth better to win.
-int block_threads_for_rows(size_t rows, int cus)
+// Block size for `rows` rows of row_bytes bytes sharing the persistent grid (one wave per SIMD in
+// all): the CUs hold cus * 256 / block blocks; a row gets floor(that / rows) of them (at least one).
+// Fewest rounds of blocks first, then the fullest round; a smaller block must fill more than a
+// tenth better to win.  With more rows than the CUs hold 64-thread blocks every row is one block
+// anyway and the row's length decides (measured with 512 MiB of rows of 4 KiB to 512 KiB).
+int block_threads_for_rows(size_t rows, size_t row_bytes, int cus)
 {
+    if (rows >= (size_t)cus * 4u) return row_bytes < 12288u ? 64 : (row_bytes < 32768u ? 128 : 256);
     int best_block = 256;
     unsigned long long best_rounds = 0;
     double best_fill = 0.0;
@@ -322,20 +325,28 @@ bool span_fits(size_t rows, size_t cols, size_t row_stride)
 bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, size_t row_stride, int cus,
                      mfr::RowsTiledShape *s, unsigned *grid)
 {
-    (void)x_addr;                        // slots are counted from each row's first element: no phase
     if (rows < 2 || cols == 0) return false;
     const unsigned long long per_slot = 16u / esize;
     const unsigned long long stride_bytes = (unsigned long long)row_stride * esize;
     const unsigned long long row_bytes = (unsigned long long)cols * esize;
     // rows this long are streamed as well or better by a grid of blocks per row
-    if (row_bytes > kRowsTiledMaxRowBytes) return false;
+    if (row_bytes >= kRowsTiledMaxRowBytes) return false;
+    // 128-bit loads at 2-byte alignment lose a quarter of the rate; the per-row kernels read aligned
+    // slots whatever the rows' phases, and from 4 KiB rows on that is the better deal
+    const bool two_byte_phase = esize == 2u && ((x_addr & 2u) != 0u || (stride_bytes & 2u) != 0u);
+    if (two_byte_phase && row_bytes >= kRowsTiledLongRowBytes) return false;
     int lp = 0;
     while (lp < 4 && (64ull << lp) < row_bytes) ++lp;
     int d = 1, gf = 8;
     if (rows >= kRowsTiledMinRows && row_bytes < kRowsTiledLongRowBytes) {
         if (lp == 4) gf = 4;
     } else if (lp == 4 && rows >= kRowsTiledMinLongRows) {
-        lp = 4; d = 4; gf = 1;
+        d = 4; gf = 1;
+        // A step of four tiles leaves up to 4 KiB of its last step empty.  Rows that would waste
+        // more than a fifth of their steps go four side by side, 1 KiB each per step, unless their
+        // stride is a multiple of 1 KiB (the four pieces would share memory channels).
+        const unsigned long long steps4 = (row_bytes + 4095ull) / 4096ull;
+        if (row_bytes * 5ull < steps4 * 4096ull * 4ull && (stride_bytes % 1024ull) != 0) { d = 1; gf = 4; }
     } else {
         return false;
     }
@@ -428,7 +439,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
 
     // Row counts that do not divide the CUs well: smaller blocks, more of them per CU, fill the
     // device in one round (300 rows: 86 % with 64-thread blocks against 70 % with 256-thread ones).
-    if (tin == nullptr && rows > 1) t.block_threads = block_threads_for_rows(rows, info.cus);
+    if (tin == nullptr && rows > 1) t.block_threads = block_threads_for_rows(rows, cols * esize, info.cus);
     const size_t batch = rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch;
 
     // Rows are addressed in aligned slots counted from the boundary at or below their first element

@@ -83,11 +83,11 @@ def expect_plan(dtype, inp, rows, cols, stride, **want):
 # (rows, cols, stride, shift) chosen to reach every kernel shape, masked and unmasked
 INT_CASES = [
     (4096, 32, 32, 0), (4099, 64, 64, 0), (4100, 128, 128, 0), (2050, 256, 256, 0), (2048, 512, 512, 0),
-    (2048, 1024, 1024, 0), (2049, 4096, 4096, 0), (600, 2048, 2048, 0),             # unmasked steps only
+    (2048, 1024, 1024, 0), (2049, 2048, 2048, 4), (600, 2048, 2048, 0),             # unmasked steps only
     (5003, 1, 1, 0), (5003, 1, 1, 1), (5003, 7, 7, 3), (5003, 31, 33, 0), (5003, 33, 40, 0), (4001, 64, 64, 1),
     (4001, 65, 72, 0), (4001, 100, 100, 0), (4001, 129, 131, 5), (3000, 255, 256, 0), (3000, 300, 304, 7),
-    (2500, 500, 500, 2), (2100, 1001, 1001, 0), (2100, 1536, 1544, 4), (2049, 3000, 3001, 0),
-    (700, 2500, 2504, 0), (513, 4001, 4003, 6),                                      # long rows from 512 rows on
+    (2500, 500, 500, 2), (2100, 1001, 1001, 0), (2100, 1536, 1544, 4), (2049, 3000, 3002, 0),
+    (700, 2500, 2504, 0), (513, 3501, 3504, 6),                                      # long rows from 512 rows on
 ]
 
 # few rows whose 16-byte phases differ: the per-row kernels, every block doing the slot arithmetic of its own row
@@ -101,6 +101,24 @@ def test_integer_rows_bit_exact(dtype, rows, cols, stride, shift, oracle_lib):
     vals = W.small_integers(rows * cols, seed=rows * 31 + cols, lo=-4, hi=4).astype(np.float32).reshape(rows, cols)
     inp = RowsInput(dtype, encode(dtype, vals).reshape(rows, cols), stride, shift)
     expect_plan(dtype, inp, rows, cols, stride)
+    want = vals.astype(np.float64).sum(axis=1)
+    got = call(dtype, inp, rows, cols, stride).astype(np.float64)
+    bad = np.nonzero(got != want)[0]
+    assert bad.size == 0, (rows, cols, stride, shift, bad[:5], got[bad[:5]], want[bad[:5]])
+
+
+# many 16-bit rows of 4 KiB or more that start 2 bytes off a 4-byte boundary, and rows of 16 KiB or more:
+# the per-row kernels again (aligned slots whatever the phase), one block per row
+LONG_ROWS_PER_ROW_CASES = [(2049, 3000, 3001, 0), (513, 4001, 4003, 6), (2049, 4096, 4096, 1), (1500, 2048, 2048, 3),
+                           (66000, 2048, 2049, 0), (1100, 8192, 8192, 0), (1100, 9001, 9001, 0)]
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("rows,cols,stride,shift", LONG_ROWS_PER_ROW_CASES)
+def test_many_long_rows_through_the_per_row_kernels_bit_exact(dtype, rows, cols, stride, shift):
+    vals = W.small_integers(rows * cols, seed=rows * 13 + cols, lo=-4, hi=4).astype(np.float32).reshape(rows, cols)
+    inp = RowsInput(dtype, encode(dtype, vals).reshape(rows, cols), stride, shift)
+    assert B.mfr_rows_plan(inp.ptr, dtype, rows, cols, stride, cus()) is None
     want = vals.astype(np.float64).sum(axis=1)
     got = call(dtype, inp, rows, cols, stride).astype(np.float64)
     bad = np.nonzero(got != want)[0]
@@ -141,7 +159,7 @@ def test_shapes_reach_every_kernel_shape():
 
 @pytest.mark.parametrize("dtype,kind", [(F16, "normal"), (F16, "uniform01"), (BF16, "normal"), (F32, "uniform_pm1")])
 @pytest.mark.parametrize("rows,cols,stride,shift", [(4096, 64, 64, 0), (3001, 100, 104, 1), (2048, 1024, 1024, 0),
-                                                    (2051, 777, 777, 0), (600, 3000, 3000, 3)])
+                                                    (2051, 777, 777, 0), (600, 3000, 3000, 2)])
 def test_random_rows_within_tolerance(dtype, kind, rows, cols, stride, shift, oracle_lib):
     seed = 7000 + rows + cols
     if dtype == F16:

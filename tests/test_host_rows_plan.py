@@ -85,7 +85,8 @@ SHAPES = [
     (0, 2048, 64, 64), (0, 2048, 32, 32), (0, 2048, 128, 128), (0, 2048, 256, 256), (0, 2048, 512, 512),
     (0, 2048, 1024, 1024), (0, 2100, 100, 100), (2, 2049, 64, 64), (14, 2048, 64, 72), (6, 2048, 7, 7),
     (0, 2048, 1, 1), (2, 2048, 1, 1), (0, 2048, 3, 5), (8, 2500, 33, 40), (0, 2048, 1001, 1001),
-    (4, 2048, 520, 523), (0, 600, 700, 704), (2, 600, 3000, 3001), (0, 1040, 33, 37), (6, 1033, 3, 3),
+    (4, 2048, 520, 523), (0, 600, 700, 704), (4, 600, 3000, 3002), (0, 600, 2304, 2312), (2, 1100, 2000, 2001),
+    (0, 1040, 33, 37), (6, 1033, 3, 3),
 ]
 
 
@@ -120,10 +121,21 @@ def test_choice_between_kernels():
     assert B.mfr_rows_plan(1 << 20, f16, 100, 64, 64, 256) is None
     assert B.mfr_rows_plan(1 << 20, f16, 100, 1001, 1001, 256) is None         # ... whatever their phases
     assert B.mfr_rows_plan(1 << 20, f16, 600, 4096, 4096, 256) is not None     # long rows from 512 rows on
-    assert B.mfr_rows_plan(1 << 20, f16, 600, 4097, 4097, 256) is not None
+    assert B.mfr_rows_plan(1 << 20, f16, 600, 4098, 4098, 256) is not None
     assert B.mfr_rows_plan(1 << 20, f16, 4096, 8, 8, 256) is not None
-    assert B.mfr_rows_plan(1 << 20, f16, 4096, 16384, 16384, 256) is None      # rows beyond 16 KiB: a grid per row
+    assert B.mfr_rows_plan(1 << 20, f16, 4096, 8191, 8192, 256) is not None
+    assert B.mfr_rows_plan(1 << 20, f16, 4096, 8192, 8192, 256) is None        # rows from 16 KiB on: a grid per row
     assert B.mfr_rows_plan(1 << 20, f16, 4096, 16385, 16385, 256) is None
+    # 16-bit rows of 4 KiB or more that start 2 bytes off a 4-byte boundary: a grid per row (aligned slots)
+    assert B.mfr_rows_plan(1 << 20, f16, 600, 4097, 4097, 256) is None
+    assert B.mfr_rows_plan((1 << 20) + 2, f16, 600, 4096, 4096, 256) is None
+    assert B.mfr_rows_plan((1 << 20) + 4, f16, 600, 4096, 4096, 256) is not None
+    assert B.mfr_rows_plan((1 << 20) + 2, f16, 4096, 2047, 2047, 256) is not None
+    assert B.mfr_rows_plan((1 << 20) + 4, B.MFR_DTYPE_F32, 600, 2049, 2049, 256) is not None
+    # long rows: four tiles of one row per step, unless that wastes over a fifth of the steps
+    assert B.mfr_rows_plan(1 << 20, f16, 600, 6000, 6000, 256)[:3] == (16, 4, 1)
+    assert B.mfr_rows_plan(1 << 20, f16, 600, 2304, 2304, 256)[:3] == (16, 1, 4)
+    assert B.mfr_rows_plan(1 << 20, f16, 600, 2560, 2560, 256)[:3] == (16, 4, 1)     # stride a multiple of 1 KiB
 
 
 def test_invalid_arguments():
