@@ -262,6 +262,17 @@ int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *t, unsigne
 int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row_stride, int cus,
                   unsigned long long plan[11]);
 
+/*
+ * Frees the scratch that calls on `stream` of the current device have left
+ * with the library (block partials, ticket counters, the recurrence variant's
+ * level buffers), after synchronising the stream.  For streams that are about
+ * to be destroyed, or to hand the memory back; a later call on the stream
+ * allocates again.  Returns MFR_OK also when the stream holds none.  Must not
+ * overlap with other libmfreduce calls on the same stream, and not be called
+ * while the stream is being captured into a graph.
+ */
+int mfr_release_scratch(hipStream_t stream);
+
 /* Static text for a status code. */
 const char *mfr_strerror(int status);
 

@@ -22,7 +22,7 @@ MFR_DTYPE_F16, MFR_DTYPE_BF16, MFR_DTYPE_F32 = 0, 1, 2
 
 EXPORTS = ("mfr_sum_f16", "mfr_sum_f16_tuned", "mfr_sum_f16_ex", "mfr_sum_bf16", "mfr_sum_f32", "mfr_sum_ex",
            "mfr_sum_rows_ex", "mfr_sum_f16_rows", "mfr_sum_f16_recurrence", "mfr_sum_f16_f64", "mfr_sum_f16_f64_ex", "mfr_get_default_tuning", "mfr_grid_for", "mfr_plan_for",
-           "mfr_plan_ex", "mfr_rows_plan", "mfr_strerror", "mfr_last_hip_error", "mfr_version")
+           "mfr_plan_ex", "mfr_rows_plan", "mfr_release_scratch", "mfr_strerror", "mfr_last_hip_error", "mfr_version")
 
 
 class mfr_tuning(ctypes.Structure):
@@ -86,6 +86,8 @@ def lib() -> ctypes.CDLL:
     L.mfr_grid_for.restype = ctypes.c_longlong
     L.mfr_plan_for.argtypes = [sz, sz, ctypes.POINTER(mfr_tuning), ctypes.POINTER(ctypes.c_ulonglong)]
     L.mfr_plan_for.restype = ci
+    L.mfr_release_scratch.argtypes = [ctypes.c_void_p]
+    L.mfr_release_scratch.restype = ci
     L.mfr_strerror.argtypes = [ci]
     L.mfr_strerror.restype = ctypes.c_char_p
     L.mfr_last_hip_error.argtypes = []
@@ -194,6 +196,10 @@ def mfr_plan_for(n: int, x_addr: int, t: mfr_tuning | None = None):
     tp = ctypes.byref(t) if t is not None else None
     _check(lib().mfr_plan_for(n, x_addr, tp, plan), "mfr_plan_for")
     return tuple(int(v) for v in plan)
+
+
+def mfr_release_scratch(stream: int = 0) -> None:
+    _check(lib().mfr_release_scratch(stream), "mfr_release_scratch")
 
 
 def mfr_strerror(status: int) -> str:

@@ -752,6 +752,26 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
     return 1;
 }
 
+int mfr_release_scratch(hipStream_t stream)
+{
+    int dev = 0;
+    MFR_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const auto it = g_scratch.find(std::make_pair(dev, stream));
+    if (it == g_scratch.end()) return MFR_OK;
+    MFR_HIP(hipStreamSynchronize(stream));       // earlier calls on the stream may still be using it
+    Scratch &s = it->second;
+    hipError_t first = hipSuccess;
+    for (void *mem : {(void *)s.partials, (void *)s.tickets, (void *)s.levels}) {
+        if (!mem) continue;
+        const hipError_t e = hipFree(mem);
+        if (e != hipSuccess && first == hipSuccess) first = e;
+    }
+    g_scratch.erase(it);
+    if (first != hipSuccess) return hip_fail(first, "hipFree(scratch)");
+    return MFR_OK;
+}
+
 const char *mfr_strerror(int status)
 {
     switch (status) {
@@ -765,6 +785,6 @@ const char *mfr_strerror(int status)
 
 const char *mfr_last_hip_error(void) { return g_hip_error; }
 
-int mfr_version(void) { return 300; }
+int mfr_version(void) { return 400; }
 
 }  // extern "C"

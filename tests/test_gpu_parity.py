@@ -315,6 +315,25 @@ def test_two_streams_overlap(oracle_lib):
     assert within_tolerance(ra[0], sa_, saa) and within_tolerance(rb[0], sb_, sba)
 
 
+def test_release_scratch_and_use_the_stream_again():
+    n = (1 << 22) + 77
+    d = DeviceInput(W.ones(n), 1)
+    o = Outputs(6)
+    s1 = torch.cuda.Stream()
+    B.mfr_release_scratch(s1.cuda_stream)                 # nothing held yet: fine
+    B.mfr_sum_f16_ex(d.ptr, n, o.ptr(0), B.make_tuning(64, 1, 65536), s1.cuda_stream)     # a large scratch
+    B.mfr_sum_f16_recurrence(d.ptr, n, o.ptr(1), 2, s1.cuda_stream)
+    B.mfr_release_scratch(s1.cuda_stream)                 # synchronises the stream first
+    B.mfr_sum_f16(d.ptr, n, o.ptr(2), s1.cuda_stream)     # allocates again
+    B.mfr_sum_f16_ex(d.ptr, n, o.ptr(3), B.make_tuning(64, 1, 65536), s1.cuda_stream)
+    B.mfr_release_scratch(s1.cuda_stream)
+    B.mfr_release_scratch(s1.cuda_stream)
+    B.mfr_sum_f16(d.ptr, n, o.ptr(4), stream_handle())    # other streams are not affected
+    B.mfr_sum_f16(d.ptr, n, o.ptr(5), s1.cuda_stream)
+    s1.synchronize()
+    assert np.all(o.get()[[0, 2, 3, 4, 5]] == float(n))   # (the recurrence variant's fp16 partials overflow here)
+
+
 def test_alternating_inputs_never_see_the_previous_calls_partials():
     # the scratch of a stream is reused by every call: a partial left over from the previous call must
     # never be read.  Two inputs with different exact sums alternate on one stream.
