@@ -79,6 +79,8 @@ def test_config3_normal_2p28_headline(oracle_lib):
     dev = upload(x)
     tunings = [None, B.make_tuning(kernel=B.MFR_KERNEL_SHFL), B.make_tuning(128, 4, B.MFR_GRID_ONE_CHAIN),
                B.make_tuning(256, 1), B.make_tuning(1024, 8, 4096)]
+    # the split variant of Section 5.3 at the fractions `bench.py --sweep split` times
+    tunings += [B.make_tuning(256, 4, 0, B.MFR_KERNEL_SPLIT, 2, 0, 0, f) for f in (0, 100, 500, 900, 1000)]
     r = run_all(dev, n, tunings)
     err = np.abs(r - s)
     print("config 3: gpu=%.6f oracle=%.6f |err|/sum|x|=%.3g |err|/|sum|=%.3g" % (r[0], s, err[0] / sa, err[0] / abs(s)))
@@ -87,6 +89,60 @@ def test_config3_normal_2p28_headline(oracle_lib):
     s1, sa1 = oracle_of(oracle_lib, x[1:])
     r1 = run_all(dev, n - 1, [None, B.make_tuning(kernel=B.MFR_KERNEL_SHFL)], offset_elems=1)
     assert (np.abs(r1 - s1) / sa1).max() <= TOL
+
+
+def test_rows_at_the_sweep_sizes_sampled_rows(oracle_lib):
+    """The batched entry on 512 MiB of rows, library defaults (the shapes `bench.py --sweep rows` times):
+    sampled rows against the oracle, one by one."""
+    total = 1 << 28
+    x = W.generate("normal", total, W.config_seed(3))
+    dev = upload(x)
+    rng = np.random.default_rng(31)
+    out = torch.empty((1 << 23) + 1, dtype=torch.float32, device="cuda")
+    shapes = [(32, 32, 0), (64, 64, 0), (256, 256, 1), (1024, 1024, 0), (1001, 1001, 0), (2304, 2304, 0), (4096, 4096, 0),
+              (4096, 4096, 1), (5001, 5001, 0), (8192, 8192, 0), (100, 104, 0), (50000, 50001, 0), (16777209, 16777209, 0),
+              (1 << 27, 1 << 27, 0)]
+    for cols, stride, shift in shapes:
+        rows = (total - shift - cols) // stride + 1
+        out.fill_(float("nan"))
+        B.mfr_sum_rows_ex(dev.data_ptr() + 2 * shift, B.MFR_DTYPE_F16, rows, cols, stride, out.data_ptr(), None, stream_handle())
+        torch.cuda.synchronize()
+        got = out[:rows].cpu().numpy().astype(np.float64)
+        assert not np.isnan(got).any(), (cols, stride, shift)
+        assert bool(torch.isnan(out[rows]).item())                       # nothing written past the rows
+        pick = np.unique(np.concatenate([[0, 1, rows - 2, rows - 1], rng.integers(0, rows, 60)]))
+        pick = pick[(pick >= 0) & (pick < rows)]
+        for r in pick:
+            seg = x[shift + r * stride: shift + r * stride + cols]
+            s, sa = oracle_of(oracle_lib, seg)
+            assert abs(got[r] - s) <= TOL * sa, (cols, stride, shift, int(r), got[r], s)
+        # all rows together: the row sums add up to the sum of the elements they cover
+        if stride == cols:
+            s, sa = oracle_of(oracle_lib, x[shift: shift + rows * cols])
+            assert abs(got.sum() - s) <= TOL * sa, (cols, stride, shift)
+
+
+@pytest.mark.parametrize("dtype,kind,n", [(B.MFR_DTYPE_BF16, "normal", 1 << 28), (B.MFR_DTYPE_F32, "uniform_pm1", (1 << 27) + 3)])
+def test_other_element_types_at_512MiB(oracle_lib, dtype, kind, n):
+    """bfloat16 and binary32 input at the size `bench.py --sweep types` times, library defaults and the
+    conventional kernel, against the oracle of the same type."""
+    if dtype == B.MFR_DTYPE_BF16:
+        x = W.generate_bf16(kind, n, W.config_seed(3))
+        s, sa = oracle_lib.sum_bf16(x)
+        dev, esize = torch.from_numpy(x.view(np.int16)).cuda(), 2
+    else:
+        x = W.generate_f32(kind, n, W.config_seed(4))
+        s, sa = oracle_lib.sum_f32(x)
+        dev, esize = torch.from_numpy(x).cuda(), 4
+    tunings = [None, B.make_tuning(kernel=B.MFR_KERNEL_SHFL), B.make_tuning(512, 2, 1000)]
+    o = Outputs(2 * len(tunings))
+    for i, t in enumerate(tunings):
+        B.mfr_sum_ex(dev.data_ptr(), dtype, n, o.ptr(2 * i), t, stream_handle())
+        B.mfr_sum_ex(dev.data_ptr() + esize, dtype, n - 1, o.ptr(2 * i + 1), t, stream_handle())     # a slice from element 1
+    r = o.get().astype(np.float64)
+    first = float(oracle_lib.bf16_to_f64(int(x[0]))) if dtype == B.MFR_DTYPE_BF16 else float(x[0])
+    assert (np.abs(r[0::2] - s) / sa).max() <= TOL, (r, s)
+    assert (np.abs(r[1::2] - (s - first)) / sa).max() <= TOL + 1e-12, (r, s, first)
 
 
 @pytest.mark.parametrize("n", [400_000_000, 400_000_007])
