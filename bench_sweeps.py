@@ -485,6 +485,53 @@ def rows(args, torch, np, B, W):
             measure(f, dtype, n // 256 - 1, 256, 256, 1, None, "default")
 
 
+def graph(args, torch, np, B, W):
+    """Many small sums per submission: 64 independent calls issued one by one against the same 64 calls
+    captured once into a HIP graph and replayed (the calls only launch kernels once a stream's scratch
+    exists, so they can be captured).  Each call has its own input and output; sizes where the launch
+    cost, not the memory, bounds the call."""
+    calls = 64
+    s = torch.cuda.Stream()
+    with open_out(args, "graph.txt") as f:
+        emit(f, "# %d sums per submission, one stream; us per sum; n  eager  graph  eager/graph  sums_exact" % calls)
+        for n in (1 << 10, 1 << 12, 1 << 14, 1 << 15, 49152, 1 << 16, 98304, 1 << 17, 196608, 1 << 18, 1 << 20, 1 << 22):
+            x = W.small_integers(n * calls, seed=n, lo=-2, hi=2)
+            dev = torch.from_numpy(x.view(np.int16)).cuda()
+            want = x.astype(np.float64).reshape(calls, n).sum(axis=1)
+            out = torch.zeros(calls, dtype=torch.float32, device="cuda")
+
+            def issue():
+                for i in range(calls):
+                    B.mfr_sum_f16(dev.data_ptr() + 2 * n * i, n, out.data_ptr() + 4 * i, s.cuda_stream)
+            with torch.cuda.stream(s):
+                issue()                                   # allocates the stream's scratch
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                issue()
+            reps = max(3, args.steps // 4)
+            times = []
+            for mode in ("eager", "graph"):
+                out.zero_()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                with torch.cuda.stream(s):
+                    e0.record()
+                    for _ in range(reps):
+                        if mode == "eager":
+                            issue()
+                        else:
+                            g.replay()
+                    e1.record()
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1) * 1e3 / (reps * calls))
+                exact = bool(np.array_equal(out.cpu().numpy().astype(np.float64), want))
+                if not exact:
+                    raise SystemExit("graph sweep: wrong sums in %s mode at n = %d" % (mode, n))
+            emit(f, "%d %.2f %.2f %.2f yes" % (n, times[0], times[1], times[0] / times[1]))
+            del g
+
+
 def run(args):
     import numpy as np
     import torch
@@ -494,4 +541,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants, "wide": wide, "combine": combine, "warm": warm}[args.sweep](args, torch, np, B, W)
+    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants, "wide": wide, "combine": combine, "warm": warm, "graph": graph}[args.sweep](args, torch, np, B, W)

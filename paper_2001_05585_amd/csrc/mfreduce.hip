@@ -76,6 +76,7 @@ constexpr int kDefaultWavesPerCU = 4;          // one wave per SIMD
 constexpr long long kTicketMaxBlocks = 2048;   // AUTO: larger grids combine with a second launch
 constexpr long long kTicketHardMax = 65536;    // single-launch combine is not offered beyond this
 constexpr size_t kMaxRowsPerLaunch = 65535;    // gridDim.y limit
+constexpr unsigned long long kOneBlockMaxChains = 32;   // library defaults: arrays this short get one block
 // Inputs that fit in the eight 4 MiB L2s may be resident there (a reduction often follows the kernel
 // that produced its input): they are read with ordinary loads, which hit in L2 (20 % faster at 32 MiB
 // when resident, 3-6 % slower when not).  Larger inputs stream through with non-temporal loads (8 %
@@ -89,12 +90,13 @@ struct DefaultGeometry {
     int block;
     int chain_R;      // 0: the per-type default
     bool valid;
+    bool overridden;  // a variable is set: the library's own choices of block size stand back
 };
 
 const DefaultGeometry &default_geometry()
 {
     static const DefaultGeometry g = [] {
-        DefaultGeometry d = {kDefaultBlock, 0, true};
+        DefaultGeometry d = {kDefaultBlock, 0, true, getenv("MFR_BLOCK") != nullptr || getenv("MFR_R") != nullptr};
         if (const char *e = getenv("MFR_BLOCK")) {
             char *end = nullptr;
             const long v = strtol(e, &end, 10);
@@ -205,6 +207,18 @@ int device_info(int dev, DeviceInfo *out)
     }
     *out = d;
     return MFR_OK;
+}
+
+// Library defaults, single array of at most kOneBlockMaxChains chains: one block with a wave per
+// chain (up to 16 waves).  Rewrites the block size and the grid of *t and returns true if so.
+bool one_block_default(unsigned long long chains, mfr_tuning *t)
+{
+    if (default_geometry().overridden || chains > kOneBlockMaxChains) return false;
+    int waves = 1;
+    while ((unsigned long long)waves < chains && waves < 16) waves *= 2;
+    t->block_threads = 64 * waves;
+    t->grid_blocks = 1;
+    return true;
 }
 
 // Blocks per row.  `rows` rows share the persistent grid.
@@ -448,6 +462,10 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     // (which gives the largest number of chains), and each block redoes the arithmetic for its row.
     Plan p;
     plan_region(cols, same_phase ? (size_t)x : 0, esize, t, &p);
+    // A short single array is summed by one block with a wave per chain (up to 16 waves, two chains
+    // each): combining several blocks costs three dependent device-scope round trips, 1.6 us, which a
+    // call replayed from a graph would see in full (1.9 us against 3.4 us per call).
+    if (tin == nullptr && rows == 1 && one_block_default(p.chains, &t)) plan_region(cols, (size_t)x, esize, t, &p);
     p.a.per_row_phase = same_phase ? 0u : 1u;
     const long long grid = grid_blocks_for(p, t, info.cus, batch);
     if (grid < 1) return MFR_ERR_INVALID_ARG;
@@ -693,6 +711,7 @@ long long mfr_grid_for(size_t n, size_t x_addr, const mfr_tuning *tin)
     if (n == 0) return 1;
     Plan p;
     plan_region(n, x_addr, 2, t, &p);
+    if (tin == nullptr && one_block_default(p.chains, &t)) return 1;
     int cus = 0;
     if (t.grid_blocks == MFR_GRID_AUTO) {
         int dev = 0;
