@@ -103,15 +103,12 @@ template <> struct ElemTraits<MFR_DTYPE_F32> { static constexpr unsigned per_slo
 
 // ---------------------------------------------------------------- loads ---
 
-// A 16-byte slot.  The pointer type claims element alignment only: rows of a batched call may start
-// at any element, and the device serves unaligned 128-bit loads (the instruction is the same).
-typedef uint4v slot_unaligned __attribute__((aligned(2)));
-
+// One aligned 16-byte slot.
 template <bool NT>
 __device__ __forceinline__ uint4v load_slot(const uint4v *p)
 {
-    if constexpr (NT) return __builtin_nontemporal_load((const slot_unaligned *)p);
-    else return *(const slot_unaligned *)p;
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
 }
 
 // Slot q with every element range-checked against [x, x + n).  A slot that
