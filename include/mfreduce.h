@@ -117,6 +117,10 @@ typedef struct mfr_tuning {
  * synchronises the stream before freeing a smaller one); later calls with a
  * grid no larger than before allocate nothing, only launch kernels (no memset
  * nodes), and can therefore be captured into a HIP graph and replayed.
+ * A captured call keeps the scratch addresses of the stream it was captured
+ * on: replays of such a graph must not overlap with each other or with other
+ * calls on that stream, and that stream's scratch must not be released or
+ * enlarged (by a later call with a larger grid) while the graph is in use.
  * With library defaults an array of at most 32 chains (49152 binary16 values)
  * is summed by a single block, which needs no scratch at all.
  */
