@@ -271,6 +271,10 @@ hipError_t launch_rows_tiled_dt(const void *x, unsigned long long rows, unsigned
     a.out = out;
     const int key = s.log2_p * 100 + s.tiles_per_step * 10 + s.groups;
     switch (key) {
+    case 14: return launch_cfg<DT, 0, 1, 4>(a, grid, s.all_plain, nt, stream);
+    case 114: return launch_cfg<DT, 1, 1, 4>(a, grid, s.all_plain, nt, stream);
+    case 214: return launch_cfg<DT, 2, 1, 4>(a, grid, s.all_plain, nt, stream);
+    case 314: return launch_cfg<DT, 3, 1, 4>(a, grid, s.all_plain, nt, stream);
     case 18: return launch_cfg<DT, 0, 1, 8>(a, grid, s.all_plain, nt, stream);
     case 118: return launch_cfg<DT, 1, 1, 8>(a, grid, s.all_plain, nt, stream);
     case 218: return launch_cfg<DT, 2, 1, 8>(a, grid, s.all_plain, nt, stream);

@@ -155,6 +155,8 @@ def test_shapes_reach_every_kernel_shape():
     for p, d, gf in ((1, 1, 8), (2, 1, 8), (4, 1, 8), (8, 1, 8), (16, 1, 4), (16, 4, 1)):
         assert (p, d, gf, 0) in seen, (p, d, gf)
         assert (p, d, gf, 1) in seen, (p, d, gf)
+    # four groups side by side for unmasked 256- and 512-byte rows of the 16-bit types
+    assert (4, 1, 4, 1) in seen and (8, 1, 4, 1) in seen
 
 
 @pytest.mark.parametrize("dtype,kind", [(F16, "normal"), (F16, "uniform01"), (BF16, "normal"), (F32, "uniform_pm1")])
