@@ -472,7 +472,7 @@ def rows(args, torch, np, B, W):
                 measure(f, f16, r, c, c, 0, explicit, "explicit")
             if lr >= 5:
                 measure(f, f16, r - 1, c, c, 1, None, "default")
-        for c, stride in ((100, 100), (100, 104), (1000, 1000), (1001, 1001), (2049, 2049), (2304, 2304), (3000, 3000), (4104, 4104),
+        for c, stride in ((100, 100), (100, 104), (300, 300), (384, 384), (600, 600), (768, 768), (1000, 1000), (1001, 1001), (2049, 2049), (2304, 2304), (3000, 3000), (4104, 4104),
                           (5000, 5000), (5001, 5001), (7000, 7000), (8192, 8192), (50000, 50001),
                           (50002, 50002), (268425, 268425), (268426, 268426), (16777209, 16777209), (16777210, 16777210)):
             r = total // stride

@@ -353,6 +353,17 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     while (lp < 4 && (64ull << lp) < row_bytes) ++lp;
     int d = 1, gf = 8;
     if (rows >= kRowsTiledMinRows && row_bytes < kRowsTiledLongRowBytes) {
+        // Rows over 512 bytes: a step of P = 16 is 1 KiB, and a row that ends early in its last step
+        // leaves the rest of that step's loads empty (520-byte rows ran at 48 % of the peak).  Rows
+        // that are whole steps of a narrower shape take that shape, unmasked (768-byte rows 89 %
+        // against 69 %); rows that fill less than 72 % of their 1 KiB steps take P = 8, whose steps
+        // are 512 bytes (600-byte rows 72 % against 55 %).
+        if (row_bytes > 512 && row_bytes % 1024ull != 0) {
+            const unsigned long long covered = (row_bytes + 1023ull) / 1024ull * 1024ull;
+            if (row_bytes % 512ull == 0) lp = 3;
+            else if (row_bytes % 256ull == 0) lp = 2;
+            else if (row_bytes < 2048 && row_bytes * 100ull < covered * 72ull) lp = 3;
+        }
         // Two steps are in flight per wave: 8 KiB with four groups, 16 KiB with eight.  Unmasked rows
         // of 256 and 512 bytes of the 16-bit types do better with four (256-element rows 88 % against
         // 84 %); shorter rows, masked rows (100-element rows 67 % against 78 %), rows read with 2-byte-aligned

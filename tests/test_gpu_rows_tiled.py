@@ -88,6 +88,8 @@ INT_CASES = [
     (4001, 65, 72, 0), (4001, 100, 100, 0), (4001, 129, 131, 5), (3000, 255, 256, 0), (3000, 300, 304, 7),
     (2500, 500, 500, 2), (2100, 1001, 1001, 0), (2100, 1536, 1544, 4), (2049, 3000, 3002, 0),
     (700, 2500, 2504, 0), (513, 3501, 3504, 6),                                      # long rows from 512 rows on
+    (2048, 384, 384, 0), (2048, 640, 648, 0), (2050, 768, 768, 4), (3000, 600, 600, 0), (2048, 350, 353, 1),
+    (2048, 300, 300, 0), (2049, 192, 192, 0),                                        # rows over 512 bytes in narrower shapes
 ]
 
 # few rows whose 16-byte phases differ: the per-row kernels, every block doing the slot arithmetic of its own row

@@ -86,6 +86,7 @@ SHAPES = [
     (0, 2048, 1024, 1024), (0, 2100, 100, 100), (2, 2049, 64, 64), (14, 2048, 64, 72), (6, 2048, 7, 7),
     (0, 2048, 1, 1), (2, 2048, 1, 1), (0, 2048, 3, 5), (8, 2500, 33, 40), (0, 2048, 1001, 1001),
     (4, 2048, 520, 523), (0, 600, 700, 704), (4, 600, 3000, 3002), (0, 600, 2304, 2312), (2, 1100, 2000, 2001),
+    (0, 2048, 384, 384), (0, 2048, 640, 640), (0, 2048, 768, 768), (0, 2048, 300, 300), (6, 2048, 350, 353), (0, 2048, 700, 704),
     (0, 1040, 33, 37), (6, 1033, 3, 3),
 ]
 
@@ -112,6 +113,20 @@ def test_power_of_two_rows_are_unmasked_at_any_alignment():
     # slots are counted from each row's first element: the base address and the stride do not matter
     plan = B.mfr_rows_plan((1 << 20) + 6, B.MFR_DTYPE_F16, 4096, 64, 67, 256)
     assert plan[0] == 2 and plan[9] == 1 and plan[8] == 4096
+
+
+def test_rows_over_512_bytes_take_the_shape_that_wastes_least():
+    f16, f32 = B.MFR_DTYPE_F16, B.MFR_DTYPE_F32
+    shape = lambda dt, cols: B.mfr_rows_plan(1 << 20, dt, 4096, cols, cols, 256)
+    assert shape(f16, 384)[:3] == (4, 1, 4) and shape(f16, 384)[9] == 1      # 768 B = 3 whole steps of 256 B
+    assert shape(f16, 640)[:3] == (4, 1, 4) and shape(f16, 640)[4] == 5
+    assert shape(f16, 768)[:3] == (8, 1, 4) and shape(f16, 768)[9] == 1      # 1536 B = 3 whole steps of 512 B
+    assert shape(f32, 192)[:3] == (4, 1, 8) and shape(f32, 384)[:3] == (8, 1, 8)
+    assert shape(f16, 300)[:3] == (8, 1, 8) and shape(f16, 300)[4] == 2       # 600 B: 59 % of one 1 KiB step
+    assert shape(f16, 600)[:3] == (8, 1, 8) and shape(f16, 600)[4] == 3
+    assert shape(f16, 400)[:3] == (16, 1, 4)                                  # 800 B: 78 % of a 1 KiB step
+    assert shape(f16, 1030)[:3] == (16, 1, 4)                                 # over 2 KiB: P = 16
+    assert shape(f16, 512)[:3] == (16, 1, 4) and shape(f16, 1024)[:3] == (16, 1, 4) and shape(f16, 1536)[:3] == (16, 1, 4)
 
 
 def test_choice_between_kernels():
