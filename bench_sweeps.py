@@ -485,6 +485,48 @@ def rows(args, torch, np, B, W):
             measure(f, dtype, n // 256 - 1, 256, 256, 1, None, "default")
 
 
+def widths(args, torch, np, B, W):
+    """Batched form over a fine grid of row lengths (contiguous rows filling 512 MiB, library defaults):
+    shows which kernel shape each length gets and what it reaches."""
+    total_bytes = 1 << 29
+    host = torch.from_numpy(W.generate("normal", total_bytes // 2, 3).view(np.int16))
+    bufs = [host.cuda() for _ in range(4)]
+    timer = Timer(torch, B)
+    out = torch.zeros((1 << 24) + 8, dtype=torch.float32, device="cuda")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    byte_lengths = [32, 48, 64, 96, 128, 160, 192, 200, 256, 320, 384, 400, 512, 514, 520, 600, 700, 768, 800, 900, 1000, 1022,
+                    1024, 1028, 1040, 1200, 1280, 1400, 1434, 1536, 1600, 1800, 2000, 2048, 2060, 2200, 2560, 2800, 3000,
+                    3072, 3500, 4000, 4096, 4104, 4608, 5000, 6000, 6144, 7000, 8192, 8208, 10000, 12288, 14000, 16384, 20000, 32768]
+    with open_out(args, "widths.txt") as f:
+        emit(f, "# contiguous rows filling 512 MiB per call, 4 rotating buffers, library defaults; GB/s counts the input and the 4-byte results")
+        emit(f, "# type row_bytes cols rows kernel_shape steps_per_row us GB/s pct_of_8TB/s")
+        for name, dtype, esize in (("f16", B.MFR_DTYPE_F16, 2), ("f32", B.MFR_DTYPE_F32, 4)):
+            for nbytes in byte_lengths:
+                if nbytes % esize:
+                    continue
+                c = nbytes // esize
+                r = total_bytes // nbytes
+                if r + 8 > out.numel():
+                    continue
+
+                def call(i):
+                    B.mfr_sum_rows_ex(bufs[i % 4].data_ptr(), dtype, r, c, c, out.data_ptr(), None, timer.stream)
+                for i in range(5):
+                    call(i)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(args.steps):
+                    call(i)
+                e1.record()
+                torch.cuda.synchronize()
+                dt = e0.elapsed_time(e1) * 1e-3 / args.steps
+                gb = (esize * r * c + 4 * r) / dt / 1e9
+                plan = B.mfr_rows_plan(bufs[0].data_ptr(), dtype, r, c, c, cus)
+                shape = "per-row" if plan is None else "P%d_D%d_GF%d%s" % (plan[0], plan[1], plan[2], "" if plan[9] else "_masked")
+                emit(f, "%s %d %d %d %s %s %.2f %.1f %.1f" % (name, nbytes, c, r, shape, "-" if plan is None else plan[4], dt * 1e6, gb,
+                                                         100 * gb / HBM_PEAK_GBPS))
+
+
 def graph(args, torch, np, B, W):
     """Many small sums per submission: 64 independent calls issued one by one against the same 64 calls
     captured once into a HIP graph and replayed (the calls only launch kernels once a stream's scratch
@@ -541,4 +583,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants, "wide": wide, "combine": combine, "warm": warm, "graph": graph}[args.sweep](args, torch, np, B, W)
+    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants, "wide": wide, "combine": combine, "warm": warm, "graph": graph, "widths": widths}[args.sweep](args, torch, np, B, W)
