@@ -42,7 +42,8 @@ typedef enum mfr_status {
 enum {
     MFR_DTYPE_F16 = 0,  /* IEEE binary16: v_mfma_f32_16x16x32_f16, 8 values per lane per tile */
     MFR_DTYPE_BF16 = 1, /* bfloat16: v_mfma_f32_16x16x32_bf16 */
-    MFR_DTYPE_F32 = 2   /* IEEE binary32: four v_mfma_f32_16x16x4_f32 per tile, 4 values per lane */
+    MFR_DTYPE_F32 = 2   /* IEEE binary32: 4 values per lane per tile, added in the lane (fp32), then one
+                           v_mfma_f32_16x16x4_f32 adds the lanes' sums into the accumulator columns */
 };
 
 /* Which kernel computes the block partials. */
@@ -79,7 +80,7 @@ typedef struct mfr_tuning {
     int chain_R;          /* 1..8.  MFMA kernel: MFMAs accumulated into one accumulator tile
                              from zero before it is folded to an fp32 partial (the paper's R).
                              SHFL kernel: 16-byte loads per lane accumulated per group.
-                             Default: 3 (MFMA, SPLIT), 6 (SHFL), 8 for binary32 input */
+                             Default: 3 (MFMA, SPLIT; 7 for binary32 input), 6 (SHFL) */
     int grid_blocks;      /* MFR_GRID_AUTO, MFR_GRID_ONE_CHAIN, or an explicit count >= 1 */
     int kernel;           /* MFR_KERNEL_MFMA, MFR_KERNEL_SHFL or MFR_KERNEL_SPLIT */
     int chains_in_flight; /* 1, 2, 3, 4, 6 or 8 independent chains whose loads are issued before

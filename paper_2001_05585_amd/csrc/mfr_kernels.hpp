@@ -270,12 +270,11 @@ __device__ __forceinline__ float4v mma_ones(uint4v tile, float4v c)
         const bf16x8 ones = {one, one, one, one, one, one, one, one};
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, __builtin_bit_cast(bf16x8, tile), c, 0, 0, 0);
     } else {
-        // binary32: B is 4x16, one value per lane per MFMA; the lane's four values go to four MFMAs
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(tile.x), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(tile.y), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(tile.z), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(tile.w), c, 0, 0, 0);
-        return c;
+        // binary32: B is 4x16, one value per lane.  The lane adds its four values (fp32, as the
+        // accumulator would) and one MFMA adds the lanes' sums into the columns: a quarter of the
+        // matrix instructions for the same result up to rounding order.
+        const float lane_sum = (__uint_as_float(tile.x) + __uint_as_float(tile.y)) + (__uint_as_float(tile.z) + __uint_as_float(tile.w));
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, lane_sum, c, 0, 0, 0);
     }
 }
 
@@ -317,22 +316,7 @@ constexpr int KIND_MFMA_COLUMNS = 16;
 template <int KERNEL, int DT, int R>
 __device__ __forceinline__ float consume_chain(const uint4v (&v)[R])
 {
-    if constexpr ((KERNEL == MFR_KERNEL_MFMA || KERNEL == KIND_MFMA_COLUMNS) && DT == MFR_DTYPE_F32) {
-        // binary32: a lane's four values go to four MFMAs.  One accumulator per position keeps the
-        // four products of a slot independent of each other (a single accumulator makes 4 R MFMAs
-        // wait on one another); the four are added once at the end of the chain.
-        float4v c0 = {0.f, 0.f, 0.f, 0.f}, c1 = c0, c2 = c0, c3 = c0;          // C_0 = 0
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            c0 = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(v[r].x), c0, 0, 0, 0);
-            c1 = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(v[r].y), c1, 0, 0, 0);
-            c2 = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(v[r].z), c2, 0, 0, 0);
-            c3 = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, __uint_as_float(v[r].w), c3, 0, 0, 0);
-        }
-        const float columns = (c0.x + c1.x) + (c2.x + c3.x);
-        if constexpr (KERNEL == KIND_MFMA_COLUMNS) return columns;
-        else return row16_sum(columns);
-    } else if constexpr (KERNEL == MFR_KERNEL_MFMA || KERNEL == KIND_MFMA_COLUMNS) {
+    if constexpr (KERNEL == MFR_KERNEL_MFMA || KERNEL == KIND_MFMA_COLUMNS) {
         float4v acc = {0.f, 0.f, 0.f, 0.f};                 // C_0 = 0
 #pragma unroll
         for (int r = 0; r < R; ++r) acc = mma_ones<DT>(v[r], acc);

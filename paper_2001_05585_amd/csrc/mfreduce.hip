@@ -71,7 +71,7 @@ constexpr int kDefaultBlock = 256;
 // chip streams fastest: 75.7 us for 512 MiB against 77.2 us with eight KiB and 89 us with four.
 constexpr int kDefaultR = 3;
 constexpr int kDefaultR_shfl = 6;              // the conventional kernel: one group of six loads
-constexpr int kDefaultR_f32 = 8;               // four MFMAs per tile: one long chain overlaps them with the loads
+constexpr int kDefaultR_f32 = 7;               // binary32: one chain of seven tiles (75.9 us; two chains of three: 80 us)
 constexpr int kDefaultWavesPerCU = 4;          // one wave per SIMD
 constexpr long long kTicketMaxBlocks = 2048;   // AUTO: larger grids combine with a second launch
 constexpr long long kTicketHardMax = 65536;    // single-launch combine is not offered beyond this
@@ -160,7 +160,7 @@ int resolve_tuning(const mfr_tuning *in, int dtype, mfr_tuning *t)
         if (z.block_threads == 0) z.block_threads = g.block;
         if (z.chain_R == 0)
             z.chain_R = g.chain_R ? g.chain_R
-                        : (dtype == MFR_DTYPE_F32 ? kDefaultR_f32 : (z.kernel == MFR_KERNEL_SHFL ? kDefaultR_shfl : kDefaultR));
+                        : (z.kernel == MFR_KERNEL_SHFL ? kDefaultR_shfl : (dtype == MFR_DTYPE_F32 ? kDefaultR_f32 : kDefaultR));
     }
     if (!valid_block(z.block_threads)) return MFR_ERR_INVALID_ARG;
     if (z.block_threads == 32 && dtype != MFR_DTYPE_F16) return MFR_ERR_INVALID_ARG;
@@ -365,12 +365,11 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
             else if (row_bytes < 2048 && row_bytes * 100ull < covered * 72ull) lp = 3;
         }
         // Two steps are in flight per wave: 8 KiB with four groups, 16 KiB with eight.  Unmasked rows
-        // of 256 and 512 bytes of the 16-bit types do better with four (256-element rows 88 % against
-        // 84 %); shorter rows, masked rows (100-element rows 67 % against 78 %), rows read with 2-byte-aligned
-        // loads and binary32, whose
-        // MFMA phase is four times as long, with eight.
+        // made of 256- or 512-byte steps do better with four (256-element fp16 rows 88 % against 84 %);
+        // shorter rows, masked rows (100-element rows 67 % against 78 %) and rows read with
+        // 2-byte-aligned loads with eight.
         const bool whole_steps = row_bytes % (64ull << lp) == 0;
-        if (lp == 4 || (esize == 2u && lp >= 2 && whole_steps && !two_byte_phase)) gf = 4;
+        if (lp == 4 || (lp >= 2 && whole_steps && !two_byte_phase)) gf = 4;
     } else if (lp == 4 && rows >= kRowsTiledMinLongRows) {
         d = 4; gf = 1;
         // A step of four tiles leaves up to 4 KiB of its last step empty.  Rows that would waste

@@ -154,11 +154,11 @@ def test_shapes_reach_every_kernel_shape():
             plan = B.mfr_rows_plan((1 << 20) + shift * esize, dtype, rows, cols, stride, 256)
             assert plan is not None
             seen.add((plan[0], plan[1], plan[2], plan[9]))
-    for p, d, gf in ((1, 1, 8), (2, 1, 8), (4, 1, 8), (8, 1, 8), (16, 1, 4), (16, 4, 1)):
+    for p, d, gf in ((1, 1, 8), (2, 1, 8), (16, 1, 4), (16, 4, 1)):
         assert (p, d, gf, 0) in seen, (p, d, gf)
         assert (p, d, gf, 1) in seen, (p, d, gf)
-    # four groups side by side for unmasked 256- and 512-byte rows of the 16-bit types
-    assert (4, 1, 4, 1) in seen and (8, 1, 4, 1) in seen
+    # 256- and 512-byte steps: eight groups side by side when masked, four when not
+    assert (4, 1, 8, 0) in seen and (8, 1, 8, 0) in seen and (4, 1, 4, 1) in seen and (8, 1, 4, 1) in seen
 
 
 @pytest.mark.parametrize("dtype,kind", [(F16, "normal"), (F16, "uniform01"), (BF16, "normal"), (F32, "uniform_pm1")])

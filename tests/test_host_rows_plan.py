@@ -121,7 +121,7 @@ def test_rows_over_512_bytes_take_the_shape_that_wastes_least():
     assert shape(f16, 384)[:3] == (4, 1, 4) and shape(f16, 384)[9] == 1      # 768 B = 3 whole steps of 256 B
     assert shape(f16, 640)[:3] == (4, 1, 4) and shape(f16, 640)[4] == 5
     assert shape(f16, 768)[:3] == (8, 1, 4) and shape(f16, 768)[9] == 1      # 1536 B = 3 whole steps of 512 B
-    assert shape(f32, 192)[:3] == (4, 1, 8) and shape(f32, 384)[:3] == (8, 1, 8)
+    assert shape(f32, 192)[:3] == (4, 1, 4) and shape(f32, 384)[:3] == (8, 1, 4)
     assert shape(f16, 300)[:3] == (8, 1, 8) and shape(f16, 300)[4] == 2       # 600 B: 59 % of one 1 KiB step
     assert shape(f16, 600)[:3] == (8, 1, 8) and shape(f16, 600)[4] == 3
     assert shape(f16, 400)[:3] == (16, 1, 4)                                  # 800 B: 78 % of a 1 KiB step
