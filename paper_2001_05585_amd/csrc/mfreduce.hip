@@ -354,15 +354,15 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     int d = 1, gf = 8;
     if (rows >= kRowsTiledMinRows && row_bytes < kRowsTiledLongRowBytes) {
         // Rows over 512 bytes: a step of P = 16 is 1 KiB, and a row that ends early in its last step
-        // leaves the rest of that step's loads empty (520-byte rows ran at 48 % of the peak).  Rows
-        // that are whole steps of a narrower shape take that shape, unmasked (768-byte rows 89 %
-        // against 69 %); rows that fill less than 72 % of their 1 KiB steps take P = 8, whose steps
-        // are 512 bytes (600-byte rows 72 % against 55 %).
+        // leaves the rest of that step's loads empty.  Rows that are whole steps of a narrower shape
+        // take that shape, unmasked (768-byte rows 89 % against 69 %); rows under 2 KiB that fill
+        // less than 55 % of their 1 KiB steps (72 % when the loads are 2-byte aligned) take P = 8, whose
+        // steps are 512 bytes.
+        const unsigned long long covered = (row_bytes + 1023ull) / 1024ull * 1024ull;      // in 1 KiB steps
         if (row_bytes > 512 && row_bytes % 1024ull != 0) {
-            const unsigned long long covered = (row_bytes + 1023ull) / 1024ull * 1024ull;
             if (row_bytes % 512ull == 0) lp = 3;
             else if (row_bytes % 256ull == 0) lp = 2;
-            else if (row_bytes < 2048 && row_bytes * 100ull < covered * 72ull) lp = 3;
+            else if (row_bytes < 2048 && row_bytes * 100ull < covered * (two_byte_phase ? 72ull : 55ull)) lp = 3;
         }
         // Two steps are in flight per wave: 8 KiB with four groups, 16 KiB with eight.  Unmasked rows
         // made of 256- or 512-byte steps do better with four (256-element fp16 rows 88 % against 84 %);
@@ -370,6 +370,10 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
         // 2-byte-aligned loads with eight.
         const bool whole_steps = row_bytes % (64ull << lp) == 0;
         if (lp == 4 || (lp >= 2 && whole_steps && !two_byte_phase)) gf = 4;
+        // A masked last step of P = 16 carries fewer bytes than it has loads: when it is the only step,
+        // or when the row fills under 80 % of its steps, eight groups keep enough of them in flight
+        // (800-byte rows 87 % against 70 %, 2200-byte rows 78 % against 72 %).
+        if (lp == 4 && !whole_steps && (covered == 1024ull || row_bytes * 100ull < covered * 80ull)) gf = 8;
     } else if (lp == 4 && rows >= kRowsTiledMinLongRows) {
         d = 4; gf = 1;
         // A step of four tiles leaves up to 4 KiB of its last step empty.  Rows that would waste

@@ -280,6 +280,7 @@ hipError_t launch_rows_tiled_dt(const void *x, unsigned long long rows, unsigned
     case 218: return launch_cfg<DT, 2, 1, 8>(a, grid, s.all_plain, nt, stream);
     case 318: return launch_cfg<DT, 3, 1, 8>(a, grid, s.all_plain, nt, stream);
     case 414: return launch_cfg<DT, 4, 1, 4>(a, grid, s.all_plain, nt, stream);
+    case 418: return launch_cfg<DT, 4, 1, 8>(a, grid, s.all_plain, nt, stream);
     case 441: return launch_cfg<DT, 4, 4, 1>(a, grid, s.all_plain, nt, stream);
     default: return hipErrorInvalidValue;
     }

@@ -122,10 +122,13 @@ def test_rows_over_512_bytes_take_the_shape_that_wastes_least():
     assert shape(f16, 640)[:3] == (4, 1, 4) and shape(f16, 640)[4] == 5
     assert shape(f16, 768)[:3] == (8, 1, 4) and shape(f16, 768)[9] == 1      # 1536 B = 3 whole steps of 512 B
     assert shape(f32, 192)[:3] == (4, 1, 4) and shape(f32, 384)[:3] == (8, 1, 4)
-    assert shape(f16, 300)[:3] == (8, 1, 8) and shape(f16, 300)[4] == 2       # 600 B: 59 % of one 1 KiB step
-    assert shape(f16, 600)[:3] == (8, 1, 8) and shape(f16, 600)[4] == 3
-    assert shape(f16, 400)[:3] == (16, 1, 4)                                  # 800 B: 78 % of a 1 KiB step
-    assert shape(f16, 1030)[:3] == (16, 1, 4)                                 # over 2 KiB: P = 16
+    assert shape(f16, 260)[:3] == (8, 1, 8) and shape(f16, 260)[4] == 2       # 520 B: 51 % of one 1 KiB step
+    assert shape(f16, 520)[:3] == (8, 1, 8) and shape(f16, 520)[4] == 3
+    # a masked row of P = 16: eight groups when one step, or when under 80 % of the steps is filled
+    assert shape(f16, 300)[:3] == (16, 1, 8) and shape(f16, 400)[:3] == (16, 1, 8) and shape(f16, 511)[:3] == (16, 1, 8)
+    assert shape(f16, 800)[:3] == (16, 1, 8) and shape(f16, 1100)[:3] == (16, 1, 8)
+    assert shape(f16, 900)[:3] == (16, 1, 4) and shape(f16, 1000)[:3] == (16, 1, 4) and shape(f16, 2000)[:3] == (16, 1, 4)
+    assert shape(f16, 1030)[:3] == (16, 1, 8)                                 # over 2 KiB: P = 16
     assert shape(f16, 512)[:3] == (16, 1, 4) and shape(f16, 1024)[:3] == (16, 1, 4) and shape(f16, 1536)[:3] == (16, 1, 4)
 
 
