@@ -497,6 +497,7 @@ def widths(args, torch, np, B, W):
     byte_lengths = [32, 48, 64, 96, 128, 160, 192, 200, 256, 320, 384, 400, 512, 514, 520, 600, 700, 768, 800, 900, 1000, 1022,
                     1024, 1028, 1040, 1200, 1280, 1400, 1434, 1536, 1600, 1800, 2000, 2048, 2060, 2200, 2560, 2800, 3000,
                     3072, 3500, 4000, 4096, 4104, 4608, 5000, 6000, 6144, 7000, 8192, 8208, 10000, 12288, 14000, 16384, 20000, 32768]
+    heat(timer, bufs, total_bytes // 2, 0.5)         # fresh buffers start slow
     with open_out(args, "widths.txt") as f:
         emit(f, "# contiguous rows filling 512 MiB per call, 4 rotating buffers, library defaults; GB/s counts the input and the 4-byte results")
         emit(f, "# type row_bytes cols rows kernel_shape steps_per_row us GB/s pct_of_8TB/s")
@@ -511,7 +512,7 @@ def widths(args, torch, np, B, W):
 
                 def call(i):
                     B.mfr_sum_rows_ex(bufs[i % 4].data_ptr(), dtype, r, c, c, out.data_ptr(), None, timer.stream)
-                for i in range(5):
+                for i in range(20):
                     call(i)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
