@@ -253,3 +253,35 @@ def test_repeat_calls_are_bit_identical_and_streams_do_not_interfere():
         B.mfr_sum_rows_ex(inp.ptr, F16, rows, cols, stride, o2.ptr(0), None, s2.cuda_stream)
     torch.cuda.synchronize()
     assert np.array_equal(o1.get().view(np.uint32), first) and np.array_equal(o2.get().view(np.uint32), first)
+
+
+def test_batched_calls_can_be_captured_in_a_hip_graph():
+    # the many-rows kernel uses no scratch; the per-row kernels use the stream's scratch, which exists after
+    # one eager call: both kinds of call only launch kernels and can be captured and replayed
+    shapes = [(3000, 200, 208, 0), (40, 50000, 50001, 1), (1200, 9000, 9000, 0)]
+    s = torch.cuda.Stream()
+    inputs, outs, wants = [], [], []
+    for rows, cols, stride, shift in shapes:
+        vals = W.small_integers(rows * cols, seed=rows + cols, lo=-3, hi=3).astype(np.float32).reshape(rows, cols)
+        inputs.append(RowsInput(F16, encode(F16, vals).reshape(rows, cols), stride, shift))
+        outs.append(Outputs(rows + 1))
+        wants.append(vals.astype(np.float64).sum(axis=1))
+
+    def issue():
+        for (rows, cols, stride, _), inp, o in zip(shapes, inputs, outs):
+            B.mfr_sum_rows_ex(inp.ptr, F16, rows, cols, stride, o.ptr(0), None, s.cuda_stream)
+    with torch.cuda.stream(s):
+        issue()                                        # eager: allocates the stream's scratch
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        issue()
+    for rep in range(4):
+        for o in outs:
+            o.tensor.fill_(Outputs.SENTINEL)           # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        for (rows, _, _, _), o, want in zip(shapes, outs, wants):
+            r = o.get()
+            assert r[rows] == Outputs.SENTINEL
+            assert np.array_equal(r[:rows].astype(np.float64), want), (rep, rows)
