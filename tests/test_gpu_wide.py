@@ -134,3 +134,42 @@ def test_wide_argument_checks_and_zero():
     B.mfr_sum_f16_f64(d.ptr, 64, o.ptr(1), stream_handle())
     r = o.get()
     assert r[0] == 0.0 and r[1] == 64.0
+
+
+def test_variants_can_be_captured_in_a_hip_graph():
+    # the binary64-accumulation mode, the recurrence variant, the split kernel and the other element types
+    # only launch kernels once their stream's scratch exists: captured together and replayed
+    n = (1 << 21) + 77
+    x = W.small_integers(n, seed=77, lo=-2, hi=2)
+    want = float(x.astype(np.float64).sum())
+    d16 = DeviceInput(x, 1)
+    d32 = torch.from_numpy(x.astype(np.float32)).cuda()
+    xs = W.small_integers(1500, seed=78, lo=0, hi=2)                          # recurrence: totals under 2048 stay exact in fp16
+    small = DeviceInput(xs)
+    want_small = float(xs.astype(np.float64).sum())
+    assert want_small < 2048
+    o64 = Out64(1)
+    o32 = torch.full((4,), -1.0, dtype=torch.float32, device="cuda")
+    s = torch.cuda.Stream()
+
+    def issue():
+        B.mfr_sum_f16_f64(d16.ptr, n, o64.ptr(0), s.cuda_stream)
+        B.mfr_sum_f16_recurrence(small.ptr, 1500, o32.data_ptr(), 2, s.cuda_stream)
+        B.mfr_sum_f16_ex(d16.ptr, n, o32.data_ptr() + 4, B.make_tuning(256, 4, 0, B.MFR_KERNEL_SPLIT, 2, 0, 0, 400), s.cuda_stream)
+        B.mfr_sum_f32(d32.data_ptr(), n, o32.data_ptr() + 8, s.cuda_stream)
+        B.mfr_sum_f16_ex(d16.ptr, n, o32.data_ptr() + 12, B.make_tuning(64, 1, 5000, 0, 1, 0, B.MFR_COMBINE_TWO_LAUNCHES), s.cuda_stream)
+    with torch.cuda.stream(s):
+        issue()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        issue()
+    for rep in range(4):
+        o32.fill_(-1.0)
+        o64.tensor.fill_(-1.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert o64.get()[0] == want
+        r = o32.cpu().numpy().astype(np.float64)
+        assert r[0] == want_small and r[1] == want and r[2] == want and r[3] == want, (rep, r, want, want_small)
