@@ -279,7 +279,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic", action="store_true", help="short run for rocprofv3 --pmc counters")
     ap.add_argument("--traffic-rows", action="store_true", help="the same for the many-rows kernel")
-    ap.add_argument("--sweep", choices=["config2", "config5", "tune", "types", "rows", "tune_f32", "split", "variants", "wide", "combine", "warm", "graph", "widths"], default=None)
+    ap.add_argument("--sweep", choices=["config2", "config5", "types", "rows", "row_lengths", "split", "variants", "wide"], default=None)
     ap.add_argument("--quick", type=int, default=0, help="sweeps: keep every k-th combination")
     ap.add_argument("--out", default=None, help="file for sweep tables (default: <results folder>/<sweep>.txt)")
     args = ap.parse_args()

@@ -3,11 +3,14 @@
   config2  block x R cells at n = 2^26 uniform [0,1) (Section 5.2's B x R
            experiment, on this GPU), both grid modes, + all-ones 2^24 exactness
   config5  n = 2^16 .. 2^30 and each 2^k + 7, MFMA kernel and shuffle kernel
-  tune     geometry search at n = 2^28 (block, R, chains in flight, grid, load policy)
+  types    512 MiB of binary16 / bfloat16 / binary32 through both kernels
+  rows     batched form: rows x cols filling 512 MiB, and a walk over row lengths
+  split    Section 5.3's fraction experiment
+  variants Section 5.4's run time and error of the variants over n
+  wide     the binary64-accumulation mode beside the fp32 mode
 """
 from __future__ import annotations
 
-import itertools
 import os
 import sys
 import time
@@ -84,45 +87,6 @@ def heat(timer, bufs, n, seconds=1.0):
     t0 = time.perf_counter()
     while time.perf_counter() - t0 < seconds:
         timer.run(bufs, n, None, 50, 0)
-
-
-def tune(args, torch, np, B, W):
-    n = args.n
-    x = W.generate("normal", n, W.config_seed(3))
-    bufs = device_buffers(torch, np, x, args.buffers)
-    timer = Timer(torch, B)
-    heat(timer, bufs, n)
-    cus = torch.cuda.get_device_properties(0).multi_processor_count
-    rows = []
-    with open_out(args, "tune.txt") as f:
-        emit(f, "# n=%d buffers=%d CUs=%d ; columns: kernel block R U nt grid us GB/s pct" % (n, len(bufs), cus))
-        combos = []
-        for kernel in (0, 1):
-            for block in (64, 128, 256, 512, 1024):
-                for R, U in ((1, 1), (1, 2), (1, 3), (1, 4), (1, 6), (1, 8), (2, 1), (2, 2), (2, 3), (2, 4), (2, 6), (2, 8),
-                             (3, 1), (3, 2), (3, 3), (3, 4), (4, 1), (4, 2), (4, 3), (4, 4), (5, 1), (5, 2), (6, 1), (6, 2), (7, 1), (7, 2), (8, 1), (8, 2)):
-                    waves = block // 64
-                    if R * U * 1 < 2:
-                        continue
-                    for wpc in (1, 2, 4, 8, 16, 32):          # waves per CU
-                        if wpc % waves:
-                            continue
-                        grid = cus * wpc // waves
-                        for nt in (1, 2):
-                            combos.append((kernel, block, R, U, nt, grid))
-                    combos.append((kernel, block, R, U, 1, -1))
-        if args.quick:
-            combos = combos[::args.quick]
-        for (kernel, block, R, U, nt, grid) in combos:
-            t = B.make_tuning(block, R, grid, kernel, U, nt)
-            dt = timer.run(bufs, n, t, args.steps, 5)
-            gbps = 2 * n / dt / 1e9
-            rows.append((gbps, kernel, block, R, U, nt, grid, dt))
-            emit(f, "%d %4d %d %d %d %7d %8.2f %7.1f %5.1f" % (kernel, block, R, U, nt, grid, dt * 1e6, gbps, 100 * gbps / HBM_PEAK_GBPS))
-        rows.sort(reverse=True)
-        emit(f, "# best 25")
-        for (gbps, kernel, block, R, U, nt, grid, dt) in rows[:25]:
-            emit(f, "# %d %4d %d %d %d %7d %8.2f %7.1f %5.1f" % (kernel, block, R, U, nt, grid, dt * 1e6, gbps, 100 * gbps / HBM_PEAK_GBPS))
 
 
 def arena_pointers(base_ptr, arena_bytes, n, max_count=4096):
@@ -272,35 +236,6 @@ def types(args, torch, np, B, W):
             del bufs
 
 
-def tune_f32(args, torch, np, B, W):
-    """Geometry search for binary32 input (four MFMAs per tile)."""
-    n = 1 << 27
-    host = torch.from_numpy(W.generate_f32("normal", n, 3))
-    bufs = [host.cuda() for _ in range(4)]
-    timer = Timer(torch, B)
-    with open_out(args, "tune_f32.txt") as f:
-        emit(f, "# f32 n=2^27 (512 MiB); kernel block R U grid us GB/s pct")
-        for kernel in (0, 1):
-            for block in (256, 512, 1024):
-                for R, U in ((1, 2), (1, 4), (1, 8), (2, 1), (2, 2), (2, 4), (4, 1), (4, 2), (8, 1), (4, 4), (8, 2)):
-                    for grid in (256, 512, 1024):
-                        t = B.make_tuning(block, R, grid, kernel, U)
-
-                        def call(i):
-                            B.mfr_sum_ex(bufs[i % 4].data_ptr(), B.MFR_DTYPE_F32, n, timer.out.data_ptr(), t, timer.stream)
-                        for i in range(5):
-                            call(i)
-                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                        e0.record()
-                        for i in range(args.steps):
-                            call(i)
-                        e1.record()
-                        torch.cuda.synchronize()
-                        dt = e0.elapsed_time(e1) * 1e-3 / args.steps
-                        gb = 4 * n / dt / 1e9
-                        emit(f, "%d %d %d %d %d %.2f %.1f %.1f" % (kernel, block, R, U, grid, dt * 1e6, gb, 100 * gb / HBM_PEAK_GBPS))
-
-
 def split(args, torch, np, B, W):
     """Section 5.3's experiment: fraction of the domain through the MFMA path vs the conventional path."""
     timer = Timer(torch, B)
@@ -380,53 +315,6 @@ def wide(args, torch, np, B, W):
                                                                       100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS, float(out64[0].item())))
 
 
-def combine(args, torch, np, B, W):
-    """Single-launch (two-level tickets) against two-launch grid combine over the number of blocks."""
-    n = 1 << 28
-    x = W.generate("normal", n, W.config_seed(3))
-    bufs = device_buffers(torch, np, x, 4)
-    timer = Timer(torch, B)
-    heat(timer, bufs, n, 0.5)
-    with open_out(args, "combine.txt") as f:
-        emit(f, "# n=2^28, 4 rotating buffers; block grid(blocks) in_flight_KiB_per_wave single_launch_us two_launch_us")
-        for block in (64, 256):
-            for grid in (256, 512, 1024, 2048, 4096, 8192, 16384, 65536):
-                waves = grid * block // 64
-                per_wave = max(1, min(8, 8192 // waves))      # keep about 8 MiB in flight
-                R, U = (4, 2) if per_wave == 8 else ((4, 1) if per_wave == 4 else ((2, 1) if per_wave == 2 else (1, 1)))
-                res = []
-                for mode in (B.MFR_COMBINE_SINGLE_LAUNCH, B.MFR_COMBINE_TWO_LAUNCHES):
-                    t = B.make_tuning(block, R, grid, 0, U, 0, mode)
-                    res.append(timer.run(bufs, n, t, args.steps, 5) * 1e6)
-                emit(f, "%d %d %d %.2f %.2f" % (block, grid, R * U, res[0], res[1]))
-
-
-def warm(args, torch, np, B, W):
-    """Cache-resident inputs (one buffer re-read): load policy, kernel and geometry over n."""
-    timer = Timer(torch, B)
-    cus = torch.cuda.get_device_properties(0).multi_processor_count
-    with open_out(args, "warm.txt") as f:
-        emit(f, "# one buffer re-read back to back (resident in L2 / last-level cache when it fits); uniform[0,1)")
-        emit(f, "# n MiB kernel nt block R U grid us GB/s")
-        for k in (20, 22, 24, 25, 26, 27):
-            n = 1 << k
-            x = W.generate("uniform01", n, W.config_seed(5))
-            bufs = device_buffers(torch, np, x, 1)
-            rows_ = []
-            for kernel in (0, 1):
-                for nt in (1, 2):
-                    for block, R, U, wpc in ((256, 4, 2, 4), (256, 4, 2, 8), (256, 4, 2, 16), (256, 2, 2, 16), (256, 4, 1, 32),
-                                             (256, 2, 1, 32), (512, 4, 2, 8), (1024, 2, 2, 16), (256, 1, 1, 32), (256, 8, 2, 4)):
-                        grid = cus * wpc // (block // 64)
-                        t = B.make_tuning(block, R, grid, kernel, U, nt)
-                        dt = timer.run(bufs, n, t, args.steps, 10)
-                        rows_.append((dt, kernel, nt, block, R, U, grid))
-            rows_.sort()
-            for dt, kernel, nt, block, R, U, grid in rows_[:6] + [r for r in rows_ if r[1:] == (0, 2, 256, 4, 2, cus)]:
-                emit(f, "%d %.0f %d %d %d %d %d %d %.2f %.1f" % (n, 2 * n / 2 ** 20, kernel, nt, block, R, U, grid, dt * 1e6, 2 * n / dt / 1e9))
-            del bufs
-
-
 def rows(args, torch, np, B, W):
     """Batched form: rows x cols elements filling 512 MiB per call, 4 rotating buffers."""
     total_bytes = 1 << 29
@@ -485,7 +373,7 @@ def rows(args, torch, np, B, W):
             measure(f, dtype, n // 256 - 1, 256, 256, 1, None, "default")
 
 
-def widths(args, torch, np, B, W):
+def row_lengths(args, torch, np, B, W):
     """Batched form over a fine grid of row lengths (contiguous rows filling 512 MiB, library defaults):
     shows which kernel shape each length gets and what it reaches."""
     total_bytes = 1 << 29
@@ -498,7 +386,7 @@ def widths(args, torch, np, B, W):
                     1024, 1028, 1040, 1200, 1280, 1400, 1434, 1536, 1600, 1800, 2000, 2048, 2060, 2200, 2560, 2800, 3000,
                     3072, 3500, 4000, 4096, 4104, 4608, 5000, 6000, 6144, 7000, 8192, 8208, 10000, 12288, 14000, 16384, 20000, 32768]
     heat(timer, bufs, total_bytes // 2, 0.5)         # fresh buffers start slow
-    with open_out(args, "widths.txt") as f:
+    with open_out(args, "row_lengths.txt") as f:
         emit(f, "# contiguous rows filling 512 MiB per call, 4 rotating buffers, library defaults; GB/s counts the input and the 4-byte results")
         emit(f, "# type row_bytes cols rows kernel_shape steps_per_row us GB/s pct_of_8TB/s")
         for name, dtype, esize in (("f16", B.MFR_DTYPE_F16, 2), ("f32", B.MFR_DTYPE_F32, 4)):
@@ -528,53 +416,6 @@ def widths(args, torch, np, B, W):
                                                          100 * gb / HBM_PEAK_GBPS))
 
 
-def graph(args, torch, np, B, W):
-    """Many small sums per submission: 64 independent calls issued one by one against the same 64 calls
-    captured once into a HIP graph and replayed (the calls only launch kernels once a stream's scratch
-    exists, so they can be captured).  Each call has its own input and output; sizes where the launch
-    cost, not the memory, bounds the call."""
-    calls = 64
-    s = torch.cuda.Stream()
-    with open_out(args, "graph.txt") as f:
-        emit(f, "# %d sums per submission, one stream; us per sum; n  eager  graph  eager/graph  sums_exact" % calls)
-        for n in (1 << 10, 1 << 12, 1 << 14, 1 << 15, 49152, 1 << 16, 98304, 1 << 17, 196608, 1 << 18, 1 << 20, 1 << 22):
-            x = W.small_integers(n * calls, seed=n, lo=-2, hi=2)
-            dev = torch.from_numpy(x.view(np.int16)).cuda()
-            want = x.astype(np.float64).reshape(calls, n).sum(axis=1)
-            out = torch.zeros(calls, dtype=torch.float32, device="cuda")
-
-            def issue():
-                for i in range(calls):
-                    B.mfr_sum_f16(dev.data_ptr() + 2 * n * i, n, out.data_ptr() + 4 * i, s.cuda_stream)
-            with torch.cuda.stream(s):
-                issue()                                   # allocates the stream's scratch
-            torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=s):
-                issue()
-            reps = max(3, args.steps // 4)
-            times = []
-            for mode in ("eager", "graph"):
-                out.zero_()
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                with torch.cuda.stream(s):
-                    e0.record()
-                    for _ in range(reps):
-                        if mode == "eager":
-                            issue()
-                        else:
-                            g.replay()
-                    e1.record()
-                torch.cuda.synchronize()
-                times.append(e0.elapsed_time(e1) * 1e3 / (reps * calls))
-                exact = bool(np.array_equal(out.cpu().numpy().astype(np.float64), want))
-                if not exact:
-                    raise SystemExit("graph sweep: wrong sums in %s mode at n = %d" % (mode, n))
-            emit(f, "%d %.2f %.2f %.2f yes" % (n, times[0], times[1], times[0] / times[1]))
-            del g
-
-
 def run(args):
     import numpy as np
     import torch
@@ -584,4 +425,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"tune": tune, "config2": config2, "config5": config5, "types": types, "rows": rows, "tune_f32": tune_f32, "split": split, "variants": variants, "wide": wide, "combine": combine, "warm": warm, "graph": graph, "widths": widths}[args.sweep](args, torch, np, B, W)
+    {"config2": config2, "config5": config5, "types": types, "rows": rows, "row_lengths": row_lengths, "split": split, "variants": variants, "wide": wide}[args.sweep](args, torch, np, B, W)

@@ -14,7 +14,6 @@ and never imports it.
 * ``mma_model``         fp64 model of the ones-matrix MMA encoding (Section 4.1,
                         4.3) used to pin the encoding identities.
 * ``recurrence_model``  the recurrence variant with its binary16 partials (Section 5.1).
-* ``cost_model``        the paper's running-time and speedup formulas (Sections 4.2, 4.3).
 """
 from __future__ import annotations
 

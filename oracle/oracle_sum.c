@@ -9,8 +9,8 @@
  * The ones-matrix MMA encoding (Section 4.1, eqs. MMA1/MMA2; Section 4.3, the
  * chained form C_r = 1 x M_r + C_{r-1}) is a re-association of this same sum,
  * not an approximation of it, so the oracle is the plain definition evaluated
- * serially (Section 4: sequential additions on one accumulator) in binary64
- * ("CPU reduction using double precision", Section 5.4), strengthened with
+ * serially (the one-accumulator algorithm of Section 4) in binary64 (the
+ * precision of the CPU reference in Section 5.4), strengthened with
  * Kahan compensation so that its own rounding error is far below one fp32 ulp
  * of the result.
  *
@@ -152,8 +152,9 @@ void oracle_sum_f32(const uint32_t *x, size_t n, double *sum, double *sum_abs)
     neumaier_sum_typed(x, n, ORACLE_F32, sum, sum_abs);
 }
 
-/* Uncompensated serial binary64 sum: literally the paper's CPU comparison
- * ("sequential additions on a single accumulator", double precision). */
+/* Uncompensated serial binary64 sum with one running total: the serial
+ * algorithm of Section 4 in double precision, which is the CPU comparison of
+ * Section 5.4. */
 void oracle_sum_f16_naive(const uint16_t *x, size_t n, double *sum)
 {
     double s = 0.0;
