@@ -35,7 +35,8 @@ typedef enum mfr_status {
     MFR_OK = 0,
     MFR_ERR_INVALID_ARG = 1, /* null pointer, misaligned x, bad block / R / grid / kernel */
     MFR_ERR_UNSUPPORTED = 2, /* current device is not gfx950 */
-    MFR_ERR_HIP = 3          /* a HIP runtime call failed; text via mfr_last_hip_error() */
+    MFR_ERR_HIP = 3,         /* a HIP runtime call failed; text via mfr_last_hip_error() */
+    MFR_ERR_SCRATCH_LIMIT = 4 /* mfr_sum_f16_noalloc only: the grid needs more scratch than the fixed region holds */
 } mfr_status;
 
 /* Element types.  binary16 is the paper's; the other two run the same kernels. */
@@ -109,19 +110,27 @@ typedef struct mfr_tuning {
  * Asynchronous: returns after enqueueing; synchronise the stream before
  * reading *out.  Same (x contents, n, tuning, device) => bit-identical *out:
  * block partials are combined in index order, never with float atomics.
+ * Precision: every chain is accumulated and folded in fp32 (32 chain_R + 4
+ * dependent additions); the chains of a wave, the waves of a block and the
+ * blocks of the grid are added in binary64, with one rounding to fp32 per block
+ * partial and one for the result, so the error bound does not depend on how
+ * many chains a wave runs (i.e. not on grid_blocks).  The conventional kernel
+ * adds the 8 * chain_R values of a lane's group in fp32 and is otherwise alike.
  * IEEE special values propagate (NaN in => NaN; +Inf and -Inf => NaN);
  * subnormal inputs contribute their value (not flushed), for every type.
- * Scratch (block partials + a ticket counter) is owned by the library, one
- * per (device, stream), allocated on first use and kept until unload; calls
- * on different streams may overlap, calls on one stream serialise.  A call
- * that has to allocate or enlarge its stream's scratch calls hipMalloc (and
- * synchronises the stream before freeing a smaller one); later calls with a
+ * Scratch (block partials + ticket counters) is owned by the library, one per
+ * (device, stream), allocated on first use and kept until mfr_release_scratch
+ * or unload; calls on different streams may overlap, calls on one stream
+ * serialise on the device (host threads may share a stream).  A call whose
+ * grid needs more scratch than its stream holds calls hipMalloc for a buffer
+ * of at least twice the size; the smaller buffer is kept, not freed, because
+ * work that was enqueued or captured earlier still refers to it.  Calls with a
  * grid no larger than before allocate nothing, only launch kernels (no memset
  * nodes), and can therefore be captured into a HIP graph and replayed.
  * A captured call keeps the scratch addresses of the stream it was captured
  * on: replays of such a graph must not overlap with each other or with other
- * calls on that stream, and that stream's scratch must not be released or
- * enlarged (by a later call with a larger grid) while the graph is in use.
+ * calls on that stream, and that stream's scratch must not be released while
+ * the graph is in use.
  * With library defaults an array of at most 32 chains (49152 binary16 values)
  * is summed by a single block, which needs no scratch at all.
  */
@@ -268,6 +277,22 @@ int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *t, unsigne
  */
 int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row_stride, int cus,
                   unsigned long long plan[11]);
+
+/*
+ * Host replay of the ticket counting of the single-launch grid combine
+ * (inspection only, no device access): `blocks` blocks draw their tickets in
+ * the order order[0], order[1], ... (a permutation of 0 .. blocks - 1) from
+ * `counters` (counters_len words, all zero on entry), with one flat counter
+ * (flat != 0) or two levels (groups of 32 blocks, then one top counter), through
+ * the same function the kernels use with the device's atomic increment.
+ * Returns the number of draws that were told "every block has drawn" -- 1 for
+ * a correct count, and only the last draw may be the one -- or -100 if an
+ * earlier draw was told so, or a negative status on invalid arguments.  On
+ * return the counters hold what the next call would find (zeros, if the count
+ * is right: every counter wraps when its last ticket is drawn).
+ */
+int mfr_ticket_replay(unsigned int blocks, int flat, const unsigned int *order, unsigned int *counters,
+                      size_t counters_len);
 
 /*
  * Frees the scratch that calls on `stream` of the current device have left

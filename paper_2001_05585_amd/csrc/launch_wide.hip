@@ -68,7 +68,8 @@ __global__ void __launch_bounds__(1024) sum_kernel_wide(const SumArgs a)
         if (threadIdx.x == 0) partials[blockIdx.x] = block_sum;
         return;
     }
-    // same publication order as the fp32 kernel: returning exchange, then the ticket
+    // same publication order as the fp32 kernel: returning exchange, then the ticket; the reader
+    // fences (acquire, device scope) before it loads the partials
     if (threadIdx.x == 0) {
         unsigned long long prev = __hip_atomic_exchange((unsigned long long *)&partials[blockIdx.x],
                                                         (unsigned long long)__double_as_longlong(block_sum),
@@ -78,6 +79,7 @@ __global__ void __launch_bounds__(1024) sum_kernel_wide(const SumArgs a)
     }
     __syncthreads();
     if (!is_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     const double total = block_sum_of_doubles(partials, gridDim.x, combine_lds);
     if (threadIdx.x == 0) *out = total;
 }

@@ -21,8 +21,18 @@
 // yields the same total, so the layout is chosen for coalescing alone.
 //
 // Element types: binary16 (the paper's), bfloat16 and binary32.  A tile is one
-// 16x16x32 MFMA for the 16-bit types (8 values per lane) and four 16x16x4
-// MFMAs for binary32 (4 values per lane, one per MFMA).
+// 16x16x32 MFMA for the 16-bit types (8 values per lane).  For binary32 (4
+// values per lane) the lane first adds its four values in fp32 and one
+// 16x16x4 MFMA per tile adds the lanes' sums into the accumulator columns, so
+// three of every four additions of that type are vector-ALU additions.
+//
+// Precision.  Inside a chain everything is fp32, as in the paper: the MFMA
+// accumulator, and the fold of its 16 column sums to the chain's fp32 result.
+// A wave adds its chains' fp32 results into a binary64 running sum, and the
+// block and grid combines stay in binary64 until the one rounding to fp32 per
+// block partial and the one of the final result.  The number of dependent fp32
+// additions therefore does not grow with the number of chains a wave runs
+// (which a caller-chosen small grid can make very large).
 #ifndef MFR_KERNELS_HPP
 #define MFR_KERNELS_HPP
 
@@ -38,6 +48,13 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxWavesPerBlock = 16;
+
+// Type of a wave's running sum over its chains' fp32 results.
+#ifdef MFR_WAVE_ACC_F32
+typedef float WaveAcc;
+#else
+typedef double WaveAcc;
+#endif
 
 struct SumArgs {
     const uint4v *base;          // slot 0 (of row 0): x rounded down to 16 bytes
@@ -193,6 +210,10 @@ __device__ __forceinline__ double wave64_sum_f64(double v)
     return v;
 }
 
+// The same for either running-sum type (the conventional path's per-lane sums).
+__device__ __forceinline__ float wave64_sum_acc(float v) { return wave64_sum(v); }
+__device__ __forceinline__ double wave64_sum_acc(double v) { return wave64_sum_f64(v); }
+
 // All threads of one block: sum of partials[0..count) in binary64, fixed order
 // (thread t takes t, t + blockDim, ... with four running sums, then lanes, then
 // waves).  Loads are device-scope atomic loads so that values published by
@@ -238,19 +259,32 @@ inline unsigned long long ticket_words(unsigned int blocks, bool flat)
     return (unsigned long long)kTicketStride * (1u + (blocks + kTicketGroup - 1u) / kTicketGroup);
 }
 
-__device__ __forceinline__ bool draw_ticket(unsigned int *tickets, unsigned int block, unsigned int blocks, bool flat)
+// `inc(p, wrap)` is atomicInc: returns *p and stores *p >= wrap ? 0 : *p + 1.  The kernels pass the
+// device atomic; the host passes a plain replay of it to check the counting (mfr_ticket_replay).
+template <typename Inc>
+__host__ __device__ inline bool draw_ticket_with(Inc inc, unsigned int *tickets, unsigned int block, unsigned int blocks,
+                                                 bool flat)
 {
-    if (flat) return atomicInc(tickets, blocks - 1u) == blocks - 1u;
+    if (flat) return inc(tickets, blocks - 1u) == blocks - 1u;
     const unsigned int groups = (blocks + kTicketGroup - 1u) / kTicketGroup;
     const unsigned int g = block / kTicketGroup;
     const unsigned int first = g * kTicketGroup;
     const unsigned int size = blocks - first < kTicketGroup ? blocks - first : kTicketGroup;
     if (size > 1u) {
-        const unsigned int old = atomicInc(tickets + kTicketStride * (1u + g), size - 1u);
+        const unsigned int old = inc(tickets + kTicketStride * (1u + g), size - 1u);
         if (old != size - 1u) return false;
     }
     if (groups == 1u) return true;
-    return atomicInc(tickets, groups - 1u) == groups - 1u;
+    return inc(tickets, groups - 1u) == groups - 1u;
+}
+
+struct DeviceAtomicInc {
+    __device__ unsigned int operator()(unsigned int *p, unsigned int wrap) const { return atomicInc(p, wrap); }
+};
+
+__device__ __forceinline__ bool draw_ticket(unsigned int *tickets, unsigned int block, unsigned int blocks, bool flat)
+{
+    return draw_ticket_with(DeviceAtomicInc(), tickets, block, blocks, flat);
 }
 
 // ------------------------------------------------------ tile consumers ---
@@ -425,31 +459,34 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
         }
     }
 
-    float partial;                       // the wave's fp32 partial, uniform
+    // Level 1: the wave's running sum over the fp32 results of its chains.  MFMA path: uniform over
+    // the wave.  Conventional path: one running sum per lane, added up across the wave at the end.
+    WaveAcc partial;
     if constexpr (KERNEL == MFR_KERNEL_MFMA) {
-        partial = stream_chains<MFR_KERNEL_MFMA, DT, R, U, NT, HALF>(a, base, x, lane, w, a.chains, W, w == W - 1);
+        partial = stream_chains<MFR_KERNEL_MFMA, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, w, a.chains, W, w == W - 1);
     } else if constexpr (KERNEL == MFR_KERNEL_SHFL) {
-        partial = wave64_sum(stream_chains<MFR_KERNEL_SHFL, DT, R, U, NT, HALF>(a, base, x, lane, w, a.chains, W, w == W - 1));
+        partial = wave64_sum_acc(stream_chains<MFR_KERNEL_SHFL, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, w, a.chains, W, w == W - 1));
     } else {
         const unsigned long long W1 = a.split_waves, C1 = a.split_chains;
         if (w < W1) {
-            partial = stream_chains<MFR_KERNEL_MFMA, DT, R, U, NT, HALF>(a, base, x, lane, w, C1, W1, w == W - 1);
+            partial = stream_chains<MFR_KERNEL_MFMA, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, w, C1, W1, w == W - 1);
         } else {
-            partial = wave64_sum(stream_chains<MFR_KERNEL_SHFL, DT, R, U, NT, HALF>(a, base, x, lane, C1 + (w - W1),
-                                                                                  a.chains, W - W1, w == W - 1));
+            partial = wave64_sum_acc(stream_chains<MFR_KERNEL_SHFL, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, C1 + (w - W1),
+                                                                                               a.chains, W - W1, w == W - 1));
         }
     }
 
-    // Level 2: one value per block from its wave partials.
-    __shared__ float wave_partials[kMaxWavesPerBlock];
+    // Level 2: one value per block from its wave partials, added in wave order, rounded to fp32 once.
+    __shared__ WaveAcc wave_partials[kMaxWavesPerBlock];
     __shared__ double wave_partials_f64[kMaxWavesPerBlock];
     __shared__ unsigned int is_last;
     if (lane == 0) wave_partials[wave] = partial;
     __syncthreads();
     float block_sum = 0.f;
-    if (wave == 0) {
-        const float t = lane < wpb ? wave_partials[lane] : 0.f;
-        block_sum = row16_sum(t);      // wpb <= 16: all partials sit in row 0
+    if (threadIdx.x == 0) {
+        WaveAcc t = wave_partials[0];
+        for (unsigned int i = 1; i < wpb; ++i) t += wave_partials[i];
+        block_sum = (float)t;
     }
 
     // Level 3: all block partials of the row to one value, in index order.
@@ -464,25 +501,28 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
         if (threadIdx.x == 0) partials[blockIdx.x] = block_sum;
         return;
     }
-    // Single-launch combine.  A release fence at device scope costs a write-back
-    // of the whole L2 per block, so ordering is obtained from the atomics
-    // themselves: the partial is published with a returning device-scope
-    // exchange, and a ticket is drawn only after that exchange has returned,
-    // i.e. after it has been performed at the device's coherence point.
-    // The block that draws the last ticket therefore finds every partial of
-    // the row published.  All counters wrap to zero by themselves, ready for
-    // the next call.
+    // Single-launch combine.  The block partial is not written with a store that a later release
+    // would have to make visible (a release fence at device scope costs a write-back of the whole
+    // L2 per block): it is the payload of a device-scope atomic exchange, performed at the device's
+    // coherence point like the ticket itself.  The exchange returns its old value; the ticket is
+    // drawn only after that value has arrived, i.e. after the exchange has been performed, so in
+    // the order of operations at the coherence point every block's exchange precedes its ticket.
+    // The block that draws the last ticket sees every ticket drawn, hence every exchange performed;
+    // it then executes a device-scope acquire fence (dropping what its own caches may hold of the
+    // partials array) and reads the partials with device-scope atomic loads.  All counters wrap to
+    // zero by themselves, ready for the next call.
     if (threadIdx.x == 0) {
         unsigned int prev = __hip_atomic_exchange((unsigned int *)&partials[blockIdx.x],
                                                   __float_as_uint(block_sum), __ATOMIC_RELAXED,
                                                   __HIP_MEMORY_SCOPE_AGENT);
-        // the exchange result must be in a register (waits for it) and no later
-        // memory operation may be moved above this point
+        // the exchange result must be in a register (the wave waits for it) and the compiler may
+        // move no later memory operation above this point
         asm volatile("" : "+v"(prev) : : "memory");
         is_last = draw_ticket(a.ticket + row * a.ticket_stride, blockIdx.x, gridDim.x, a.ticket_flat != 0u) ? 1u : 0u;
     }
     __syncthreads();
     if (!is_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     const double total = block_sum_f64(partials, gridDim.x, wave_partials_f64);
     if (threadIdx.x == 0) *out = (float)total;
 }

@@ -10,6 +10,7 @@
 #include <map>
 #include <mutex>
 #include <utility>
+#include <vector>
 
 #include "mfr_kernels.hpp"
 
@@ -60,6 +61,10 @@ struct Scratch {
     size_t tickets_capacity = 0;    // counters, all zero between calls
     unsigned short *levels = nullptr;   // recurrence variant: the binary16 partials of two levels
     size_t levels_capacity = 0;
+    // Buffers that a larger one has replaced.  A call copies the current pointers under the mutex
+    // and launches after dropping it, and work already enqueued (or captured into a graph) keeps
+    // the addresses it was given, so a replaced buffer is kept until mfr_release_scratch.
+    std::vector<void *> retired;
 };
 
 std::mutex g_mutex;
@@ -278,38 +283,51 @@ bool ticket_flat_for(long long grid, const Plan &p)
     return grid <= 512 && per_wave >= 32;
 }
 
-int grow(void **mem, size_t *capacity, size_t need, size_t elem, size_t floor_count, bool zero, hipStream_t stream)
+// Capacity doubles until it covers `need`.  The buffer that is outgrown is not freed here (see
+// Scratch::retired): all retired buffers of a stream together are smaller than its current one.
+int grow(void **mem, size_t *capacity, size_t need, size_t elem, size_t floor_count, bool zero,
+         std::vector<void *> *retired)
 {
     if (*capacity >= need) return MFR_OK;
     size_t cap = *capacity ? *capacity : floor_count;
     while (cap < need) cap *= 2;
-    if (*mem) {
-        // earlier calls on this stream may still be using the old buffer
-        MFR_HIP(hipStreamSynchronize(stream));
-        MFR_HIP(hipFree(*mem));
-        *mem = nullptr;
-        *capacity = 0;
-    }
     void *fresh = nullptr;
     MFR_HIP(hipMalloc(&fresh, cap * elem));
     if (zero) {
         const hipError_t e = hipMemset(fresh, 0, cap * elem);
         if (e != hipSuccess) { (void)hipFree(fresh); return hip_fail(e, "hipMemset(scratch)"); }
+        // the fill runs on the null stream; the caller's stream need not wait for that stream by itself
+        const hipError_t e2 = hipStreamSynchronize(nullptr);
+        if (e2 != hipSuccess) { (void)hipFree(fresh); return hip_fail(e2, "hipStreamSynchronize(scratch fill)"); }
     }
+    if (*mem) retired->push_back(*mem);
     *mem = fresh;
     *capacity = cap;
     return MFR_OK;
 }
 
-int get_scratch(int dev, hipStream_t stream, size_t partials, size_t tickets, Scratch *out)
+// Where a call's block partials and ticket counters live: the stream's library-owned buffers
+// (allocated or enlarged here if need be), or a fixed region that the caller of sum_rows_impl
+// hands in and that is never enlarged.
+struct ScratchView {
+    float *partials = nullptr;
+    size_t partials_capacity = 0;
+    unsigned int *tickets = nullptr;
+    size_t tickets_capacity = 0;
+};
+
+int get_scratch(int dev, hipStream_t stream, size_t partials, size_t tickets, ScratchView *out)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
     Scratch &s = g_scratch[std::make_pair(dev, stream)];
-    int st = grow((void **)&s.partials, &s.partials_capacity, partials, sizeof(float), 4096, false, stream);
+    int st = grow((void **)&s.partials, &s.partials_capacity, partials, sizeof(float), 4096, false, &s.retired);
     if (st != MFR_OK) return st;
-    st = grow((void **)&s.tickets, &s.tickets_capacity, tickets, sizeof(unsigned int), 1024, true, stream);
+    st = grow((void **)&s.tickets, &s.tickets_capacity, tickets, sizeof(unsigned int), 1024, true, &s.retired);
     if (st != MFR_OK) return st;
-    *out = s;
+    out->partials = s.partials;
+    out->partials_capacity = s.partials_capacity;
+    out->tickets = s.tickets;
+    out->tickets_capacity = s.tickets_capacity;
     return MFR_OK;
 }
 
@@ -422,8 +440,12 @@ int fill_zero(float *out, size_t count, hipStream_t stream)
 }
 
 // rows sums of cols elements each; consecutive rows are row_stride elements apart.
+// `fixed`: if not null, the block partials and tickets live there and nothing is allocated; a call
+// that needs more than it holds fails with MFR_ERR_SCRATCH_LIMIT.  `per_row_only`: skip the
+// many-rows kernel although tin is null.
 int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row_stride, float *out,
-                  const mfr_tuning *tin, hipStream_t stream)
+                  const mfr_tuning *tin, hipStream_t stream, const ScratchView *fixed = nullptr,
+                  bool per_row_only = false)
 {
     mfr_tuning t;
     const int st = resolve_tuning(tin, dtype, &t);
@@ -451,7 +473,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
 
     // Many rows: tiles shared out among rows, one launch for any alignment and stride.
-    if (tin == nullptr) {
+    if (tin == nullptr && !per_row_only) {
         mfr::RowsTiledShape shape;
         unsigned grid = 0;
         if (plan_rows_tiled((size_t)x, esize, rows, cols, row_stride, info.cus, &shape, &grid)) {
@@ -461,12 +483,11 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
                 : dtype == MFR_DTYPE_BF16 ? mfr::launch_rows_tiled_bf16(x, rows, cols, row_stride, out, shape, grid, nt, stream)
                                           : mfr::launch_rows_tiled_f32(x, rows, cols, row_stride, out, shape, grid, nt, stream);
             if (e != hipSuccess) return hip_fail(e, "rows_tiled launch");
-            // the few rows at the end whose last 16-byte slot would reach past the array: one by one
-            for (size_t r = shape.row_hi; r < rows; ++r) {
-                const int se = sum_rows_impl((const char *)x + r * row_stride * esize, dtype, 1, cols, cols, out + r,
-                                             nullptr, stream);
-                if (se != MFR_OK) return se;
-            }
+            // the few rows at the end whose last 16-byte slot would reach past the array: one more
+            // launch, of the per-row kernels, which read nothing outside a row
+            if (shape.row_hi < rows)
+                return sum_rows_impl((const char *)x + shape.row_hi * row_stride * esize, dtype, rows - shape.row_hi, cols,
+                                     row_stride, out + shape.row_hi, nullptr, stream, fixed, true);
             return MFR_OK;
         }
     }
@@ -492,11 +513,17 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
     const bool ticket_flat = ticket_flat_for(grid, p);
-    Scratch s;
+    ScratchView s;
     if (grid > 1) {
         const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid, ticket_flat) * batch;
-        const int ss = get_scratch(dev, stream, (size_t)grid * batch, ticket_words, &s);
-        if (ss != MFR_OK) return ss;
+        if (fixed) {
+            if ((size_t)grid * batch > fixed->partials_capacity || ticket_words > fixed->tickets_capacity)
+                return MFR_ERR_SCRATCH_LIMIT;
+            s = *fixed;
+        } else {
+            const int ss = get_scratch(dev, stream, (size_t)grid * batch, ticket_words, &s);
+            if (ss != MFR_OK) return ss;
+        }
     }
 
     for (size_t r0 = 0; r0 < rows; r0 += batch) {
@@ -558,7 +585,7 @@ int recurrence_impl(const mfr_half *x, size_t n, float *out, int R, hipStream_t 
         std::lock_guard<std::mutex> lock(g_mutex);
         Scratch &s = g_scratch[std::make_pair(dev, stream)];
         const int st = grow((void **)&s.levels, &s.levels_capacity, first_padded + second + 8, sizeof(unsigned short),
-                            4096, false, stream);
+                            4096, false, &s.retired);
         if (st != MFR_OK) return st;
         levels = s.levels;
     }
@@ -622,7 +649,7 @@ int sum_wide_impl(const mfr_half *x, size_t n, double *out, const mfr_tuning *ti
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
     const bool ticket_flat = ticket_flat_for(grid, p);
-    Scratch s;
+    ScratchView s;
     if (grid > 1) {
         const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid, ticket_flat);
         const int ss = get_scratch(dev, stream, 2 * (size_t)grid + 2, ticket_words, &s);   // doubles live in the float array
@@ -791,6 +818,30 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
     return 1;
 }
 
+int mfr_ticket_replay(unsigned int blocks, int flat, const unsigned int *order, unsigned int *counters,
+                      size_t counters_len)
+{
+    if (blocks < 1 || !order || !counters) return -MFR_ERR_INVALID_ARG;
+    if (counters_len < mfr::ticket_words(blocks, flat != 0)) return -MFR_ERR_INVALID_ARG;
+    struct SerialInc {
+        unsigned int operator()(unsigned int *p, unsigned int wrap) const
+        {
+            const unsigned int old = *p;
+            *p = old >= wrap ? 0u : old + 1u;
+            return old;
+        }
+    };
+    int winners = 0;
+    for (unsigned int i = 0; i < blocks; ++i) {
+        if (order[i] >= blocks) return -MFR_ERR_INVALID_ARG;
+        if (mfr::draw_ticket_with(SerialInc(), counters, order[i], blocks, flat != 0)) {
+            if (i != blocks - 1u) return -100;      // somebody was told "last" before everybody had drawn
+            ++winners;
+        }
+    }
+    return winners;
+}
+
 int mfr_release_scratch(hipStream_t stream)
 {
     int dev = 0;
@@ -801,7 +852,11 @@ int mfr_release_scratch(hipStream_t stream)
     MFR_HIP(hipStreamSynchronize(stream));       // earlier calls on the stream may still be using it
     Scratch &s = it->second;
     hipError_t first = hipSuccess;
-    for (void *mem : {(void *)s.partials, (void *)s.tickets, (void *)s.levels}) {
+    std::vector<void *> all = s.retired;
+    all.push_back(s.partials);
+    all.push_back(s.tickets);
+    all.push_back(s.levels);
+    for (void *mem : all) {
         if (!mem) continue;
         const hipError_t e = hipFree(mem);
         if (e != hipSuccess && first == hipSuccess) first = e;
@@ -818,12 +873,13 @@ const char *mfr_strerror(int status)
     case MFR_ERR_INVALID_ARG: return "invalid argument";
     case MFR_ERR_UNSUPPORTED: return "unsupported device (gfx950 required)";
     case MFR_ERR_HIP: return "HIP runtime error";
+    case MFR_ERR_SCRATCH_LIMIT: return "the call needs more scratch than the fixed scratch region holds";
     default: return "unknown status";
     }
 }
 
 const char *mfr_last_hip_error(void) { return g_hip_error; }
 
-int mfr_version(void) { return 400; }
+int mfr_version(void) { return 500; }
 
 }  // extern "C"

@@ -350,6 +350,62 @@ def test_alternating_inputs_never_see_the_previous_calls_partials():
             assert np.all(r[0::2] == float(n)) and np.all(r[1::2] == 3.0 * n), (block, R, grid, combine)
 
 
+@pytest.mark.parametrize("kernel", [B.MFR_KERNEL_MFMA, B.MFR_KERNEL_SHFL])
+def test_tiny_explicit_grids_on_long_real_inputs_stay_in_tolerance(kernel, oracle_lib):
+    """One to three blocks on 2^24 and more values: a wave then runs thousands of chains.  Their fp32
+    results are added in binary64, so the error does not grow with that count; uniform [0,1) inputs are
+    the hard case for a running sum (every addition rounds, all in the same direction class)."""
+    for n, kind in ((1 << 24, "uniform01"), ((1 << 25) + 77, "uniform01"), (1 << 24, "normal")):
+        x = W.generate(kind, n, 4242 + n % 13)
+        s, sa = oracle_lib.sum_f16(x)
+        d = DeviceInput(x, 3)
+        cells = [(64, 1, 1, 1), (256, 3, 1, 0), (64, 8, 2, 0), (1024, 2, 3, 0), (128, 5, 1, 0)]
+        o = Outputs(len(cells))
+        for i, (block, R, grid, U) in enumerate(cells):
+            B.mfr_sum_f16_ex(d.ptr, n, o.ptr(i), B.make_tuning(block, R, grid, kernel, U), stream_handle())
+        r = o.get().astype(np.float64)
+        worst = float(np.max(np.abs(r - s))) / sa
+        print("grid 1-3, kernel %d, %s n=%d: worst |err|/sum|x| = %.3g" % (kernel, kind, n, worst))
+        assert worst <= TOL, (kernel, kind, n, r, s)
+        assert worst <= 2e-6      # far inside the gate: (32 R + 8 R + 6) 2^-24 at most, in practice 1e-8
+
+
+def test_host_threads_sharing_one_stream_while_the_scratch_grows(oracle_lib):
+    """Several host threads enqueue on the same stream, with grids that keep outgrowing the stream's
+    scratch.  A buffer that is outgrown stays allocated (work enqueued earlier still uses it), so
+    every result is right whatever the interleaving."""
+    import threading
+    n = (1 << 20) + 24
+    x = W.small_integers(n, seed=5, lo=-2, hi=2)
+    want = float(x.astype(np.float64).sum())
+    d = DeviceInput(x)
+    s = torch.cuda.Stream()
+    B.mfr_release_scratch(s.cuda_stream)
+    grids = [3, 9, 40, 300, 1500, 5000, 9000, 20000, 40000, 65536]
+    threads, per_thread = 4, len(grids) * 6
+    o = Outputs(threads * per_thread)
+    errors = []
+
+    def work(tid):
+        try:
+            for j in range(per_thread):
+                grid = grids[(j + tid) % len(grids)]
+                t = B.make_tuning(64, 1, grid, 0, 1, 0, B.MFR_COMBINE_SINGLE_LAUNCH if j % 2 else B.MFR_COMBINE_AUTO)
+                B.mfr_sum_f16_ex(d.ptr, n, o.ptr(tid * per_thread + j), t, s.cuda_stream)
+        except Exception as e:      # noqa: BLE001
+            errors.append(e)
+
+    ts = [threading.Thread(target=work, args=(i,)) for i in range(threads)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    s.synchronize()
+    assert not errors, errors
+    assert np.all(o.get() == want)
+    B.mfr_release_scratch(s.cuda_stream)
+
+
 def test_single_launch_combine_with_65536_blocks():
     n = 1 << 25
     d = DeviceInput(W.ones(n))

@@ -90,6 +90,8 @@ INT_CASES = [
     (700, 2500, 2504, 0), (513, 3501, 3504, 6),                                      # long rows from 512 rows on
     (2048, 384, 384, 0), (2048, 640, 648, 0), (2050, 768, 768, 4), (3000, 600, 600, 0), (2048, 350, 353, 1),
     (2048, 300, 300, 0), (2049, 192, 192, 0),                                        # rows over 512 bytes in narrower shapes
+    (2048, 257, 257, 0), (2048, 514, 514, 0), (2048, 1030, 1030, 0), (2048, 260, 260, 0),   # whole steps and a few bytes
+    (1100, 257, 257, 1), (1100, 129, 129, 0), (1027, 515, 515, 0),
 ]
 
 # few rows whose 16-byte phases differ: the per-row kernels, every block doing the slot arithmetic of its own row
@@ -285,3 +287,36 @@ def test_batched_calls_can_be_captured_in_a_hip_graph():
             r = o.get()
             assert r[rows] == Outputs.SENTINEL
             assert np.array_equal(r[:rows].astype(np.float64), want), (rep, rows)
+
+
+def test_tail_rows_after_the_many_rows_kernel_are_summed_in_one_more_launch(oracle_lib):
+    """Contiguous rows whose last 16-byte slot would reach past the array's end are left to the
+    per-row kernels (one launch for all of them); their sums and the rows before them are exact."""
+    for dtype in (F16, F32):
+        for rows, cols, shift in ((3000, 33, 0), (3000, 1, 3), (2048, 257, 0), (1500, 515, 1), (1200, 1021, 0)):
+            rng = np.random.default_rng(rows + cols)
+            vals = rng.integers(-3, 4, size=(rows, cols)).astype(np.float32)
+            inp = RowsInput(dtype, encode(dtype, vals).reshape(rows, cols), cols, shift)
+            plan = B.mfr_rows_plan(inp.ptr, dtype, rows, cols, cols, cus())
+            assert plan is not None and plan[8] < rows, (dtype, rows, cols, plan)      # there are tail rows
+            got = call(dtype, inp, rows, cols, cols)
+            assert np.array_equal(got.astype(np.float64), vals.astype(np.float64).sum(axis=1)), (dtype, rows, cols, shift)
+
+
+def test_alternating_inputs_never_see_the_previous_calls_partials_per_row_kernels():
+    """The per-row kernels of a batched call share one scratch array (gridDim.x partials per row) and
+    ticket counters per row across calls: two inputs with different exact row sums alternate on one stream."""
+    rows, cols = 24, (1 << 17) + 40
+    a = RowsInput(F16, encode(F16, np.ones((rows, cols), np.float32)).reshape(rows, cols), cols, 0)
+    b = RowsInput(F16, encode(F16, np.full((rows, cols), 3.0, np.float32)).reshape(rows, cols), cols + 8, 1)
+    for block, R, grid, combine in ((256, 3, 0, 1), (64, 2, 40, 1), (128, 1, 9, 2), (64, 1, 700, 1)):
+        t = B.make_tuning(block, R, grid, 0, 0, 0, combine)
+        calls = 400
+        o = Outputs(rows * calls)
+        for i in range(calls):
+            if i % 2 == 0:
+                B.mfr_sum_rows_ex(a.ptr, F16, rows, cols, cols, o.ptr(rows * i), t, stream_handle())
+            else:
+                B.mfr_sum_rows_ex(b.ptr, F16, rows, cols, cols + 8, o.ptr(rows * i), t, stream_handle())
+        r = o.get().reshape(calls, rows)
+        assert np.all(r[0::2] == float(cols)) and np.all(r[1::2] == 3.0 * cols), (block, R, grid, combine)

@@ -173,3 +173,20 @@ def test_variants_can_be_captured_in_a_hip_graph():
         assert o64.get()[0] == want
         r = o32.cpu().numpy().astype(np.float64)
         assert r[0] == want_small and r[1] == want and r[2] == want and r[3] == want, (rep, r, want, want_small)
+
+
+def test_alternating_inputs_never_see_the_previous_calls_partials():
+    """The binary64 kernel publishes its block partials the way the fp32 kernel does (returning
+    exchange, ticket, acquire, atomic loads) into scratch that every call on the stream reuses: two
+    inputs with different exact sums alternate on one stream, in both combine modes."""
+    n = (1 << 22) + 640
+    a, b = DeviceInput(W.ones(n)), DeviceInput(W.constant(n, 3.0), 1)
+    for block, R, grid in ((256, 1, 256), (128, 2, 700), (64, 1, 2048), (64, 1, 8192)):
+        for combine in (B.MFR_COMBINE_SINGLE_LAUNCH, B.MFR_COMBINE_TWO_LAUNCHES):
+            t = B.make_tuning(block, R, grid, 0, 0, 0, combine)
+            o = Out64(1000)
+            for i in range(1000):
+                d = a if i % 2 == 0 else b
+                B.mfr_sum_f16_f64_ex(d.ptr, n, o.ptr(i), t, stream_handle())
+            r = o.get()
+            assert np.all(r[0::2] == float(n)) and np.all(r[1::2] == 3.0 * n), (block, R, grid, combine)
