@@ -129,11 +129,16 @@ def cpu_baseline(x, n, gpu_value, budget_s=25.0):
     return res
 
 
-def measured_traffic():
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if recorded."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_sum_2p28.json")
+TRAFFIC_RECORD = os.path.join("profiles", "hbm_traffic_sum_2p28.json")
+
+
+def measured_traffic(n, tuning_is_default):
+    """HBM bytes per launch from the recorded rocprofv3 --pmc runs (FETCH_SIZE / WRITE_SIZE) of this
+    workload; None for any other size or geometry.  Counters cannot be read from inside this run."""
+    if n != 1 << 28 or not tuning_is_default:
+        return None
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, TRAFFIC_RECORD)) as f:
             return json.load(f).get("bytes_per_launch")
     except (OSError, ValueError):
         return None
@@ -153,11 +158,16 @@ def headline(args):
     kind, cfg = ("normal", 3)
     log("generating %s n=%d ..." % (kind, n))
     x = W.generate(kind, n, W.config_seed(cfg))
-    bufs = make_buffers(torch, np, x, args.buffers)
+    # enough distinct copies that the 256 MB last-level cache cannot serve the reads: 2 GiB in rotation
+    copies = args.buffers if args.buffers > 0 else max(4, min(1024, (1 << 31) // max(2 * n, 1)))
+    bufs = make_buffers(torch, np, x, copies)
     out = torch.zeros(4, dtype=torch.float32, device="cuda")
     tuning = B.make_tuning(args.block, args.R, args.grid, args.kernel, args.in_flight, args.nontemporal, args.combine)
-    grid = B.mfr_grid_for(n, bufs[0].data_ptr(), tuning)
-    log("timing: block=%d R=%d grid=%d kernel=%d ..." % (tuning.block_threads, tuning.chain_R, grid, tuning.kernel))
+    tuning_is_default = not any((args.block, args.R, args.grid, args.kernel, args.in_flight, args.nontemporal, args.combine))
+    grid = B.mfr_grid_for(n, bufs[0].data_ptr(), None if tuning_is_default else tuning)
+    if tuning_is_default:
+        tuning = None              # the library's own choices, exactly as mfr_sum_f16 makes them
+    log("timing: block=%d R=%d grid=%d kernel=%d, %d buffers ..." % (args.block, args.R, grid, args.kernel, copies))
     # Freshly allocated buffers run 3-10 % slow for their first few hundred calls: a quarter of a second
     # of untimed calls before the warm-up steps, so that short runs measure the sustained rate too.
     settle(torch, B, bufs, n, out, tuning, PREHEAT_S)
@@ -177,10 +187,11 @@ def headline(args):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "config 3: sum of n=2^28 fp16 values i.i.d. normal(0,1), fp32 result; "
-                               "%d distinct 512 MiB buffers rotated" % len(bufs),
-                   "n": n, "input_dtype": "f16", "kernel": "mfma_chain" if tuning.kernel == 0 else "shfl_tree",
-                   "block_threads": tuning.block_threads or b, "chain_R": tuning.chain_R or r,
+        "config": {"workload": "%s: sum of n=%d fp16 values i.i.d. normal(0,1), fp32 result; "
+                               "%d distinct %.4g MiB buffers rotated" % ("config 3" if n == 1 << 28 else "config 3's distribution at another size",
+                                                                        n, len(bufs), 2 * n / 2 ** 20),
+                   "n": n, "input_dtype": "f16", "kernel": ("mfma_chain", "shfl_tree", "split")[args.kernel],
+                   "block_threads": args.block or b, "chain_R": args.R or r,
                    "grid_blocks": grid, "buffers": len(bufs), "untimed_preheat_s": PREHEAT_S},
         "hbm_gbps": round(achieved, 1), "pct_hbm_peak": round(100 * achieved / HBM_PEAK_GBPS, 2),
         "per_call_us": {"median": round(statistics.median(calls) * 1e6, 2), "min": round(min(calls) * 1e6, 2)},
@@ -189,7 +200,9 @@ def headline(args):
                           "note": "one buffer re-read; part of it is served by the last-level cache"},
         "paper_context": "paper reports ~3.2x over a conventional GPU reduction on Nvidia tensor-core hardware",
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(),
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(n, tuning_is_default),
+                     "traffic_source": ("recorded rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE runs of this workload (%s), "
+                                        "not measured in this run" % TRAFFIC_RECORD) if measured_traffic(n, tuning_is_default) is not None else None,
                      "kernel": "sum_kernel", "bytes_per_launch": nbytes,
                      "launch_us": round(launch_s * 1e6, 3)},
     }
@@ -268,7 +281,7 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--n", type=int, default=1 << 28)
-    ap.add_argument("--buffers", type=int, default=4)
+    ap.add_argument("--buffers", type=int, default=0, help="distinct input copies in rotation (0: 2 GiB worth, at least 4)")
     ap.add_argument("--block", type=int, default=0)
     ap.add_argument("--R", type=int, default=0)
     ap.add_argument("--grid", type=int, default=0)

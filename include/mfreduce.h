@@ -121,7 +121,9 @@ typedef struct mfr_tuning {
  * Scratch (block partials + ticket counters) is owned by the library, one per
  * (device, stream), allocated on first use and kept until mfr_release_scratch
  * or unload; calls on different streams may overlap, calls on one stream
- * serialise on the device (host threads may share a stream).  A call whose
+ * serialise on the device.  Host threads may share a stream: the launches of
+ * one call are enqueued under a per-stream mutex, so they stay together.  A
+ * call whose
  * grid needs more scratch than its stream holds calls hipMalloc for a buffer
  * of at least twice the size; the smaller buffer is kept, not freed, because
  * work that was enqueued or captured earlier still refers to it.  Calls with a

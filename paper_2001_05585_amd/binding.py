@@ -13,7 +13,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmfreduce.so")
 
-MFR_OK, MFR_ERR_INVALID_ARG, MFR_ERR_UNSUPPORTED, MFR_ERR_HIP = 0, 1, 2, 3
+MFR_OK, MFR_ERR_INVALID_ARG, MFR_ERR_UNSUPPORTED, MFR_ERR_HIP, MFR_ERR_SCRATCH_LIMIT = 0, 1, 2, 3, 4
 MFR_KERNEL_MFMA, MFR_KERNEL_SHFL, MFR_KERNEL_SPLIT = 0, 1, 2
 MFR_GRID_AUTO, MFR_GRID_ONE_CHAIN = 0, -1
 MFR_COMBINE_AUTO, MFR_COMBINE_SINGLE_LAUNCH, MFR_COMBINE_TWO_LAUNCHES = 0, 1, 2

@@ -65,6 +65,11 @@ struct Scratch {
     // and launches after dropping it, and work already enqueued (or captured into a graph) keeps
     // the addresses it was given, so a replaced buffer is kept until mfr_release_scratch.
     std::vector<void *> retired;
+    // Held by a call from before it reads the pointers above until its last launch is enqueued: the
+    // launches of one call (sum kernel + combine kernel, the levels of the recurrence) then sit next
+    // to each other in the stream even when several host threads enqueue on it, so no other call's
+    // kernel can overwrite the scratch between them.
+    std::mutex launch_mutex;
 };
 
 std::mutex g_mutex;
@@ -314,12 +319,21 @@ struct ScratchView {
     size_t partials_capacity = 0;
     unsigned int *tickets = nullptr;
     size_t tickets_capacity = 0;
+    std::mutex *launch_mutex = nullptr;     // fixed regions: the mutex that keeps one call's launches together
 };
 
-int get_scratch(int dev, hipStream_t stream, size_t partials, size_t tickets, ScratchView *out)
+// Locks the stream's launch mutex into *launch_lock (the caller keeps it until its last launch).
+int get_scratch(int dev, hipStream_t stream, size_t partials, size_t tickets, ScratchView *out,
+                std::unique_lock<std::mutex> *launch_lock)
 {
+    Scratch *entry = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        entry = &g_scratch[std::make_pair(dev, stream)];      // map nodes do not move
+    }
+    *launch_lock = std::unique_lock<std::mutex>(entry->launch_mutex);
     std::lock_guard<std::mutex> lock(g_mutex);
-    Scratch &s = g_scratch[std::make_pair(dev, stream)];
+    Scratch &s = *entry;
     int st = grow((void **)&s.partials, &s.partials_capacity, partials, sizeof(float), 4096, false, &s.retired);
     if (st != MFR_OK) return st;
     st = grow((void **)&s.tickets, &s.tickets_capacity, tickets, sizeof(unsigned int), 1024, true, &s.retired);
@@ -514,14 +528,16 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
                               (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
     const bool ticket_flat = ticket_flat_for(grid, p);
     ScratchView s;
+    std::unique_lock<std::mutex> launch_lock;      // released when this call has enqueued its last kernel
     if (grid > 1) {
         const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid, ticket_flat) * batch;
         if (fixed) {
             if ((size_t)grid * batch > fixed->partials_capacity || ticket_words > fixed->tickets_capacity)
                 return MFR_ERR_SCRATCH_LIMIT;
             s = *fixed;
+            launch_lock = std::unique_lock<std::mutex>(*fixed->launch_mutex);
         } else {
-            const int ss = get_scratch(dev, stream, (size_t)grid * batch, ticket_words, &s);
+            const int ss = get_scratch(dev, stream, (size_t)grid * batch, ticket_words, &s, &launch_lock);
             if (ss != MFR_OK) return ss;
         }
     }
@@ -581,9 +597,16 @@ int recurrence_impl(const mfr_half *x, size_t n, float *out, int R, hipStream_t 
     const size_t second = (first + group - 1) / group + 1;
     const size_t first_padded = (first + 7) / 8 * 8;            // keeps the second buffer 16-byte aligned
     unsigned short *levels = nullptr;
+    std::unique_lock<std::mutex> launch_lock;      // the levels of one call stay together in the stream
     {
+        Scratch *entry = nullptr;
+        {
+            std::lock_guard<std::mutex> lock(g_mutex);
+            entry = &g_scratch[std::make_pair(dev, stream)];
+        }
+        launch_lock = std::unique_lock<std::mutex>(entry->launch_mutex);
         std::lock_guard<std::mutex> lock(g_mutex);
-        Scratch &s = g_scratch[std::make_pair(dev, stream)];
+        Scratch &s = *entry;
         const int st = grow((void **)&s.levels, &s.levels_capacity, first_padded + second + 8, sizeof(unsigned short),
                             4096, false, &s.retired);
         if (st != MFR_OK) return st;
@@ -650,9 +673,10 @@ int sum_wide_impl(const mfr_half *x, size_t n, double *out, const mfr_tuning *ti
                               (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
     const bool ticket_flat = ticket_flat_for(grid, p);
     ScratchView s;
+    std::unique_lock<std::mutex> launch_lock;
     if (grid > 1) {
         const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid, ticket_flat);
-        const int ss = get_scratch(dev, stream, 2 * (size_t)grid + 2, ticket_words, &s);   // doubles live in the float array
+        const int ss = get_scratch(dev, stream, 2 * (size_t)grid + 2, ticket_words, &s, &launch_lock);   // doubles live in the float array
         if (ss != MFR_OK) return ss;
     }
     p.a.base = (const uint4v *)((size_t)x & ~(size_t)15);

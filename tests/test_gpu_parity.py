@@ -372,8 +372,10 @@ def test_tiny_explicit_grids_on_long_real_inputs_stay_in_tolerance(kernel, oracl
 
 def test_host_threads_sharing_one_stream_while_the_scratch_grows(oracle_lib):
     """Several host threads enqueue on the same stream, with grids that keep outgrowing the stream's
-    scratch.  A buffer that is outgrown stays allocated (work enqueued earlier still uses it), so
-    every result is right whatever the interleaving."""
+    scratch, half of them with the two-launch combine.  A buffer that is outgrown stays allocated
+    (work enqueued earlier still uses it) and the launches of one call are enqueued under the stream's
+    launch mutex (no other call's kernel gets between a sum kernel and its combine kernel), so every
+    result is right whatever the interleaving."""
     import threading
     n = (1 << 20) + 24
     x = W.small_integers(n, seed=5, lo=-2, hi=2)
@@ -402,7 +404,8 @@ def test_host_threads_sharing_one_stream_while_the_scratch_grows(oracle_lib):
         t.join()
     s.synchronize()
     assert not errors, errors
-    assert np.all(o.get() == want)
+    r = o.get()
+    assert np.all(r == want), [(int(i), float(r[i])) for i in np.nonzero(r != want)[0][:10]]
     B.mfr_release_scratch(s.cuda_stream)
 
 
