@@ -152,6 +152,27 @@ int mfr_sum_f16_ex(const mfr_half *x, size_t n, float *out,
                    const mfr_tuning *t, hipStream_t stream);
 
 /*
+ * mfr_sum_f16_ex for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same result,
+ * bit for bit, as mfr_sum_f16_ex with the same arguments, but the block
+ * partials and ticket counters live in a fixed 64 KiB array in device memory
+ * that is part of the library's code object (every GPU the library runs on
+ * holds its own copy from load to process exit), so the call never calls
+ * hipMalloc, hipFree or any allocating routine, on any call, the first
+ * included.
+ *   Limit: grids of at most 8192 blocks (and ticket counters for them); a
+ *   tuning that asks for more -- MFR_GRID_ONE_CHAIN on a long input, a large
+ *   explicit grid_blocks -- returns MFR_ERR_SCRATCH_LIMIT and enqueues
+ *   nothing.  The library defaults (t == NULL) need 256 partials at most.
+ *   All calls of this entry point on one GPU share that array, whatever their
+ *   stream: calls that overlap in time on one GPU race on it and give wrong
+ *   results; calls on one stream, or otherwise ordered, are safe.  The array
+ *   needs no clearing: partials are written before they are read within a
+ *   call, and every ticket counter is back at zero when a call completes.
+ */
+int mfr_sum_f16_noalloc(const mfr_half *x, size_t n, float *out, const mfr_tuning *t, hipStream_t stream);
+
+/*
  * The same reduction (Section 4: R(X) = sum x_i, Section 5.2 single pass) for
  * other element types; x must be aligned to its element size.  block_threads
  * == 32 is accepted for binary16 only.  chain_R counts tiles (1 KiB loads per

@@ -695,6 +695,37 @@ int sum_impl(const void *x, int dtype, size_t n, float *out, const mfr_tuning *t
     return sum_rows_impl(x, dtype, 1, n, n, out, tin, stream);
 }
 
+// Scratch of the entry point that allocates nothing: block partials, then ticket counters, in a
+// device array that every GPU the library runs on holds from the load of the code object to the
+// end of the process.  Zero when loaded; the partials need no initial value and the counters wrap
+// back to zero at the end of every call.
+constexpr size_t kStaticPartials = 8192;       // floats: grids of up to this many blocks
+constexpr size_t kStaticTickets = 8192;        // counters: covers two-level tickets of such a grid
+static __device__ __align__(256) unsigned char scratch[(kStaticPartials + kStaticTickets) * 4];
+
+// The array's address on each device.  `scratch` itself is a host-side handle, not a device
+// address: only what hipGetSymbolAddress returns for the current device may reach a kernel.
+unsigned char *g_static_scratch[64];
+std::mutex g_static_launch_mutex[64];      // one call's launches stay together (host threads sharing a stream)
+
+int static_scratch(int dev, ScratchView *out)
+{
+    if (dev < 0 || dev >= 64) return MFR_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (!g_static_scratch[dev]) {
+        void *ptr = nullptr;
+        MFR_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));     // for the current device, which is `dev`
+        if (!ptr) return hip_fail(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+        g_static_scratch[dev] = (unsigned char *)ptr;
+    }
+    out->partials = (float *)g_static_scratch[dev];
+    out->partials_capacity = kStaticPartials;
+    out->tickets = (unsigned int *)(g_static_scratch[dev] + kStaticPartials * sizeof(float));
+    out->tickets_capacity = kStaticTickets;
+    out->launch_mutex = &g_static_launch_mutex[dev];
+    return MFR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -721,6 +752,21 @@ int mfr_sum_f16_tuned(const mfr_half *x, size_t n, float *out, int block_threads
 int mfr_sum_f16_ex(const mfr_half *x, size_t n, float *out, const mfr_tuning *t, hipStream_t stream)
 {
     return sum_impl(x, MFR_DTYPE_F16, n, out, t, stream);
+}
+
+int mfr_sum_f16_noalloc(const mfr_half *x, size_t n, float *out, const mfr_tuning *t, hipStream_t stream)
+{
+    // argument errors first, as everywhere: they do not depend on a device being present
+    mfr_tuning resolved;
+    const int st = resolve_tuning(t, MFR_DTYPE_F16, &resolved);
+    if (st != MFR_OK) return st;
+    if (!out || (n > 0 && !x) || ((size_t)x & 1u) != 0) return MFR_ERR_INVALID_ARG;
+    int dev = 0;
+    MFR_HIP(hipGetDevice(&dev));
+    ScratchView fixed;
+    const int ss = static_scratch(dev, &fixed);
+    if (ss != MFR_OK) return ss;
+    return sum_rows_impl(x, MFR_DTYPE_F16, 1, n, n, out, t, stream, &fixed);
 }
 
 int mfr_sum_bf16(const uint16_t *x, size_t n, float *out, hipStream_t stream)
