@@ -50,6 +50,20 @@ class Timer:
         return float(self.out[0].item())
 
 
+def oracle_reference(x):
+    """(sum, sum of |x|) of the fp16 array x from the CPU oracle, blocked over the host cores: the
+    checking leg of the sweeps (every timed cell is also compared with it); nothing else here uses
+    the oracle."""
+    import oracle
+    s, sa, _ = oracle.sum_f16_blocked(x, min(os.cpu_count() or 1, 16))
+    return s, sa
+
+
+def rel_err(value, ref):
+    s, sa = ref
+    return abs(float(value) - s) / sa if sa else 0.0
+
+
 def load_context():
     """ctypes handle of the hipCUB comparison library, or None if it has not been built."""
     import ctypes
@@ -119,11 +133,13 @@ def config2(args, torch, np, B, W):
     ptrs = [b.data_ptr() for b in bufs]
     ones = torch.ones(1 << 24, dtype=torch.float16, device="cuda")
     timer = Timer(torch, B)
+    ref = oracle_reference(x)
     heat(timer, bufs, n)
     with open_out(args, "config2.txt") as f:
         emit(f, "# config 2: n=%d uniform[0,1), MFMA-chain kernel; rotating %d x %.3f MiB buffers (cold) and one buffer (warm, cache-resident)" % (n, copies, 2 * n / 2 ** 20))
         emit(f, "# grid: persistent = MFR_GRID_AUTO, one-chain = one chain of R MFMAs per wave (the paper's geometry)")
-        emit(f, "# block R grid_mode blocks cold_us cold_Gelem/s cold_GB/s cold_pct warm_us warm_GB/s ones_2p24")
+        emit(f, "# err/sum|x| = |gpu - oracle| / sum|x_i| of the timed cell's result against the fp64 Kahan oracle (gate: 1e-5)")
+        emit(f, "# block R grid_mode blocks cold_us cold_Gelem/s cold_GB/s cold_pct warm_us warm_GB/s err/sum|x| ones_2p24")
         for grid_mode, gname in ((B.MFR_GRID_AUTO, "persistent"), (B.MFR_GRID_ONE_CHAIN, "one-chain")):
             for block in (32, 64, 128, 256, 512, 1024):
                 for R in range(1, 9):
@@ -131,12 +147,15 @@ def config2(args, torch, np, B, W):
                     steps = args.steps if grid_mode == B.MFR_GRID_AUTO else max(5, args.steps // 4)
                     cold = time_rotating(timer, ptrs, n, t, steps, 3)
                     warm = time_rotating(timer, ptrs[:1], n, t, steps, 3)
+                    err = rel_err(timer.result(), ref)
+                    if not err <= 1e-5:
+                        raise SystemExit("config2: block %d R %d %s: |err|/sum|x| = %g" % (block, R, gname, err))
                     B.mfr_sum_f16_ex(ones.data_ptr(), 1 << 24, timer.out.data_ptr(), t, timer.stream)
                     exact = "exact" if timer.result() == 16777216.0 else "WRONG(%r)" % timer.result()
                     label = "32(wave64,half-filled)" if block == 32 else str(block)
-                    emit(f, "%s %d %s %d %.2f %.1f %.1f %.1f %.2f %.1f %s" % (
+                    emit(f, "%s %d %s %d %.2f %.1f %.1f %.1f %.2f %.1f %.2e %s" % (
                         label, R, gname, B.mfr_grid_for(n, ptrs[0], t), cold * 1e6, n / cold / 1e9,
-                        2 * n / cold / 1e9, 100 * 2 * n / cold / 1e9 / HBM_PEAK_GBPS, warm * 1e6, 2 * n / warm / 1e9, exact))
+                        2 * n / cold / 1e9, 100 * 2 * n / cold / 1e9 / HBM_PEAK_GBPS, warm * 1e6, 2 * n / warm / 1e9, err, exact))
 
 
 def config5(args, torch, np, B, W):
@@ -151,16 +170,23 @@ def config5(args, torch, np, B, W):
     with open_out(args, "config5.txt") as f:
         emit(f, "# config 5: uniform[0,1); inputs rotate through a 2 GiB arena (distinct addresses per call) so that")
         emit(f, "# sizes below the last-level cache capacity are not served from cache; default tuning per kernel")
-        emit(f, "# n kernel blocks us Gelem/s GB/s pct_of_8TB/s")
+        emit(f, "# err/sum|x| = |gpu - oracle| / sum|x_i| against the fp64 Kahan oracle on the first of the rotating slices (gate: 1e-5);")
+        emit(f, "# mfma_chain = the library's default entry (t == NULL), shfl_tree = the conventional kernel with default tuning")
+        emit(f, "# n kernel blocks us Gelem/s GB/s pct_of_8TB/s err/sum|x|")
         for k in range(16, 31):
             for n in (1 << k, (1 << k) + 7):
                 ptrs = arena_pointers(arena.data_ptr(), arena_bytes, n)
+                ref = oracle_reference(x[:n])
                 for kernel, kname in ((B.MFR_KERNEL_MFMA, "mfma_chain"), (B.MFR_KERNEL_SHFL, "shfl_tree")):
-                    t = B.make_tuning(kernel=kernel)
+                    t = None if kernel == B.MFR_KERNEL_MFMA else B.make_tuning(kernel=kernel)
                     steps = max(10, min(args.steps * 4, int(2e-2 / max(2 * n / 6e12, 4e-6))))
                     dt = time_rotating(timer, ptrs, n, t, steps, 5)
-                    emit(f, "%d %s %d %.2f %.2f %.1f %.2f" % (n, kname, B.mfr_grid_for(n, ptrs[0], t), dt * 1e6,
-                                                            n / dt / 1e9, 2 * n / dt / 1e9, 100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS))
+                    B.mfr_sum_f16_ex(ptrs[0], n, timer.out.data_ptr(), t, timer.stream)
+                    err = rel_err(timer.result(), ref)
+                    if not err <= 1e-5:
+                        raise SystemExit("config5: n %d %s: |err|/sum|x| = %g" % (n, kname, err))
+                    emit(f, "%d %s %d %.2f %.2f %.1f %.2f %.2e" % (n, kname, B.mfr_grid_for(n, ptrs[0], t), dt * 1e6,
+                                                                 n / dt / 1e9, 2 * n / dt / 1e9, 100 * 2 * n / dt / 1e9 / HBM_PEAK_GBPS, err))
                 # context only: PyTorch's own reduction (fp32 accumulation) on the same rotating slices
                 halves = arena.view(torch.float16)
                 stride_e = (ptrs[1] - ptrs[0]) // 2 if len(ptrs) > 1 else 0
@@ -213,7 +239,9 @@ def types(args, torch, np, B, W):
             else:
                 host = torch.from_numpy(W.generate_f32("normal", n, 3))
             bufs = [host.cuda() for _ in range(4)]
-            for kernel, kname in ((B.MFR_KERNEL_MFMA, "mfma_chain"), (B.MFR_KERNEL_SHFL, "shfl_tree")):
+            # binary32: three of four additions are vector-ALU adds in the lane, one MFMA per tile adds the lanes
+            for kernel, kname in ((B.MFR_KERNEL_MFMA, "valu+mfma_chain" if dtype == B.MFR_DTYPE_F32 else "mfma_chain"),
+                                  (B.MFR_KERNEL_SHFL, "shfl_tree")):
                 t = B.make_tuning(kernel=kernel)
 
                 def call(i):
@@ -258,16 +286,19 @@ def split(args, torch, np, B, W):
 def variants(args, torch, np, B, W):
     """Section 5.4's comparison on this GPU: run time of the single-pass, recurrence and shuffle
     kernels and the result each returns, over n, for normal(0,1) and uniform[0,1) inputs.
-    (The errors against the CPU oracle are tabulated by tests/test_gpu_recurrence.py::test_error_vs_n_table.)"""
+    The error columns are Section 5.4's "% error against a CPU reduction in double precision",
+    100 |gpu - oracle| / |oracle|, and |gpu - oracle| / sum|x_i| (the figure the tolerance is stated in)."""
     timer = Timer(torch, B)
     out = torch.zeros(4, dtype=torch.float32, device="cuda")
     with open_out(args, "variants.txt") as f:
-        emit(f, "# kind n variant us Gelem/s result   (one buffer per n: sizes up to 2^26 are cache-resident)")
+        emit(f, "# one buffer per n (sizes up to 2^26 are cache-resident); inf = the variant's binary16 partials overflowed")
+        emit(f, "# kind n variant us Gelem/s result err_pct_of_|sum| err/sum|x|")
         for kind, cfg in (("normal", 3), ("uniform01", 2)):
             x = W.generate(kind, 1 << 28, W.config_seed(cfg))
             dev = torch.from_numpy(x.view(np.int16)).cuda()
             for k in range(10, 29, 2):
                 n = 1 << k
+                ref = oracle_reference(x[:n])
                 calls = (("single_pass", lambda: B.mfr_sum_f16(dev.data_ptr(), n, out.data_ptr(), timer.stream)),
                          ("recurrence_R4", lambda: B.mfr_sum_f16_recurrence(dev.data_ptr(), n, out.data_ptr(), 4, timer.stream)),
                          ("recurrence_R5", lambda: B.mfr_sum_f16_recurrence(dev.data_ptr(), n, out.data_ptr(), 5, timer.stream)),
@@ -282,7 +313,9 @@ def variants(args, torch, np, B, W):
                     e1.record()
                     torch.cuda.synchronize()
                     dt = e0.elapsed_time(e1) * 1e-3 / args.steps
-                    emit(f, "%s %d %s %.2f %.2f %r" % (kind, n, name, dt * 1e6, n / dt / 1e9, float(out[0].item())))
+                    got = float(out[0].item())
+                    pct = 100.0 * abs(got - ref[0]) / abs(ref[0]) if ref[0] else float("nan")
+                    emit(f, "%s %d %s %.2f %.2f %r %.3g %.3g" % (kind, n, name, dt * 1e6, n / dt / 1e9, got, pct, rel_err(got, ref)))
 
 
 def wide(args, torch, np, B, W):

@@ -68,7 +68,7 @@ enum {
  * one location; both modes here add them in index order instead). */
 enum {
     MFR_COMBINE_AUTO = 0,          /* single launch for grids up to 2048 blocks, else two */
-    MFR_COMBINE_SINGLE_LAUNCH = 1, /* the block that draws the last ticket adds the partials
+    MFR_COMBINE_SINGLE_LAUNCH = 1, /* the block with the highest index gathers and adds the partials
                                       (grids above 65536 blocks still use two launches) */
     MFR_COMBINE_TWO_LAUNCHES = 2   /* a second one-block kernel adds the partials */
 };
@@ -81,7 +81,10 @@ typedef struct mfr_tuning {
     int chain_R;          /* 1..8.  MFMA kernel: MFMAs accumulated into one accumulator tile
                              from zero before it is folded to an fp32 partial (the paper's R).
                              SHFL kernel: 16-byte loads per lane accumulated per group.
-                             Default: 3 (MFMA, SPLIT; 7 for binary32 input), 6 (SHFL) */
+                             Default: 3 (MFMA, SPLIT; 7 for binary32 input), 6 (SHFL); but a
+                             single array of more than 96 KiB and at most 256 MiB for which
+                             block_threads, chain_R and chains_in_flight are all left to the
+                             library gets 128-thread blocks and one chain of 8 */
     int grid_blocks;      /* MFR_GRID_AUTO, MFR_GRID_ONE_CHAIN, or an explicit count >= 1 */
     int kernel;           /* MFR_KERNEL_MFMA, MFR_KERNEL_SHFL or MFR_KERNEL_SPLIT */
     int chains_in_flight; /* 1, 2, 3, 4, 6 or 8 independent chains whose loads are issued before
@@ -118,7 +121,7 @@ typedef struct mfr_tuning {
  * adds the 8 * chain_R values of a lane's group in fp32 and is otherwise alike.
  * IEEE special values propagate (NaN in => NaN; +Inf and -Inf => NaN);
  * subnormal inputs contribute their value (not flushed), for every type.
- * Scratch (block partials + ticket counters) is owned by the library, one per
+ * Scratch (one word per block for the grid combine) is owned by the library, one per
  * (device, stream), allocated on first use and kept until mfr_release_scratch
  * or unload; calls on different streams may overlap, calls on one stream
  * serialise on the device.  Host threads may share a stream: the launches of
@@ -155,12 +158,12 @@ int mfr_sum_f16_ex(const mfr_half *x, size_t n, float *out,
  * mfr_sum_f16_ex for callers that cannot allocate: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same result,
  * bit for bit, as mfr_sum_f16_ex with the same arguments, but the block
- * partials and ticket counters live in a fixed 64 KiB array in device memory
+ * partials and combine slots live in a fixed 64 KiB array in device memory
  * that is part of the library's code object (every GPU the library runs on
  * holds its own copy from load to process exit), so the call never calls
  * hipMalloc, hipFree or any allocating routine, on any call, the first
  * included.
- *   Limit: grids of at most 8192 blocks (and ticket counters for them); a
+ *   Limit: grids of at most 8192 blocks; a
  *   tuning that asks for more -- MFR_GRID_ONE_CHAIN on a long input, a large
  *   explicit grid_blocks -- returns MFR_ERR_SCRATCH_LIMIT and enqueues
  *   nothing.  The library defaults (t == NULL) need 256 partials at most.
@@ -168,7 +171,7 @@ int mfr_sum_f16_ex(const mfr_half *x, size_t n, float *out,
  *   stream: calls that overlap in time on one GPU race on it and give wrong
  *   results; calls on one stream, or otherwise ordered, are safe.  The array
  *   needs no clearing: partials are written before they are read within a
- *   call, and every ticket counter is back at zero when a call completes.
+ *   call, and every combine slot is back at zero when a call completes.
  */
 int mfr_sum_f16_noalloc(const mfr_half *x, size_t n, float *out, const mfr_tuning *t, hipStream_t stream);
 
@@ -246,7 +249,8 @@ int mfr_sum_f16_f64_ex(const mfr_half *x, size_t n, double *out, const mfr_tunin
 int mfr_sum_f16_recurrence(const mfr_half *x, size_t n, float *out, int chain_R, hipStream_t stream);
 
 /*
- * The geometry mfr_sum_f16 uses.  Any pointer may be NULL.
+ * The geometry mfr_sum_f16 uses for inputs of more than 256 MiB (smaller ones:
+ * see mfr_tuning.chain_R).  Any pointer may be NULL.
  * The environment variables MFR_BLOCK (32 .. 1024, a power of two) and MFR_R
  * (1 .. 8), read once per process, replace the built-in default block size and
  * chain length wherever a call leaves them to the library (the B and R of
@@ -302,24 +306,8 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
                   unsigned long long plan[11]);
 
 /*
- * Host replay of the ticket counting of the single-launch grid combine
- * (inspection only, no device access): `blocks` blocks draw their tickets in
- * the order order[0], order[1], ... (a permutation of 0 .. blocks - 1) from
- * `counters` (counters_len words, all zero on entry), with one flat counter
- * (flat != 0) or two levels (groups of 32 blocks, then one top counter), through
- * the same function the kernels use with the device's atomic increment.
- * Returns the number of draws that were told "every block has drawn" -- 1 for
- * a correct count, and only the last draw may be the one -- or -100 if an
- * earlier draw was told so, or a negative status on invalid arguments.  On
- * return the counters hold what the next call would find (zeros, if the count
- * is right: every counter wraps when its last ticket is drawn).
- */
-int mfr_ticket_replay(unsigned int blocks, int flat, const unsigned int *order, unsigned int *counters,
-                      size_t counters_len);
-
-/*
  * Frees the scratch that calls on `stream` of the current device have left
- * with the library (block partials, ticket counters, the recurrence variant's
+ * with the library (block partials, combine slots, the recurrence variant's
  * level buffers), after synchronising the stream.  For streams that are about
  * to be destroyed, or to hand the memory back; a later call on the stream
  * allocates again.  Returns MFR_OK also when the stream holds none.  Must not

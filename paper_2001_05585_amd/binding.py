@@ -22,7 +22,7 @@ MFR_DTYPE_F16, MFR_DTYPE_BF16, MFR_DTYPE_F32 = 0, 1, 2
 
 EXPORTS = ("mfr_sum_f16", "mfr_sum_f16_tuned", "mfr_sum_f16_ex", "mfr_sum_f16_noalloc", "mfr_sum_bf16", "mfr_sum_f32", "mfr_sum_ex",
            "mfr_sum_rows_ex", "mfr_sum_f16_rows", "mfr_sum_f16_recurrence", "mfr_sum_f16_f64", "mfr_sum_f16_f64_ex", "mfr_get_default_tuning", "mfr_grid_for", "mfr_plan_for",
-           "mfr_plan_ex", "mfr_rows_plan", "mfr_ticket_replay", "mfr_release_scratch", "mfr_strerror", "mfr_last_hip_error", "mfr_version")
+           "mfr_plan_ex", "mfr_rows_plan", "mfr_release_scratch", "mfr_strerror", "mfr_last_hip_error", "mfr_version")
 
 
 class mfr_tuning(ctypes.Structure):
@@ -88,8 +88,6 @@ def lib() -> ctypes.CDLL:
     L.mfr_grid_for.restype = ctypes.c_longlong
     L.mfr_plan_for.argtypes = [sz, sz, ctypes.POINTER(mfr_tuning), ctypes.POINTER(ctypes.c_ulonglong)]
     L.mfr_plan_for.restype = ci
-    L.mfr_ticket_replay.argtypes = [ctypes.c_uint, ci, ctypes.POINTER(ctypes.c_uint), ctypes.POINTER(ctypes.c_uint), sz]
-    L.mfr_ticket_replay.restype = ci
     L.mfr_release_scratch.argtypes = [ctypes.c_void_p]
     L.mfr_release_scratch.restype = ci
     L.mfr_strerror.argtypes = [ci]
@@ -205,15 +203,6 @@ def mfr_plan_for(n: int, x_addr: int, t: mfr_tuning | None = None):
     tp = ctypes.byref(t) if t is not None else None
     _check(lib().mfr_plan_for(n, x_addr, tp, plan), "mfr_plan_for")
     return tuple(int(v) for v in plan)
-
-
-def mfr_ticket_replay(blocks: int, flat: bool, order, counters_len: int | None = None):
-    """(winners, counters after the replay) for blocks drawing in `order`."""
-    words = 16 * (2 + (blocks + 31) // 32) if counters_len is None else counters_len
-    arr = (ctypes.c_uint * blocks)(*order)
-    counters = (ctypes.c_uint * words)()
-    r = int(lib().mfr_ticket_replay(blocks, 1 if flat else 0, arr, counters, words))
-    return r, list(counters)
 
 
 def mfr_release_scratch(stream: int = 0) -> None:

@@ -10,15 +10,6 @@
 
 namespace mfr {
 
-__device__ __forceinline__ double row16_sum_f64(double v)
-{
-    v += __shfl_xor(v, 1, 64);
-    v += __shfl_xor(v, 2, 64);
-    v += __shfl_xor(v, 4, 64);
-    v += __shfl_xor(v, 8, 64);
-    return v;
-}
-
 // All threads of one block: sum of partials[0..count) in fixed order; thread 0 gets it.
 __device__ __forceinline__ double block_sum_of_doubles(const double *partials, unsigned int count, double *lds)
 {
@@ -51,7 +42,6 @@ __global__ void __launch_bounds__(1024) sum_kernel_wide(const SumArgs a)
 
     __shared__ double wave_partials[kMaxWavesPerBlock];
     __shared__ double combine_lds[kMaxWavesPerBlock];
-    __shared__ unsigned int is_last;
     if (lane == 0) wave_partials[wave] = wave_total;
     __syncthreads();
     double block_sum = 0.0;
@@ -59,29 +49,22 @@ __global__ void __launch_bounds__(1024) sum_kernel_wide(const SumArgs a)
         for (unsigned int i = 0; i < wpb; ++i) block_sum += wave_partials[i];
 
     double *out = (double *)a.out;
-    double *partials = (double *)a.partials;
     if (gridDim.x == 1) {
         if (threadIdx.x == 0) *out = block_sum;
         return;
     }
-    if (a.ticket == nullptr) {
-        if (threadIdx.x == 0) partials[blockIdx.x] = block_sum;
+    if (a.combine_slots == nullptr) {
+        if (threadIdx.x == 0) ((double *)a.partials)[blockIdx.x] = block_sum;
         return;
     }
-    // same publication order as the fp32 kernel: returning exchange, then the ticket; the reader
-    // fences (acquire, device scope) before it loads the partials
-    if (threadIdx.x == 0) {
-        unsigned long long prev = __hip_atomic_exchange((unsigned long long *)&partials[blockIdx.x],
-                                                        (unsigned long long)__double_as_longlong(block_sum),
-                                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("" : "+v"(prev) : : "memory");
-        is_last = draw_ticket(a.ticket, blockIdx.x, gridDim.x, a.ticket_flat != 0u) ? 1u : 0u;
+    // the same hand-over as in the fp32 kernel, with 64-bit slots
+    unsigned long long *slots = (unsigned long long *)a.combine_slots;
+    if (blockIdx.x + 1u != gridDim.x) {
+        if (threadIdx.x == 0) publish_slot(&slots[blockIdx.x], block_sum);
+        return;
     }
-    __syncthreads();
-    if (!is_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    const double total = block_sum_of_doubles(partials, gridDim.x, combine_lds);
-    if (threadIdx.x == 0) *out = total;
+    const double others = gather_slots(slots, gridDim.x - 1u, combine_lds);
+    if (threadIdx.x == 0) *out = others + block_sum;
 }
 
 __global__ void __launch_bounds__(256) combine_wide_kernel(const double *partials, unsigned int count, double *out)
@@ -98,7 +81,7 @@ static hipError_t launch_wide_ru(const Plan &p, dim3 grid, bool nt, hipStream_t 
     if (nt) hipLaunchKernelGGL((sum_kernel_wide<R, U, true>), grid, b, 0, stream, p.a);
     else hipLaunchKernelGGL((sum_kernel_wide<R, U, false>), grid, b, 0, stream, p.a);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && grid.x > 1 && p.a.ticket == nullptr) {
+    if (e == hipSuccess && grid.x > 1 && p.a.combine_slots == nullptr) {
         hipLaunchKernelGGL(combine_wide_kernel, dim3(1), dim3(256), 0, stream, (const double *)p.a.partials, grid.x,
                            (double *)p.a.out);
         e = hipGetLastError();

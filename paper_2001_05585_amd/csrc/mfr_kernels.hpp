@@ -4,8 +4,8 @@
 //      (Section 4.3) with an fp32 accumulator, and folds each finished chain
 //      to one fp32 partial;
 //   2. the waves of a block combine their partials through LDS;
-//   3. block partials go to a scratch array; the block that draws the last
-//      ticket adds them in index order and writes the result, or a second
+//   3. every block hands its partial to the block with the highest index,
+//      which adds them in index order and writes the result, or a second
 //      one-block launch does (the paper adds them with float atomics, whose
 //      order varies from run to run).
 // A conventional kernel (per-lane fp32 accumulation + wave shuffle tree, the
@@ -69,14 +69,13 @@ struct SumArgs {
     unsigned long long row_bytes;  // distance between rows in bytes
     unsigned long long split_chains;  // MFR_KERNEL_SPLIT: chains [0, split_chains) take the MFMA path ...
     unsigned long long split_waves;   // ... on waves [0, split_waves); the rest is conventional
-    unsigned long long ticket_stride;  // ticket words per row
-    unsigned int ticket_flat;    // nonzero: one ticket counter per row, else two levels
     unsigned int head;           // elements of slot 0 that lie before x
     unsigned int per_row_phase;  // nonzero: the rows of a batched call differ in 16-byte phase; each block then
                                  // derives base, head, vend, main0, chains, epi0, epi1 and slots of its row
                                  // itself (the values above are those of a row that starts on a boundary)
-    float *partials;             // gridDim.x per row
-    unsigned int *ticket;        // one per row; nullptr = two-launch combine
+    float *partials;             // two-launch combine: gridDim.x per row, read by combine_kernel
+    unsigned int *combine_slots; // single-launch combine: gridDim.x words per row, all zero between calls;
+                                 // nullptr = two-launch combine
     float *out;                  // one per row
 };
 
@@ -203,11 +202,35 @@ __device__ __forceinline__ float wave64_sum(float v)
     return (a + b) + (c + d);
 }
 
+template <int CTRL>
+__device__ __forceinline__ double dpp_add_f64(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+    return v + __hiloint2double(hi, lo);
+}
+
+// Sum over each row of 16 lanes in binary64, result in every lane of the row.
+__device__ __forceinline__ double row16_sum_f64(double v)
+{
+    v = dpp_add_f64<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add_f64<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add_f64<0x141>(v);   // row_half_mirror
+    v = dpp_add_f64<0x140>(v);   // row_mirror
+    return v;
+}
+
+// Sum over the 64 lanes in binary64, wave-uniform: DPP within each row of 16 lanes (no trip
+// through the LDS crossbar), then the four row sums.
 __device__ __forceinline__ double wave64_sum_f64(double v)
 {
+    v = row16_sum_f64(v);
+    double r[4];
 #pragma unroll
-    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
-    return v;
+    for (int k = 0; k < 4; ++k)
+        r[k] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 16 * k),
+                                __builtin_amdgcn_readlane(__double2loint(v), 16 * k));
+    return (r[0] + r[1]) + (r[2] + r[3]);
 }
 
 // The same for either running-sum type (the conventional path's per-lane sums).
@@ -242,49 +265,89 @@ __device__ __forceinline__ double block_sum_f64(const float *partials, unsigned 
     return total;
 }
 
-// Ticket for `blocks` blocks.  Flat: all blocks draw from one counter (word
-// 0); same-address atomics serialise (about 8 ns each), which is hidden when
-// the blocks finish at different times (long inputs) and exposed when they
-// finish together (short inputs).  Two-level: word kTicketStride * (1 + g) is
-// the counter of group g of kTicketGroup blocks (counters on separate 64-byte
-// lines), and word 0 the top counter, drawn by the block that completes its
-// group.  Returns true for exactly one caller: the one after which every other
-// block has drawn.  The host chooses the form and sizes the counters.
-constexpr unsigned int kTicketGroup = 32;
-constexpr unsigned int kTicketStride = 16;
+// Single-launch grid combine: hand-over of block partials through one word each.
+//
+// A slot is a 32-bit (64-bit for binary64 partials) word of device memory that is zero between
+// calls.  A block publishes its partial with ONE device-scope atomic exchange of the value's bits --
+// +0.0, the only value whose bits are zero, goes as -0.0, which adds the same -- and is done: it
+// waits for nothing.  The block with the highest index of the row takes the other blocks' slots
+// with device-scope atomic exchanges against zero until each has returned a non-zero word, and
+// adds the values in index order in binary64.  The exchange is a read-modify-write, so it is
+// performed where the device keeps its memory coherent (never answered from a cache of the
+// reader's own die), and it puts the zero back in the same operation.  Value and "it is there"
+// travel in the same word, so no ordering between two memory operations is relied on and no fence
+// is needed: an exchange returns either the zero that the previous call left (made visible by the
+// kernel boundary) or the one value that this call stored.
+//
+// Why the reader cannot wait forever: workgroups are dispatched in index order, so when the
+// highest-index block of a row runs, every block it waits for has been dispatched or is waiting for
+// a compute unit that the reader, a single workgroup, does not hold.  None of them waits for
+// anything.  The spin limit below (seconds) only turns a device that stopped making progress into a
+// NaN result instead of a hang.
+constexpr unsigned int kSpinLimit = 1u << 22;
 
-inline unsigned long long ticket_words(unsigned int blocks, bool flat)
+__device__ __forceinline__ unsigned int slot_bits(float v)
 {
-    if (flat) return kTicketStride;
-    return (unsigned long long)kTicketStride * (1u + (blocks + kTicketGroup - 1u) / kTicketGroup);
+    const unsigned int b = __float_as_uint(v);
+    return b ? b : 0x80000000u;
+}
+__device__ __forceinline__ unsigned long long slot_bits(double v)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    return b ? b : 0x8000000000000000ull;
+}
+__device__ __forceinline__ double slot_value(unsigned int b) { return (double)__uint_as_float(b); }
+__device__ __forceinline__ double slot_value(unsigned long long b) { return __longlong_as_double((long long)b); }
+
+template <typename Word, typename Value>
+__device__ __forceinline__ void publish_slot(Word *slot, Value v)
+{
+    // a read-modify-write whose result nobody waits for: performed at the coherence point like the
+    // reader's exchange, whatever the write policy of this die's cache
+    (void)__hip_atomic_exchange(slot, slot_bits(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// `inc(p, wrap)` is atomicInc: returns *p and stores *p >= wrap ? 0 : *p + 1.  The kernels pass the
-// device atomic; the host passes a plain replay of it to check the counting (mfr_ticket_replay).
-template <typename Inc>
-__host__ __device__ inline bool draw_ticket_with(Inc inc, unsigned int *tickets, unsigned int block, unsigned int blocks,
-                                                 bool flat)
+// All threads of the reading block: sum of slots[0..count) in binary64, fixed order (thread t takes
+// t, t + blockDim, ... in rounds of eight exchanges, then lanes, then waves); every slot is zero
+// again afterwards.  Result valid in thread 0.
+template <typename Word>
+__device__ __forceinline__ double gather_slots(Word *slots, unsigned int count, double *lds)
 {
-    if (flat) return inc(tickets, blocks - 1u) == blocks - 1u;
-    const unsigned int groups = (blocks + kTicketGroup - 1u) / kTicketGroup;
-    const unsigned int g = block / kTicketGroup;
-    const unsigned int first = g * kTicketGroup;
-    const unsigned int size = blocks - first < kTicketGroup ? blocks - first : kTicketGroup;
-    if (size > 1u) {
-        const unsigned int old = inc(tickets + kTicketStride * (1u + g), size - 1u);
-        if (old != size - 1u) return false;
+    constexpr int K = 8;
+    const unsigned int lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, wpb = (blockDim.x + 63u) >> 6;
+    const unsigned int step = blockDim.x;
+    double acc = 0.0;
+    for (unsigned int base = threadIdx.x; base < count; base += K * step) {
+        Word v[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) v[k] = 0;
+        unsigned int spins = 0;
+        for (;;) {
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const unsigned int i = base + (unsigned)k * step;
+                if (i < count && v[k] == 0)
+                    v[k] = __hip_atomic_exchange(&slots[i], (Word)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            bool pending = false;
+#pragma unroll
+            for (int k = 0; k < K; ++k) pending |= (base + (unsigned)k * step < count) && v[k] == 0;
+            if (!pending) break;
+            if (++spins == kSpinLimit) { acc = __builtin_nan(""); break; }
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const unsigned int i = base + (unsigned)k * step;
+            if (i < count) acc += slot_value(v[k]);
+        }
     }
-    if (groups == 1u) return true;
-    return inc(tickets, groups - 1u) == groups - 1u;
-}
-
-struct DeviceAtomicInc {
-    __device__ unsigned int operator()(unsigned int *p, unsigned int wrap) const { return atomicInc(p, wrap); }
-};
-
-__device__ __forceinline__ bool draw_ticket(unsigned int *tickets, unsigned int block, unsigned int blocks, bool flat)
-{
-    return draw_ticket_with(DeviceAtomicInc(), tickets, block, blocks, flat);
+    acc = wave64_sum_f64(acc);
+    if (lane == 0) lds[wave] = acc;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0)
+        for (unsigned int w = 0; w < wpb; ++w) total += lds[w];
+    return total;
 }
 
 // ------------------------------------------------------ tile consumers ---
@@ -380,6 +443,56 @@ __device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *bas
     const uint4v *lane_base = base + a.main0 + (carries ? lane : 0u);
     Acc partial = 0;
 
+    // Border: leftover whole tiles (fewer than R), leftover slots, the partial last slot and the head
+    // slot, as masked tiles in chains of R (at most two chains; tiles past the end are all zeros).
+    // The loads of the first border chain are issued early and consumed after the main loop, and
+    // they go out right after the loads of this wave's first main step, so that the border's own
+    // memory round trips (its element-wise loads wait for each other) run in the shadow of that
+    // step: the wave that carries the border neither starts nor ends with a round trip of its own.
+    uint4v vb[R];
+    if (border) {
+        auto load_border = [&]() {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                vb[r] = load_epilogue<DT>(a, base, x, a.epi0 + (unsigned long long)r * TS + lane, carries);
+        };
+        bool stepped = false;
+        if constexpr (U > 1) {
+            if (c + (unsigned long long)(U - 1) * stride < c_end) {
+                uint4v v[U][R];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const uint4v *p = lane_base + ((c + (unsigned long long)u * stride) * R + r) * TS;
+                        v[u][r] = carries ? load_slot<NT>(p) : zero4;
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+                load_border();
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < U; ++u) partial += (Acc)consume_chain<KIND, DT, R>(v[u]);
+                c += (unsigned long long)U * stride;
+                stepped = true;
+            }
+        }
+        if (!stepped && c < c_end) {
+            uint4v v[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const uint4v *p = lane_base + (c * R + r) * TS;
+                v[r] = carries ? load_slot<NT>(p) : zero4;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            load_border();
+            __builtin_amdgcn_sched_barrier(0);
+            partial += (Acc)consume_chain<KIND, DT, R>(v);
+            c += stride;
+            stepped = true;
+        }
+        if (!stepped) load_border();
+    }
+
     if constexpr (U > 1) {
         for (; c + (unsigned long long)(U - 1) * stride < c_end; c += (unsigned long long)U * stride) {
             uint4v v[U][R];
@@ -407,11 +520,9 @@ __device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *bas
         partial += (Acc)consume_chain<KIND, DT, R>(v);
     }
 
-    // Border: leftover whole tiles (fewer than R), leftover slots, the partial
-    // last slot and the head slot, as masked tiles in chains of R (at most two
-    // chains; tiles past the end are all zeros).
     if (border) {
-        for (unsigned long long p0 = a.epi0; p0 < a.epi1; p0 += (unsigned long long)R * TS) {
+        if (a.epi0 < a.epi1) partial += (Acc)consume_chain<KIND, DT, R>(vb);
+        for (unsigned long long p0 = a.epi0 + (unsigned long long)R * TS; p0 < a.epi1; p0 += (unsigned long long)R * TS) {
             uint4v v[R];
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -479,7 +590,6 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
     // Level 2: one value per block from its wave partials, added in wave order, rounded to fp32 once.
     __shared__ WaveAcc wave_partials[kMaxWavesPerBlock];
     __shared__ double wave_partials_f64[kMaxWavesPerBlock];
-    __shared__ unsigned int is_last;
     if (lane == 0) wave_partials[wave] = partial;
     __syncthreads();
     float block_sum = 0.f;
@@ -495,36 +605,20 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
         if (threadIdx.x == 0) *out = block_sum;
         return;
     }
-    float *partials = a.partials + row * gridDim.x;
-    if (a.ticket == nullptr) {
+    if (a.combine_slots == nullptr) {
         // two-launch combine: the partial is picked up by combine_kernel
-        if (threadIdx.x == 0) partials[blockIdx.x] = block_sum;
+        if (threadIdx.x == 0) a.partials[row * gridDim.x + blockIdx.x] = block_sum;
         return;
     }
-    // Single-launch combine.  The block partial is not written with a store that a later release
-    // would have to make visible (a release fence at device scope costs a write-back of the whole
-    // L2 per block): it is the payload of a device-scope atomic exchange, performed at the device's
-    // coherence point like the ticket itself.  The exchange returns its old value; the ticket is
-    // drawn only after that value has arrived, i.e. after the exchange has been performed, so in
-    // the order of operations at the coherence point every block's exchange precedes its ticket.
-    // The block that draws the last ticket sees every ticket drawn, hence every exchange performed;
-    // it then executes a device-scope acquire fence (dropping what its own caches may hold of the
-    // partials array) and reads the partials with device-scope atomic loads.  All counters wrap to
-    // zero by themselves, ready for the next call.
-    if (threadIdx.x == 0) {
-        unsigned int prev = __hip_atomic_exchange((unsigned int *)&partials[blockIdx.x],
-                                                  __float_as_uint(block_sum), __ATOMIC_RELAXED,
-                                                  __HIP_MEMORY_SCOPE_AGENT);
-        // the exchange result must be in a register (the wave waits for it) and the compiler may
-        // move no later memory operation above this point
-        asm volatile("" : "+v"(prev) : : "memory");
-        is_last = draw_ticket(a.ticket + row * a.ticket_stride, blockIdx.x, gridDim.x, a.ticket_flat != 0u) ? 1u : 0u;
+    // Single-launch combine: every block but the last publishes its partial and is done; the block
+    // with the highest index gathers them, adds its own and writes the result.
+    unsigned int *slots = a.combine_slots + row * gridDim.x;
+    if (blockIdx.x + 1u != gridDim.x) {
+        if (threadIdx.x == 0) publish_slot(&slots[blockIdx.x], block_sum);
+        return;
     }
-    __syncthreads();
-    if (!is_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    const double total = block_sum_f64(partials, gridDim.x, wave_partials_f64);
-    if (threadIdx.x == 0) *out = (float)total;
+    const double others = gather_slots(slots, gridDim.x - 1u, wave_partials_f64);
+    if (threadIdx.x == 0) *out = (float)(others + (double)block_sum);
 }
 
 // ------------------------------------------------------------ launching ---

@@ -57,8 +57,8 @@ struct DeviceInfo {
 struct Scratch {
     float *partials = nullptr;
     size_t partials_capacity = 0;   // floats
-    unsigned int *tickets = nullptr;
-    size_t tickets_capacity = 0;    // counters, all zero between calls
+    unsigned int *slots = nullptr;      // single-launch combine: one word per block, all zero between calls
+    size_t slots_capacity = 0;
     unsigned short *levels = nullptr;   // recurrence variant: the binary16 partials of two levels
     size_t levels_capacity = 0;
     // Buffers that a larger one has replaced.  A call copies the current pointers under the mutex
@@ -82,9 +82,18 @@ constexpr int kDefaultBlock = 256;
 constexpr int kDefaultR = 3;
 constexpr int kDefaultR_shfl = 6;              // the conventional kernel: one group of six loads
 constexpr int kDefaultR_f32 = 7;               // binary32: one chain of seven tiles (75.9 us; two chains of three: 80 us)
+// A single array of more than 96 KiB and at most 256 MiB, all of block size, chain length and chains
+// in flight left to the library: 128-thread blocks and one chain of eight tiles, i.e. 8 KiB contiguous
+// per wave and step.  Such calls spend a large part of their time getting started and finishing, and
+// this geometry shortens both (64 MiB: 21.3 us against 22.0; 32 MiB: 7.8 against 8.3; 8 MiB: 4.5
+// against 4.8); from 512 MiB on six KiB per wave in two chains streams faster (75.6 us against 76.5).
+constexpr unsigned long long kMidSizeMinBytes = 96ull << 10;
+constexpr unsigned long long kMidSizeMaxBytes = 256ull << 20;
+constexpr int kMidSizeBlock = 128;
+constexpr int kMidSizeR = 8;
 constexpr int kDefaultWavesPerCU = 4;          // one wave per SIMD
-constexpr long long kTicketMaxBlocks = 2048;   // AUTO: larger grids combine with a second launch
-constexpr long long kTicketHardMax = 65536;    // single-launch combine is not offered beyond this
+constexpr long long kSingleLaunchAutoMax = 2048;   // AUTO: larger grids combine with a second launch
+constexpr long long kSingleLaunchHardMax = 65536;  // single-launch combine is not offered beyond this
 constexpr size_t kMaxRowsPerLaunch = 65535;    // gridDim.y limit
 constexpr unsigned long long kOneBlockMaxChains = 32;   // library defaults: arrays this short get one block
 // Inputs that fit in the eight 4 MiB L2s may be resident there (a reduction often follows the kernel
@@ -157,8 +166,9 @@ bool valid_dtype(int dtype)
     return dtype == MFR_DTYPE_F16 || dtype == MFR_DTYPE_BF16 || dtype == MFR_DTYPE_F32;
 }
 
-// Fills in defaults and checks ranges; no HIP calls.
-int resolve_tuning(const mfr_tuning *in, int dtype, mfr_tuning *t)
+// Fills in defaults and checks ranges; no HIP calls.  `single_array_bytes`: size of the input when
+// the call sums one array (selects the size-dependent defaults), 0 otherwise.
+int resolve_tuning(const mfr_tuning *in, int dtype, mfr_tuning *t, unsigned long long single_array_bytes = 0)
 {
     mfr_tuning z;
     memset(&z, 0, sizeof z);
@@ -167,6 +177,12 @@ int resolve_tuning(const mfr_tuning *in, int dtype, mfr_tuning *t)
     if (z.block_threads == 0 || z.chain_R == 0) {
         const DefaultGeometry &g = default_geometry();
         if (!g.valid) return MFR_ERR_INVALID_ARG;
+        if (z.block_threads == 0 && z.chain_R == 0 && z.chains_in_flight == 0 && !g.overridden &&
+            z.kernel != MFR_KERNEL_SPLIT && single_array_bytes > kMidSizeMinBytes && single_array_bytes <= kMidSizeMaxBytes) {
+            z.block_threads = kMidSizeBlock;
+            z.chain_R = kMidSizeR;
+            z.chains_in_flight = 1;
+        }
         if (z.block_threads == 0) z.block_threads = g.block;
         if (z.chain_R == 0)
             z.chain_R = g.chain_R ? g.chain_R
@@ -279,15 +295,6 @@ int block_threads_for_rows(size_t rows, size_t row_bytes, int cus)
     return best_block;
 }
 
-// One counter for all blocks when the grid is small, or when each wave has so
-// much to do that the blocks do not finish together; two levels otherwise.
-bool ticket_flat_for(long long grid, const Plan &p)
-{
-    if (grid <= 64) return true;
-    const unsigned long long per_wave = p.chains / ((unsigned long long)grid * (unsigned)p.waves);
-    return grid <= 512 && per_wave >= 32;
-}
-
 // Capacity doubles until it covers `need`.  The buffer that is outgrown is not freed here (see
 // Scratch::retired): all retired buffers of a stream together are smaller than its current one.
 int grow(void **mem, size_t *capacity, size_t need, size_t elem, size_t floor_count, bool zero,
@@ -311,19 +318,19 @@ int grow(void **mem, size_t *capacity, size_t need, size_t elem, size_t floor_co
     return MFR_OK;
 }
 
-// Where a call's block partials and ticket counters live: the stream's library-owned buffers
+// Where a call's block partials (two-launch combine) and slots (single-launch combine) live: the stream's library-owned buffers
 // (allocated or enlarged here if need be), or a fixed region that the caller of sum_rows_impl
 // hands in and that is never enlarged.
 struct ScratchView {
     float *partials = nullptr;
     size_t partials_capacity = 0;
-    unsigned int *tickets = nullptr;
-    size_t tickets_capacity = 0;
+    unsigned int *slots = nullptr;
+    size_t slots_capacity = 0;
     std::mutex *launch_mutex = nullptr;     // fixed regions: the mutex that keeps one call's launches together
 };
 
 // Locks the stream's launch mutex into *launch_lock (the caller keeps it until its last launch).
-int get_scratch(int dev, hipStream_t stream, size_t partials, size_t tickets, ScratchView *out,
+int get_scratch(int dev, hipStream_t stream, size_t partials, size_t slots, ScratchView *out,
                 std::unique_lock<std::mutex> *launch_lock)
 {
     Scratch *entry = nullptr;
@@ -336,12 +343,12 @@ int get_scratch(int dev, hipStream_t stream, size_t partials, size_t tickets, Sc
     Scratch &s = *entry;
     int st = grow((void **)&s.partials, &s.partials_capacity, partials, sizeof(float), 4096, false, &s.retired);
     if (st != MFR_OK) return st;
-    st = grow((void **)&s.tickets, &s.tickets_capacity, tickets, sizeof(unsigned int), 1024, true, &s.retired);
+    st = grow((void **)&s.slots, &s.slots_capacity, slots, sizeof(unsigned int), 1024, true, &s.retired);
     if (st != MFR_OK) return st;
     out->partials = s.partials;
     out->partials_capacity = s.partials_capacity;
-    out->tickets = s.tickets;
-    out->tickets_capacity = s.tickets_capacity;
+    out->slots = s.slots;
+    out->slots_capacity = s.slots_capacity;
     return MFR_OK;
 }
 
@@ -454,7 +461,7 @@ int fill_zero(float *out, size_t count, hipStream_t stream)
 }
 
 // rows sums of cols elements each; consecutive rows are row_stride elements apart.
-// `fixed`: if not null, the block partials and tickets live there and nothing is allocated; a call
+// `fixed`: if not null, the block partials and slots live there and nothing is allocated; a call
 // that needs more than it holds fails with MFR_ERR_SCRATCH_LIMIT.  `per_row_only`: skip the
 // many-rows kernel although tin is null.
 int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row_stride, float *out,
@@ -462,7 +469,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
                   bool per_row_only = false)
 {
     mfr_tuning t;
-    const int st = resolve_tuning(tin, dtype, &t);
+    const int st = resolve_tuning(tin, dtype, &t, rows == 1 && valid_dtype(dtype) ? (unsigned long long)cols * elem_size(dtype) : 0ull);
     if (st != MFR_OK) return st;
     const unsigned esize = elem_size(dtype);
     if (!out) return MFR_ERR_INVALID_ARG;
@@ -520,24 +527,25 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     // A short single array is summed by one block with a wave per chain (up to 16 waves, two chains
     // each): combining several blocks costs three dependent device-scope round trips, 1.6 us, which a
     // call replayed from a graph would see in full (1.9 us against 3.4 us per call).
-    if (tin == nullptr && rows == 1 && one_block_default(p.chains, &t)) plan_region(cols, (size_t)x, esize, t, &p);
+    if (tin == nullptr && rows == 1 && cols * esize <= kMidSizeMinBytes && one_block_default(p.chains, &t))
+        plan_region(cols, (size_t)x, esize, t, &p);
     p.a.per_row_phase = same_phase ? 0u : 1u;
     const long long grid = grid_blocks_for(p, t, info.cus, batch);
     if (grid < 1) return MFR_ERR_INVALID_ARG;
-    const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
-                              (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
-    const bool ticket_flat = ticket_flat_for(grid, p);
+    const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kSingleLaunchHardMax ||
+                              (t.combine == MFR_COMBINE_AUTO && grid > kSingleLaunchAutoMax);
     ScratchView s;
     std::unique_lock<std::mutex> launch_lock;      // released when this call has enqueued its last kernel
     if (grid > 1) {
-        const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid, ticket_flat) * batch;
+        // one float per block and row for the second launch to read, or one slot per block and row
+        const size_t partial_count = two_launches ? (size_t)grid * batch : 1;
+        const size_t slot_count = two_launches ? 1 : (size_t)grid * batch;
         if (fixed) {
-            if ((size_t)grid * batch > fixed->partials_capacity || ticket_words > fixed->tickets_capacity)
-                return MFR_ERR_SCRATCH_LIMIT;
+            if (partial_count > fixed->partials_capacity || slot_count > fixed->slots_capacity) return MFR_ERR_SCRATCH_LIMIT;
             s = *fixed;
             launch_lock = std::unique_lock<std::mutex>(*fixed->launch_mutex);
         } else {
-            const int ss = get_scratch(dev, stream, (size_t)grid * batch, ticket_words, &s, &launch_lock);
+            const int ss = get_scratch(dev, stream, partial_count, slot_count, &s, &launch_lock);
             if (ss != MFR_OK) return ss;
         }
     }
@@ -561,9 +569,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
             p.a.split_chains = c1;
         }
         p.a.partials = s.partials;
-        p.a.ticket = two_launches ? nullptr : s.tickets;
-        p.a.ticket_stride = mfr::ticket_words((unsigned)grid, ticket_flat);
-        p.a.ticket_flat = ticket_flat ? 1u : 0u;
+        p.a.combine_slots = two_launches ? nullptr : s.slots;
         p.a.out = out + r0;
         const hipError_t e = launch_dtype(dtype, p, dim3((unsigned)grid, (unsigned)nr), t, stream);
         if (e != hipSuccess) return hip_fail(e, "kernel launch");
@@ -669,21 +675,20 @@ int sum_wide_impl(const mfr_half *x, size_t n, double *out, const mfr_tuning *ti
     plan_region(n, (size_t)x, 2, t, &p);
     const long long grid = grid_blocks_for(p, t, info.cus, 1);
     if (grid < 1) return MFR_ERR_INVALID_ARG;
-    const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kTicketHardMax ||
-                              (t.combine == MFR_COMBINE_AUTO && grid > kTicketMaxBlocks);
-    const bool ticket_flat = ticket_flat_for(grid, p);
+    const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kSingleLaunchHardMax ||
+                              (t.combine == MFR_COMBINE_AUTO && grid > kSingleLaunchAutoMax);
     ScratchView s;
     std::unique_lock<std::mutex> launch_lock;
     if (grid > 1) {
-        const size_t ticket_words = two_launches ? 1 : (size_t)mfr::ticket_words((unsigned)grid, ticket_flat);
-        const int ss = get_scratch(dev, stream, 2 * (size_t)grid + 2, ticket_words, &s, &launch_lock);   // doubles live in the float array
+        // binary64 partials and 64-bit slots: two words of the 4-byte arrays each (hipMalloc'ed: 8-byte aligned)
+        const int ss = get_scratch(dev, stream, two_launches ? 2 * (size_t)grid + 2 : 1, two_launches ? 1 : 2 * (size_t)grid + 2,
+                                   &s, &launch_lock);
         if (ss != MFR_OK) return ss;
     }
     p.a.base = (const uint4v *)((size_t)x & ~(size_t)15);
     p.a.x = x;
-    p.a.partials = s.partials;          // hipMalloc'ed: 8-byte aligned
-    p.a.ticket = two_launches ? nullptr : s.tickets;
-    p.a.ticket_flat = ticket_flat ? 1u : 0u;
+    p.a.partials = s.partials;
+    p.a.combine_slots = two_launches ? nullptr : s.slots;
     p.a.out = (float *)out;
     const hipError_t e = mfr::launch_sum_wide(p, dim3((unsigned)grid), t, stream);
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
@@ -695,13 +700,13 @@ int sum_impl(const void *x, int dtype, size_t n, float *out, const mfr_tuning *t
     return sum_rows_impl(x, dtype, 1, n, n, out, tin, stream);
 }
 
-// Scratch of the entry point that allocates nothing: block partials, then ticket counters, in a
-// device array that every GPU the library runs on holds from the load of the code object to the
-// end of the process.  Zero when loaded; the partials need no initial value and the counters wrap
-// back to zero at the end of every call.
+// Scratch of the entry point that allocates nothing: block partials (two-launch combine), then
+// slots (single-launch combine), in a device array that every GPU the library runs on holds from
+// the load of the code object to the end of the process.  Zero when loaded; the partials need no
+// initial value and the reading block puts the zero back into every slot it has read.
 constexpr size_t kStaticPartials = 8192;       // floats: grids of up to this many blocks
-constexpr size_t kStaticTickets = 8192;        // counters: covers two-level tickets of such a grid
-static __device__ __align__(256) unsigned char scratch[(kStaticPartials + kStaticTickets) * 4];
+constexpr size_t kStaticSlots = 8192;          // words: the same
+static __device__ __align__(256) unsigned char scratch[(kStaticPartials + kStaticSlots) * 4];
 
 // The array's address on each device.  `scratch` itself is a host-side handle, not a device
 // address: only what hipGetSymbolAddress returns for the current device may reach a kernel.
@@ -720,8 +725,8 @@ int static_scratch(int dev, ScratchView *out)
     }
     out->partials = (float *)g_static_scratch[dev];
     out->partials_capacity = kStaticPartials;
-    out->tickets = (unsigned int *)(g_static_scratch[dev] + kStaticPartials * sizeof(float));
-    out->tickets_capacity = kStaticTickets;
+    out->slots = (unsigned int *)(g_static_scratch[dev] + kStaticPartials * sizeof(float));
+    out->slots_capacity = kStaticSlots;
     out->launch_mutex = &g_static_launch_mutex[dev];
     return MFR_OK;
 }
@@ -824,11 +829,11 @@ int mfr_get_default_tuning(int *block_threads, int *chain_R, int *grid_blocks)
 long long mfr_grid_for(size_t n, size_t x_addr, const mfr_tuning *tin)
 {
     mfr_tuning t;
-    if (resolve_tuning(tin, MFR_DTYPE_F16, &t) != MFR_OK) return -1;
+    if (resolve_tuning(tin, MFR_DTYPE_F16, &t, (unsigned long long)n * 2ull) != MFR_OK) return -1;
     if (n == 0) return 1;
     Plan p;
     plan_region(n, x_addr, 2, t, &p);
-    if (tin == nullptr && one_block_default(p.chains, &t)) return 1;
+    if (tin == nullptr && n * 2ull <= kMidSizeMinBytes && one_block_default(p.chains, &t)) return 1;
     int cus = 0;
     if (t.grid_blocks == MFR_GRID_AUTO) {
         int dev = 0;
@@ -842,7 +847,7 @@ long long mfr_grid_for(size_t n, size_t x_addr, const mfr_tuning *tin)
 int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *tin, unsigned long long plan[7])
 {
     mfr_tuning t;
-    const int st = resolve_tuning(tin, dtype, &t);
+    const int st = resolve_tuning(tin, dtype, &t, valid_dtype(dtype) ? (unsigned long long)n * elem_size(dtype) : 0ull);
     if (st != MFR_OK) return st;
     const unsigned esize = elem_size(dtype);
     if (!plan || (x_addr & (esize - 1u)) || n > ((size_t)1 << 60)) return MFR_ERR_INVALID_ARG;
@@ -888,30 +893,6 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
     return 1;
 }
 
-int mfr_ticket_replay(unsigned int blocks, int flat, const unsigned int *order, unsigned int *counters,
-                      size_t counters_len)
-{
-    if (blocks < 1 || !order || !counters) return -MFR_ERR_INVALID_ARG;
-    if (counters_len < mfr::ticket_words(blocks, flat != 0)) return -MFR_ERR_INVALID_ARG;
-    struct SerialInc {
-        unsigned int operator()(unsigned int *p, unsigned int wrap) const
-        {
-            const unsigned int old = *p;
-            *p = old >= wrap ? 0u : old + 1u;
-            return old;
-        }
-    };
-    int winners = 0;
-    for (unsigned int i = 0; i < blocks; ++i) {
-        if (order[i] >= blocks) return -MFR_ERR_INVALID_ARG;
-        if (mfr::draw_ticket_with(SerialInc(), counters, order[i], blocks, flat != 0)) {
-            if (i != blocks - 1u) return -100;      // somebody was told "last" before everybody had drawn
-            ++winners;
-        }
-    }
-    return winners;
-}
-
 int mfr_release_scratch(hipStream_t stream)
 {
     int dev = 0;
@@ -924,7 +905,7 @@ int mfr_release_scratch(hipStream_t stream)
     hipError_t first = hipSuccess;
     std::vector<void *> all = s.retired;
     all.push_back(s.partials);
-    all.push_back(s.tickets);
+    all.push_back(s.slots);
     all.push_back(s.levels);
     for (void *mem : all) {
         if (!mem) continue;

@@ -409,6 +409,30 @@ def test_host_threads_sharing_one_stream_while_the_scratch_grows(oracle_lib):
     B.mfr_release_scratch(s.cuda_stream)
 
 
+def test_an_mfma_adds_a_column_with_one_rounding(oracle_lib):
+    """What the tolerance argument rests on, measured: one column of a tile holds 1.0 followed by 31
+    values of 2^-24, each exactly half a unit in the last place of 1.0f.  Thirty-two sequential fp32
+    additions would leave 1.0 (every addition is a tie that rounds back to even); the matrix unit adds
+    the column's products and the accumulator with a single rounding, so the result is the correctly
+    rounded sum, for one tile and for a chain of eight (255 such values).  A chain of R MFMAs therefore
+    rounds R times per column, not 32 R times."""
+    tiny = np.float16(2.0 ** -24)
+    for R in (1, 2, 3, 8):
+        # column 0 of a tile = the slots of lanes 0, 16, 32, 48: values 8 l .. 8 l + 7
+        col0 = [512 * r + 8 * lane + j for r in range(R) for lane in (0, 16, 32, 48) for j in range(8)]
+        x = np.zeros(512 * R, dtype=np.float16)
+        x[col0] = tiny
+        x[col0[0]] = 1.0
+        s, sa = oracle_lib.sum_f16(x)
+        assert s == 1.0 + (32 * R - 1) * 2.0 ** -24
+        got = gpu_sum(x, B.make_tuning(64, R, 1, B.MFR_KERNEL_MFMA, 1))
+        assert float(got) == float(np.float32(s)) != 1.0, (R, float(got), s)
+        # the large value last in its column: the same
+        x[col0[0]], x[col0[-1]] = tiny, 1.0
+        got = gpu_sum(x, B.make_tuning(64, R, 1, B.MFR_KERNEL_MFMA, 1))
+        assert float(got) == float(np.float32(s)), (R, float(got), s)
+
+
 def test_single_launch_combine_with_65536_blocks():
     n = 1 << 25
     d = DeviceInput(W.ones(n))

@@ -180,8 +180,9 @@ def test_environment_override_of_the_default_geometry():
     assert r.returncode == 0, r.stderr
     lines = r.stdout.splitlines()
     assert lines[0] == "(512, 2, 0)"
-    # 2^20 halves = 2048 tiles of 64 slots: chains of R = 2 tiles instead of 3
-    assert eval(lines[1])[3] == 1024 and eval(base.stdout.splitlines()[1])[3] == 682
+    # 2^20 halves = 2048 tiles of 64 slots: chains of R = 2 tiles instead of the 8 that an input of
+    # 2 MiB gets by default (the override also switches the size-dependent defaults off)
+    assert eval(lines[1])[3] == 1024 and eval(base.stdout.splitlines()[1])[3] == 256
     # explicit tuning is not affected
     r = _in_fresh_process({"MFR_BLOCK": "512", "MFR_R": "2"},
                           "from paper_2001_05585_amd import binding as B\n"

@@ -59,48 +59,3 @@ def test_grid_for_is_consistent(n, block, R, grid):
     else:
         assert g == grid
 
-
-# ------------------------------------------------------------- ticket counting ---
-
-def _ticket_orders(blocks, rng):
-    yield list(range(blocks))
-    yield list(range(blocks - 1, -1, -1))
-    # whole groups first, then the stragglers of every group: every group is completed late
-    late = [b for b in range(blocks) if b % 32 == 31 or b == blocks - 1]
-    yield [b for b in range(blocks) if b not in set(late)] + late
-    for _ in range(3):
-        order = list(range(blocks))
-        rng.shuffle(order)
-        yield order
-
-
-def test_exactly_one_block_is_told_it_is_last_and_counters_return_to_zero():
-    """The single-launch combine relies on this: whatever the order in which blocks draw, only the
-    last draw is told that every block has drawn, and all counters are back at zero for the next
-    call.  Every grid size up to 1100 blocks and some large ones, flat and two-level counters."""
-    import random
-    rng = random.Random(7)
-    sizes = list(range(1, 1101)) + [2047, 2048, 2049, 4096, 8191, 65535, 65536]
-    for blocks in sizes:
-        for flat in (True, False):
-            orders = list(_ticket_orders(blocks, rng))
-            if blocks > 300:
-                orders = orders[2:4] if not flat else orders[:1]
-            for order in orders:
-                winners, counters = B.mfr_ticket_replay(blocks, flat, order)
-                assert winners == 1, (blocks, flat, winners)
-                assert not any(counters), (blocks, flat)
-    # a second call on the same counters finds them usable again; counters left non-zero would not be
-    blocks = 100
-    order = list(range(blocks))
-    words = 16 * (2 + (blocks + 31) // 32)
-    import ctypes
-    arr = (ctypes.c_uint * blocks)(*order)
-    counters = (ctypes.c_uint * words)()
-    for _ in range(3):
-        assert B.lib().mfr_ticket_replay(blocks, 0, arr, counters, words) == 1
-    # invalid arguments
-    assert B.lib().mfr_ticket_replay(0, 0, arr, counters, words) < 0
-    assert B.lib().mfr_ticket_replay(blocks, 0, arr, counters, 16) < 0
-    bad = (ctypes.c_uint * blocks)(*([blocks] * blocks))
-    assert B.lib().mfr_ticket_replay(blocks, 0, bad, counters, words) < 0
