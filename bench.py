@@ -223,7 +223,7 @@ def traffic(args):
     torch.cuda.set_device(0)
     n = args.n
     x = W.generate("normal", n, W.config_seed(3))
-    bufs = make_buffers(torch, np, x, args.buffers)
+    bufs = make_buffers(torch, np, x, args.buffers if args.buffers > 0 else 4)
     dst = torch.empty_like(bufs[0])
     out = torch.zeros(4, dtype=torch.float32, device="cuda")
     tuning = B.make_tuning(args.block, args.R, args.grid, args.kernel, args.in_flight, args.nontemporal, args.combine)
@@ -292,7 +292,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic", action="store_true", help="short run for rocprofv3 --pmc counters")
     ap.add_argument("--traffic-rows", action="store_true", help="the same for the many-rows kernel")
-    ap.add_argument("--sweep", choices=["config2", "config5", "types", "rows", "row_lengths", "split", "variants", "wide"], default=None)
+    ap.add_argument("--sweep", choices=["config2", "config5", "types", "rows", "row_lengths", "split", "variants", "wide", "timeline"], default=None)
     ap.add_argument("--quick", type=int, default=0, help="sweeps: keep every k-th combination")
     ap.add_argument("--out", default=None, help="file for sweep tables (default: <results folder>/<sweep>.txt)")
     args = ap.parse_args()

@@ -8,6 +8,7 @@
   split    Section 5.3's fraction experiment
   variants Section 5.4's run time and error of the variants over n
   wide     the binary64-accumulation mode beside the fp32 mode
+  timeline where the time of a call goes, from the kernel's own clock readings
 """
 from __future__ import annotations
 
@@ -449,6 +450,45 @@ def row_lengths(args, torch, np, B, W):
                                                          100 * gb / HBM_PEAK_GBPS))
 
 
+def timeline(args, torch, np, B, W):
+    """Where the time of a call goes, from the kernel's own clock readings (mfr_sum_f16_stamped): for each
+    size the call period without stamps (HIP events over back-to-back calls on rotating inputs), and, from
+    20 stamped calls, the spread of the block starts, when the first and the last block had consumed its
+    last chain, when the last partial was handed over and when the result was stored, all counted from the
+    first block's start."""
+    nmax = 1 << 30
+    x = W.generate("uniform01", nmax, W.config_seed(5))
+    arena = torch.from_numpy(x.view(np.int16)).cuda()
+    timer = Timer(torch, B)
+    heat(timer, [arena], 1 << 28)
+    tick_us = 1e3 / B.mfr_wall_clock_khz()
+    with open_out(args, "timeline.txt") as f:
+        emit(f, "# uniform[0,1), library defaults (t == NULL), inputs rotating through a 2 GiB arena; times in us")
+        emit(f, "# period = HIP events over back-to-back unstamped calls; the other columns are means over 20 stamped calls,")
+        emit(f, "# counted from the start of the first block: spread of the block starts, first / last block done with its chains,")
+        emit(f, "# last partial handed over, result stored; ideal = 2 n bytes at 8 TB/s")
+        emit(f, "# n blocks period start_spread first_streamed last_streamed last_handed_over stored ideal_8TB/s")
+        for k in (16, 18, 20, 22, 23, 24, 25, 26, 27, 28, 29, 30):
+            n = 1 << k
+            ptrs = arena_pointers(arena.data_ptr(), 2 * nmax, n)
+            grid = B.mfr_grid_for(n, ptrs[0], None)
+            steps = max(20, min(400, int(2e-2 / max(2 * n / 6e12, 4e-6))))
+            period = time_rotating(timer, ptrs, n, None, steps, 5)
+            stamps = torch.zeros(4 * grid, dtype=torch.int64, device="cuda")
+            acc = np.zeros(5)
+            reps = 20
+            for r in range(reps):
+                stamps.zero_()
+                B.mfr_sum_f16_stamped(ptrs[(r + 7) % len(ptrs)], n, timer.out.data_ptr(), None, stamps.data_ptr(), 4 * grid, timer.stream)
+                torch.cuda.synchronize()
+                st = stamps.cpu().numpy().reshape(grid, 4).astype(np.float64)
+                t0 = st[:, 0].min()
+                stored = st[:, 3].max()
+                acc += np.array([st[:, 0].max() - t0, st[:, 1].min() - t0, st[:, 1].max() - t0, st[:, 2].max() - t0, stored - t0]) * tick_us
+            acc /= reps
+            emit(f, "%d %d %.2f %.2f %.2f %.2f %.2f %.2f %.2f" % (n, grid, period * 1e6, acc[0], acc[1], acc[2], acc[3], acc[4], 2 * n / 8e6))
+
+
 def run(args):
     import numpy as np
     import torch
@@ -458,4 +498,4 @@ def run(args):
         raise SystemExit("sweeps need a GPU")
     torch.cuda.set_device(0)
     B.lib()
-    {"config2": config2, "config5": config5, "types": types, "rows": rows, "row_lengths": row_lengths, "split": split, "variants": variants, "wide": wide}[args.sweep](args, torch, np, B, W)
+    {"config2": config2, "config5": config5, "types": types, "rows": rows, "row_lengths": row_lengths, "split": split, "variants": variants, "wide": wide, "timeline": timeline}[args.sweep](args, torch, np, B, W)

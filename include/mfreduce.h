@@ -176,6 +176,23 @@ int mfr_sum_f16_ex(const mfr_half *x, size_t n, float *out,
 int mfr_sum_f16_noalloc(const mfr_half *x, size_t n, float *out, const mfr_tuning *t, hipStream_t stream);
 
 /*
+ * Diagnostic form of mfr_sum_f16_ex: the same call (Section 5.2's single pass),
+ * which also records when each block started, finished its chains, handed its
+ * partial over and (the block that does) stored the result, so that the time
+ * of a call can be split into start-up, streaming and combine.
+ *   stamps      device pointer to stamps_len 64-bit words, stamps_len >= 4 *
+ *               mfr_grid_for(n, x, t); block b writes stamps[4b .. 4b+3]:
+ *               start, last chain consumed, partial handed over, result stored
+ *               (0 for the blocks that do not store it), in ticks of the
+ *               device's constant-rate wall clock (mfr_wall_clock_khz)
+ * The readings themselves cost a few hundred nanoseconds per call.
+ */
+int mfr_sum_f16_stamped(const mfr_half *x, size_t n, float *out, const mfr_tuning *t, unsigned long long *stamps,
+                        size_t stamps_len, hipStream_t stream);
+/* Rate of that clock on the current device, in kHz. */
+int mfr_wall_clock_khz(int *khz);
+
+/*
  * The same reduction (Section 4: R(X) = sum x_i, Section 5.2 single pass) for
  * other element types; x must be aligned to its element size.  block_threads
  * == 32 is accepted for binary16 only.  chain_R counts tiles (1 KiB loads per

@@ -20,7 +20,7 @@ MFR_COMBINE_AUTO, MFR_COMBINE_SINGLE_LAUNCH, MFR_COMBINE_TWO_LAUNCHES = 0, 1, 2
 
 MFR_DTYPE_F16, MFR_DTYPE_BF16, MFR_DTYPE_F32 = 0, 1, 2
 
-EXPORTS = ("mfr_sum_f16", "mfr_sum_f16_tuned", "mfr_sum_f16_ex", "mfr_sum_f16_noalloc", "mfr_sum_bf16", "mfr_sum_f32", "mfr_sum_ex",
+EXPORTS = ("mfr_sum_f16", "mfr_sum_f16_tuned", "mfr_sum_f16_ex", "mfr_sum_f16_noalloc", "mfr_sum_f16_stamped", "mfr_wall_clock_khz", "mfr_sum_bf16", "mfr_sum_f32", "mfr_sum_ex",
            "mfr_sum_rows_ex", "mfr_sum_f16_rows", "mfr_sum_f16_recurrence", "mfr_sum_f16_f64", "mfr_sum_f16_f64_ex", "mfr_get_default_tuning", "mfr_grid_for", "mfr_plan_for",
            "mfr_plan_ex", "mfr_rows_plan", "mfr_release_scratch", "mfr_strerror", "mfr_last_hip_error", "mfr_version")
 
@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
     L.mfr_sum_f16_ex.restype = ci
     L.mfr_sum_f16_noalloc.argtypes = [vp, sz, vp, ctypes.POINTER(mfr_tuning), vp]
     L.mfr_sum_f16_noalloc.restype = ci
+    L.mfr_sum_f16_stamped.argtypes = [vp, sz, vp, ctypes.POINTER(mfr_tuning), vp, sz, vp]
+    L.mfr_sum_f16_stamped.restype = ci
+    L.mfr_wall_clock_khz.argtypes = [ctypes.POINTER(ci)]
+    L.mfr_wall_clock_khz.restype = ci
     L.mfr_sum_bf16.argtypes = [vp, sz, vp, vp]
     L.mfr_sum_bf16.restype = ci
     L.mfr_sum_f32.argtypes = [vp, sz, vp, vp]
@@ -131,6 +135,17 @@ def mfr_sum_f16_ex(x: int, n: int, out: int, t: mfr_tuning | None = None, stream
 def mfr_sum_f16_noalloc(x: int, n: int, out: int, t: mfr_tuning | None = None, stream: int = 0) -> None:
     tp = ctypes.byref(t) if t is not None else None
     _check(lib().mfr_sum_f16_noalloc(x, n, out, tp, stream), "mfr_sum_f16_noalloc")
+
+
+def mfr_sum_f16_stamped(x: int, n: int, out: int, t: mfr_tuning | None, stamps: int, stamps_len: int, stream: int = 0) -> None:
+    tp = ctypes.byref(t) if t is not None else None
+    _check(lib().mfr_sum_f16_stamped(x, n, out, tp, stamps, stamps_len, stream), "mfr_sum_f16_stamped")
+
+
+def mfr_wall_clock_khz() -> int:
+    khz = ctypes.c_int()
+    _check(lib().mfr_wall_clock_khz(ctypes.byref(khz)), "mfr_wall_clock_khz")
+    return khz.value
 
 
 def mfr_sum_bf16(x: int, n: int, out: int, stream: int = 0) -> None:

@@ -77,6 +77,7 @@ struct SumArgs {
     unsigned int *combine_slots; // single-launch combine: gridDim.x words per row, all zero between calls;
                                  // nullptr = two-launch combine
     float *out;                  // one per row
+    unsigned long long *stamps;  // diagnostic: four wall-clock readings per block (see mfr_sum_f16_stamped); normally nullptr
 };
 
 // Slot arithmetic of one array of n elements whose first element lies `head` elements past a
@@ -553,6 +554,7 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
     const unsigned long long W = (unsigned long long)gridDim.x * wpb;
     const unsigned long long w = (unsigned long long)blockIdx.x * wpb + wave;
 
+    const unsigned long long stamp_start = launch_args.stamps ? wall_clock64() : 0ull;
     SumArgs a = launch_args;             // as seen by this block's row
     const unsigned long long row = blockIdx.y;
     const char *x = (const char *)a.x + row * a.row_bytes;
@@ -587,6 +589,8 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
         }
     }
 
+    const unsigned long long stamp_streamed = a.stamps ? wall_clock64() : 0ull;
+
     // Level 2: one value per block from its wave partials, added in wave order, rounded to fp32 once.
     __shared__ WaveAcc wave_partials[kMaxWavesPerBlock];
     __shared__ double wave_partials_f64[kMaxWavesPerBlock];
@@ -601,13 +605,27 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
 
     // Level 3: all block partials of the row to one value, in index order.
     float *out = a.out + row;
+    // Diagnostic stamps of block b (row 0 only): [4b] start, [4b+1] the block's last chain consumed (read
+    // before the block's waves meet), [4b+2] partial handed over, [4b+3] result stored (0 unless it did)
+    auto stamp = [&](bool stored) {
+        if (a.stamps && threadIdx.x == 0 && row == 0) {
+            unsigned long long *st = a.stamps + 4ull * blockIdx.x;
+            const unsigned long long now = wall_clock64();
+            st[0] = stamp_start;
+            st[1] = stamp_streamed;
+            st[2] = stored ? stamp_streamed : now;
+            st[3] = stored ? now : 0ull;
+        }
+    };
     if (gridDim.x == 1) {
         if (threadIdx.x == 0) *out = block_sum;
+        stamp(true);
         return;
     }
     if (a.combine_slots == nullptr) {
         // two-launch combine: the partial is picked up by combine_kernel
         if (threadIdx.x == 0) a.partials[row * gridDim.x + blockIdx.x] = block_sum;
+        stamp(false);
         return;
     }
     // Single-launch combine: every block but the last publishes its partial and is done; the block
@@ -615,10 +633,12 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
     unsigned int *slots = a.combine_slots + row * gridDim.x;
     if (blockIdx.x + 1u != gridDim.x) {
         if (threadIdx.x == 0) publish_slot(&slots[blockIdx.x], block_sum);
+        stamp(false);
         return;
     }
     const double others = gather_slots(slots, gridDim.x - 1u, wave_partials_f64);
     if (threadIdx.x == 0) *out = (float)(others + (double)block_sum);
+    stamp(true);
 }
 
 // ------------------------------------------------------------ launching ---

@@ -466,7 +466,7 @@ int fill_zero(float *out, size_t count, hipStream_t stream)
 // many-rows kernel although tin is null.
 int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row_stride, float *out,
                   const mfr_tuning *tin, hipStream_t stream, const ScratchView *fixed = nullptr,
-                  bool per_row_only = false)
+                  bool per_row_only = false, unsigned long long *stamps = nullptr, size_t stamps_len = 0)
 {
     mfr_tuning t;
     const int st = resolve_tuning(tin, dtype, &t, rows == 1 && valid_dtype(dtype) ? (unsigned long long)cols * elem_size(dtype) : 0ull);
@@ -534,6 +534,8 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     if (grid < 1) return MFR_ERR_INVALID_ARG;
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kSingleLaunchHardMax ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kSingleLaunchAutoMax);
+    if (stamps && stamps_len < 4u * (size_t)grid) return MFR_ERR_INVALID_ARG;
+    p.a.stamps = stamps;
     ScratchView s;
     std::unique_lock<std::mutex> launch_lock;      // released when this call has enqueued its last kernel
     if (grid > 1) {
@@ -772,6 +774,22 @@ int mfr_sum_f16_noalloc(const mfr_half *x, size_t n, float *out, const mfr_tunin
     const int ss = static_scratch(dev, &fixed);
     if (ss != MFR_OK) return ss;
     return sum_rows_impl(x, MFR_DTYPE_F16, 1, n, n, out, t, stream, &fixed);
+}
+
+int mfr_sum_f16_stamped(const mfr_half *x, size_t n, float *out, const mfr_tuning *t, unsigned long long *stamps,
+                        size_t stamps_len, hipStream_t stream)
+{
+    if (!stamps) return MFR_ERR_INVALID_ARG;
+    return sum_rows_impl(x, MFR_DTYPE_F16, 1, n, n, out, t, stream, nullptr, false, stamps, stamps_len);
+}
+
+int mfr_wall_clock_khz(int *khz)
+{
+    if (!khz) return MFR_ERR_INVALID_ARG;
+    int dev = 0;
+    MFR_HIP(hipGetDevice(&dev));
+    MFR_HIP(hipDeviceGetAttribute(khz, hipDeviceAttributeWallClockRate, dev));
+    return MFR_OK;
 }
 
 int mfr_sum_bf16(const uint16_t *x, size_t n, float *out, hipStream_t stream)

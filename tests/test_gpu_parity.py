@@ -583,3 +583,25 @@ def test_environment_override_reaches_the_default_entry():
     bits_default, bits_explicit, grid = [int(v) for v in fields.split(")")[1].split()]
     assert bits_default == bits_explicit            # the default entry ran the overridden geometry
     assert grid == 4 * torch.cuda.get_device_properties(0).multi_processor_count   # 64-thread blocks: four per CU
+
+
+def test_stamped_call_gives_the_same_sum_and_ordered_stamps(oracle_lib):
+    """The diagnostic entry runs the same kernels: same bits as mfr_sum_f16_ex, and per block
+    start <= chains consumed <= handed over, with exactly one block storing the result, last of all."""
+    x = W.generate("uniform_pm1", (1 << 22) + 3, 321)
+    d = DeviceInput(x, 1)
+    for t in (None, B.make_tuning(256, 3, 40), B.make_tuning(64, 1, 700, B.MFR_KERNEL_SHFL), B.make_tuning(256, 2, 1)):
+        grid = B.mfr_grid_for(d.n, d.ptr, t)
+        stamps = torch.zeros(4 * grid, dtype=torch.int64, device="cuda")
+        o = Outputs(2)
+        B.mfr_sum_f16_stamped(d.ptr, d.n, o.ptr(0), t, stamps.data_ptr(), 4 * grid, stream_handle())
+        B.mfr_sum_f16_ex(d.ptr, d.n, o.ptr(1), t, stream_handle())
+        r = o.get()
+        assert r[0] == r[1]
+        st = stamps.cpu().numpy().reshape(grid, 4)
+        assert np.all(st[:, 0] > 0) and np.all(st[:, 0] <= st[:, 1]) and np.all(st[:, 1] <= st[:, 2])
+        storing = np.nonzero(st[:, 3])[0]
+        assert storing.tolist() == [grid - 1] and st[grid - 1, 3] >= st[:, 2].max()
+    assert B.lib().mfr_sum_f16_stamped(d.ptr, d.n, o.ptr(0), None, stamps.data_ptr(), 3, stream_handle()) == B.MFR_ERR_INVALID_ARG
+    assert B.lib().mfr_sum_f16_stamped(d.ptr, d.n, o.ptr(0), None, None, 1 << 20, stream_handle()) == B.MFR_ERR_INVALID_ARG
+    assert 1000 <= B.mfr_wall_clock_khz() <= 10_000_000
