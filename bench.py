@@ -242,6 +242,8 @@ ROWS_TRAFFIC_SHAPES = (
     # (dtype name, cols, stride, shift in elements); rows fill 512 MiB
     ("f16", 32, 32, 0), ("f16", 64, 64, 0), ("f16", 100, 100, 0), ("f16", 256, 256, 0), ("f16", 1001, 1001, 0),
     ("f16", 1024, 1024, 0), ("f16", 4096, 4096, 0), ("f16", 256, 256, 1), ("f32", 256, 256, 0),
+    # rows a few bytes longer than a whole number of steps, and 32-byte rows
+    ("f16", 257, 257, 0), ("f16", 514, 514, 0), ("f16", 1030, 1030, 0), ("f16", 16, 16, 0),
 )
 
 
@@ -257,7 +259,7 @@ def traffic_rows(args):
     x = W.generate("normal", n, W.config_seed(3))
     bufs = make_buffers(torch, np, x, 4)
     dst = torch.empty_like(bufs[0])
-    out = torch.zeros(1 << 23, dtype=torch.float32, device="cuda")
+    out = torch.zeros((1 << 24) + 8, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     shapes = []
     for name, cols, stride, shift in ROWS_TRAFFIC_SHAPES:

@@ -376,7 +376,7 @@ def rows(args, torch, np, B, W):
         dt = e0.elapsed_time(e1) * 1e-3 / args.steps
         gb = (esize * r * c + 4 * r) / dt / 1e9
         plan = B.mfr_rows_plan(bufs[0].data_ptr() + off, dtype, r, c, stride, torch.cuda.get_device_properties(0).multi_processor_count)
-        shape = "per-row" if (t is not None or plan is None) else "P%d_D%d_GF%d%s" % (plan[0], plan[1], plan[2], "" if plan[9] else "_masked")
+        shape = "per-row" if (t is not None or plan is None) else "P%d_D%d_GF%d%s" % (plan[0], plan[1], plan[2], "_tail" if plan[11] else ("" if plan[9] else "_masked"))
         emit(f, "%s %d %d %d %d %s %s %.2f %.1f %.1f %.1f" % (names[dtype], r, c, stride, shift_elems, label, shape, dt * 1e6,
                                                        r * c / dt / 1e9, gb, 100 * gb / HBM_PEAK_GBPS))
 
@@ -416,8 +416,8 @@ def row_lengths(args, torch, np, B, W):
     timer = Timer(torch, B)
     out = torch.zeros((1 << 24) + 8, dtype=torch.float32, device="cuda")
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    byte_lengths = [32, 48, 64, 96, 128, 160, 192, 200, 256, 320, 384, 400, 512, 514, 520, 600, 700, 768, 800, 900, 1000, 1022,
-                    1024, 1028, 1040, 1200, 1280, 1400, 1434, 1536, 1600, 1800, 2000, 2048, 2060, 2200, 2560, 2800, 3000,
+    byte_lengths = [32, 48, 64, 96, 128, 160, 192, 200, 256, 320, 384, 400, 512, 514, 520, 576, 580, 600, 700, 768, 800, 900, 1000, 1022,
+                    1024, 1028, 1040, 1088, 1200, 1280, 1400, 1434, 1536, 1540, 1600, 1800, 2000, 2048, 2060, 2112, 2200, 2560, 2800, 3000,
                     3072, 3500, 4000, 4096, 4104, 4608, 5000, 6000, 6144, 7000, 8192, 8208, 10000, 12288, 14000, 16384, 20000, 32768]
     heat(timer, bufs, total_bytes // 2, 0.5)         # fresh buffers start slow
     with open_out(args, "row_lengths.txt") as f:
@@ -445,7 +445,7 @@ def row_lengths(args, torch, np, B, W):
                 dt = e0.elapsed_time(e1) * 1e-3 / args.steps
                 gb = (esize * r * c + 4 * r) / dt / 1e9
                 plan = B.mfr_rows_plan(bufs[0].data_ptr(), dtype, r, c, c, cus)
-                shape = "per-row" if plan is None else "P%d_D%d_GF%d%s" % (plan[0], plan[1], plan[2], "" if plan[9] else "_masked")
+                shape = "per-row" if plan is None else "P%d_D%d_GF%d%s" % (plan[0], plan[1], plan[2], "_tail" if plan[11] else ("" if plan[9] else "_masked"))
                 emit(f, "%s %d %d %d %s %s %.2f %.1f %.1f" % (name, nbytes, c, r, shape, "-" if plan is None else plan[4], dt * 1e6, gb,
                                                          100 * gb / HBM_PEAK_GBPS))
 

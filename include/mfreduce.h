@@ -318,9 +318,13 @@ int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *t, unsigne
  *            summed one by one as single arrays (in a tile that holds rows of both
  *            kinds they are replaced by row end - 1, and not stored)
  *   plan[9]  1 if every step is unmasked    plan[10] blocks of 256 threads
+ *   plan[11] 1 if the rows end in a tail tile: plan[4] then counts the plain steps only (plan[9] is 1), and
+ *            the at most four slots of each row after them are read once per iteration, as one tile in
+ *            which lane l = 16 q + j reads slot 4 P plan[4] + q of row j of the iteration (j below
+ *            GF * 16 / P <= 16; masked and substituted like a masked step's slots)
  */
 int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row_stride, int cus,
-                  unsigned long long plan[11]);
+                  unsigned long long plan[12]);
 
 /*
  * Frees the scratch that calls on `stream` of the current device have left

@@ -192,8 +192,8 @@ def mfr_plan_ex(n: int, x_addr: int, dtype: int, t: mfr_tuning | None = None):
 
 
 def mfr_rows_plan(x_addr: int, dtype: int, rows: int, cols: int, row_stride: int, cus: int = 256):
-    """None if the per-row kernels are chosen, else the 11 plan values of the many-rows kernel."""
-    plan = (ctypes.c_ulonglong * 11)()
+    """None if the per-row kernels are chosen, else the 12 plan values of the many-rows kernel."""
+    plan = (ctypes.c_ulonglong * 12)()
     st = int(lib().mfr_rows_plan(x_addr, dtype, rows, cols, row_stride, cus, plan))
     if st < 0:
         _check(-st, "mfr_rows_plan")

@@ -391,7 +391,21 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     int lp = 0;
     while (lp < 4 && (64ull << lp) < row_bytes) ++lp;
     int d = 1, gf = 8;
-    if (rows >= kRowsTiledMinRows && row_bytes < kRowsTiledLongRowBytes) {
+    // Rows under 4 KiB that are whole 1 KiB steps (P = 16), or one 512-byte step (P = 8), and at most 64 bytes
+    // more: plain steps, and the rest of all rows of an iteration in one tail tile instead of a masked step of
+    // their own (520-byte rows 83 % against 69 %, 1040-byte rows 88 % against 74 %, 2060-byte rows 80 % against
+    // 76 %).  One plain step: eight groups side by side; several: four (as for unmasked rows of these steps).
+    // Longer rows gain nothing from it (4104-byte rows 78 % either way), nor do several 512-byte steps.
+    const unsigned long long rest16 = row_bytes % 1024ull, rest8 = row_bytes % 512ull;
+    const int tail_lp = row_bytes >= kRowsTiledLongRowBytes ? 0
+                        : (row_bytes > 1024ull && rest16 > 0 && rest16 <= 64ull) ? 4
+                        : (row_bytes > 512ull && row_bytes < 1024ull && rest8 <= 64ull) ? 3 : 0;
+    bool tail = false;
+    if (tail_lp != 0 && rows >= kRowsTiledMinRows) {
+        lp = tail_lp;
+        tail = true;
+        gf = row_bytes < 2048ull ? 8 : 4;
+    } else if (rows >= kRowsTiledMinRows && row_bytes < kRowsTiledLongRowBytes) {
         // Rows over 512 bytes: a step of P = 16 is 1 KiB, and a row that ends early in its last step
         // leaves the rest of that step's loads empty.  Rows that are whole steps of a narrower shape
         // take that shape, unmasked (768-byte rows 89 % against 69 %); rows under 2 KiB that fill
@@ -427,8 +441,8 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     const unsigned long long rows_per_iter = (unsigned long long)gf * (16ull / p);
     const unsigned long long slots_per_step = 4ull * p * (unsigned)d;
     const unsigned long long slots = (cols + per_slot - 1ull) / per_slot;
-    const unsigned long long batches = (slots + slots_per_step - 1ull) / slots_per_step;
     const unsigned long long plain_hi = (cols / per_slot) / slots_per_step;       // >= batches - 1
+    const unsigned long long batches = tail ? plain_hi : (slots + slots_per_step - 1ull) / slots_per_step;
     if (batches > 0xffffffffull) return false;
     s->log2_p = lp;
     s->tiles_per_step = d;
@@ -437,6 +451,7 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     s->batches = (unsigned int)batches;
     s->plain_hi = (unsigned int)plain_hi;
     s->all_plain = plain_hi == batches;
+    s->tail = tail;
     // Rows whose last slot would end past the array's span are not for this kernel: row r reads
     // bytes [r * stride, r * stride + 16 * slots) from x, the span ends at (rows - 1) * stride + row_bytes.
     const unsigned long long span = (rows - 1ull) * stride_bytes + row_bytes;
@@ -887,7 +902,7 @@ int mfr_plan_for(size_t n, size_t x_addr, const mfr_tuning *tin, unsigned long l
 }
 
 int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row_stride, int cus,
-                  unsigned long long plan[11])
+                  unsigned long long plan[12])
 {
     if (!valid_dtype(dtype) || !plan || cus < 1) return -MFR_ERR_INVALID_ARG;
     const unsigned esize = elem_size(dtype);
@@ -908,6 +923,7 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
     plan[8] = s.row_hi;
     plan[9] = s.all_plain ? 1ull : 0ull;
     plan[10] = grid;
+    plan[11] = s.tail ? 1ull : 0ull;
     return 1;
 }
 

@@ -35,6 +35,11 @@
 // span; the few rows at the end whose last slot would reach past the span are
 // left out -- the kernel stores rows [0, row_hi) and the host sums the others
 // with the single-array kernel.
+//
+// Rows that are a whole number of steps and at most four slots more (P = 8 or 16) do not pay a masked step for
+// those few bytes: after the row's plain steps ONE further tile takes the rest of all rows of the iteration at
+// once, with every column a row of its own (lane l = 16 q + j reads slot q of the rest of row j), and one more
+// MFMA (eq. MMA1 again) leaves each row's rest in its column; the storing lanes fetch it across lanes.
 #pragma once
 #include "mfr_kernels.hpp"
 
@@ -47,7 +52,7 @@ struct RowsArgs {
     unsigned long long stride_bytes;
     unsigned long long iters;        // ceil(rows / rows per iteration)
     unsigned long long row_hi;       // rows [0, row_hi) are summed here: all their slots lie inside the span
-    unsigned int batches;            // steps per row
+    unsigned int batches;            // steps per row (TAIL: the plain steps; the rest of the row is the tail tile)
     unsigned int plain_hi;           // steps [0, plain_hi) consist of whole in-row slots; plain_hi >= batches - 1
     float *out;
 };
@@ -97,11 +102,14 @@ __device__ __forceinline__ float fold_columns(float v)
 
 // DT: element type.  LP: log2 P.  D: tiles of a row per step.  GF: groups side by side.
 // ALLPLAIN: every step consists of whole in-row slots (cols is a multiple of the elements per step).
-// NT: non-temporal loads and stores.
-template <int DT, int LP, int D, int GF, bool ALLPLAIN, bool NT>
+// NT: non-temporal loads and stores.  TAIL: every step is plain and up to four more slots of each row go
+// through the tail tile (P >= 8, D == 1, so that an iteration has at most 16 rows).
+template <int DT, int LP, int D, int GF, bool ALLPLAIN, bool NT, bool TAIL = false>
 __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 {
+    static_assert(!TAIL || (ALLPLAIN && D == 1 && LP >= 3), "the tail tile serves plain steps of P >= 8");
     constexpr unsigned P = 1u << LP, RPT = 16u / P;
+    constexpr unsigned RPI = (unsigned)GF * RPT;          // rows per iteration
     constexpr long long E = (long long)ElemTraits<DT>::per_slot;
     const unsigned lane = threadIdx.x & 63u;
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -127,6 +135,24 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
         }
     }
 
+    // TAIL: this lane's slot of the tail tile is slot q of the rest of row j of the iteration (lanes with
+    // j >= RPI carry nothing): its byte offset in the row and the mask of the elements inside the row, as for
+    // a masked step.
+    unsigned long long tail_off = 0ull;
+    uint4v tail_keep = {0u, 0u, 0u, 0u};
+    if constexpr (TAIL) {
+        const unsigned long long s = 4ull * P * a.batches + q;
+        long long left = (long long)a.cols - E * (long long)s;
+        left = (left < 0 || j >= RPI) ? 0 : (left > E ? E : left);
+        tail_off = left > 0 ? 16ull * s : 0ull;
+        tail_keep = keep_first<DT>((int)left);
+    }
+    auto tail_row_offset = [&](unsigned long long it) {
+        unsigned long long r = it * (unsigned long long)RPI + (j < RPI ? j : 0u);
+        r = r < a.row_hi ? r : a.row_hi - 1ull;
+        return r * a.stride_bytes;
+    };
+
     // Byte offsets from x of this lane's rows in the GF groups of iteration `it`.  An iteration that
     // lies wholly below row_hi needs one scalar product and an add per group; the last one replaces
     // rows from row_hi on by row row_hi - 1 (their sums are not stored).
@@ -149,7 +175,7 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 
     // Loads of one step.  The address of a slot is chosen by a select, not by a branch, so that the
     // stream of loads does not depend on control flow.
-    auto issue = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D]) {
+    auto issue = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], uint4v &vt) {
         const bool plain = is_plain(cb);
         unsigned long long off[GF];
         row_offsets(it, off);
@@ -163,13 +189,15 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
                 v[u][d] = load_slot_at<NT>(row + rel);
             }
         }
+        // the tail tile is loaded with every step (no branch around a load); only the last step uses it
+        if constexpr (TAIL) vt = load_slot_at<NT>(a.x + tail_row_offset(it) + tail_off);
     };
 
     float4v acc[GF];                                                 // C_0 = 0
 #pragma unroll
     for (int u = 0; u < GF; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    auto consume = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D]) {
+    auto consume = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], uint4v &vt) {
         if constexpr (!ALLPLAIN) {
             if (!is_plain(cb)) {
 #pragma unroll
@@ -183,6 +211,11 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 #pragma unroll
             for (int d = 0; d < D; ++d) acc[u] = mma_ones<DT>(v[u][d], acc[u]);
         if (cb + 1u == a.batches) {
+            float4v acc_tail = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (TAIL) {
+                vt &= tail_keep;
+                acc_tail = mma_ones<DT>(vt, acc_tail);        // column j: the rest of row j of the iteration
+            }
             // Every lane of a row's P columns holds, after the fold, that row's sum for each group;
             // the lanes with part 0 and q = u mod 4 store group u.
 #pragma unroll
@@ -191,6 +224,12 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 #pragma unroll
                 for (int u = 1; u < 4 && 4 * h + u < GF; ++u) val = q == (unsigned)u ? acc[4 * h + u].x : val;
                 val = fold_columns<LP>(val);
+                if constexpr (TAIL) {
+                    // the row this lane stores is row (4 h + q) RPT + row_local of the iteration: its rest sits in
+                    // that column of the tail accumulator (every 16-lane row of the wave holds a copy)
+                    const unsigned column = ((4u * (unsigned)h + q) * RPT + row_local) & 15u;
+                    val += __shfl(acc_tail.x, (int)((lane & 48u) | column), 64);
+                }
                 const unsigned long long r = (it * GF + 4u * h + q) * RPT + row_local;
                 if (part == 0u && 4u * h + q < (unsigned)GF && r < a.row_hi) {
                     // a store instruction covers 64 / P rows; streaming stores pay only for whole 128-byte lines
@@ -212,30 +251,40 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
         if (++cb == a.batches) { cb = 0u; it += W; }
     };
     uint4v v0[GF][D], v1[GF][D];
+    uint4v vt0 = {0u, 0u, 0u, 0u}, vt1 = {0u, 0u, 0u, 0u};
     unsigned long long it0 = w, it1 = w;
     unsigned cb0 = 0u, cb1 = 0u;
     unsigned long long k = 0;                   // step held in v0
-    issue(it0, cb0, v0);
+    issue(it0, cb0, v0, vt0);
     while (k + 2ull < steps) {
         it1 = it0; cb1 = cb0; advance(it1, cb1);
-        issue(it1, cb1, v1);
+        issue(it1, cb1, v1, vt1);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it0, cb0, v0);
+        consume(it0, cb0, v0, vt0);
         it0 = it1; cb0 = cb1; advance(it0, cb0);
-        issue(it0, cb0, v0);
+        issue(it0, cb0, v0, vt0);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it1, cb1, v1);
+        consume(it1, cb1, v1, vt1);
         k += 2ull;
     }
     if (k + 1ull < steps) {
         it1 = it0; cb1 = cb0; advance(it1, cb1);
-        issue(it1, cb1, v1);
+        issue(it1, cb1, v1, vt1);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it0, cb0, v0);
-        consume(it1, cb1, v1);
+        consume(it0, cb0, v0, vt0);
+        consume(it1, cb1, v1, vt1);
     } else {
-        consume(it0, cb0, v0);
+        consume(it0, cb0, v0, vt0);
     }
+}
+
+template <int DT, int LP, int GF>
+static hipError_t launch_tail(const RowsArgs &a, unsigned grid, bool nt, hipStream_t stream)
+{
+    const dim3 g(grid), b(256);
+    if (nt) hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, 1, GF, true, true, true>), g, b, 0, stream, a);
+    else hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, 1, GF, true, false, true>), g, b, 0, stream, a);
+    return hipGetLastError();
 }
 
 template <int DT, int LP, int D, int GF>
@@ -270,6 +319,15 @@ hipError_t launch_rows_tiled_dt(const void *x, unsigned long long rows, unsigned
     a.plain_hi = s.plain_hi;
     a.out = out;
     const int key = s.log2_p * 100 + s.tiles_per_step * 10 + s.groups;
+    if (s.tail) {
+        switch (key) {
+        case 314: return launch_tail<DT, 3, 4>(a, grid, nt, stream);
+        case 318: return launch_tail<DT, 3, 8>(a, grid, nt, stream);
+        case 414: return launch_tail<DT, 4, 4>(a, grid, nt, stream);
+        case 418: return launch_tail<DT, 4, 8>(a, grid, nt, stream);
+        default: return hipErrorInvalidValue;
+        }
+    }
     switch (key) {
     case 14: return launch_cfg<DT, 0, 1, 4>(a, grid, s.all_plain, nt, stream);
     case 114: return launch_cfg<DT, 1, 1, 4>(a, grid, s.all_plain, nt, stream);

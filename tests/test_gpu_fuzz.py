@@ -30,6 +30,8 @@ def random_tuning(rng, dtype):
 
 
 def test_random_geometries_on_exact_inputs():
+    """Expected values come from numpy's binary64 prefix sums of small integers: every partial sum is an
+    integer below 2^24, exact in binary64 and binary32 alike, so it is the number the oracle returns too."""
     rng = np.random.default_rng(20010558)
     pool = W.small_integers((1 << 21) + 64, seed=12, lo=-6, hi=6)
     pool64 = pool.astype(np.float64)
@@ -57,6 +59,7 @@ def test_random_geometries_on_exact_inputs():
 
 
 def test_random_row_shapes_on_exact_inputs():
+    """As above: integer-valued rows, numpy's binary64 row sums are the exact sums."""
     rng = np.random.default_rng(5585)
     pool = W.small_integers((1 << 22) + 4096, seed=13, lo=-3, hi=3)
     dev = torch.from_numpy(pool.view(np.int16)).cuda()

@@ -102,10 +102,14 @@ MIXED_PHASE_CASES = [(33, 1001, 1001, 0), (100, 37, 39, 1), (1000, 5, 5, 0), (40
 @pytest.mark.parametrize("dtype", [F16, BF16, F32])
 @pytest.mark.parametrize("rows,cols,stride,shift", INT_CASES)
 def test_integer_rows_bit_exact(dtype, rows, cols, stride, shift, oracle_lib):
+    """Expected values are numpy's binary64 row sums of small integers: every row sum is an integer far
+    below 2^24, so numpy's sum, the oracle's and any other correct sum are the same number (the first
+    row is also checked against the oracle itself)."""
     vals = W.small_integers(rows * cols, seed=rows * 31 + cols, lo=-4, hi=4).astype(np.float32).reshape(rows, cols)
     inp = RowsInput(dtype, encode(dtype, vals).reshape(rows, cols), stride, shift)
     expect_plan(dtype, inp, rows, cols, stride)
     want = vals.astype(np.float64).sum(axis=1)
+    assert want[0] == oracle_lib.sum_f32(np.ascontiguousarray(vals[0]))[0]
     got = call(dtype, inp, rows, cols, stride).astype(np.float64)
     bad = np.nonzero(got != want)[0]
     assert bad.size == 0, (rows, cols, stride, shift, bad[:5], got[bad[:5]], want[bad[:5]])

@@ -65,6 +65,8 @@ def test_integer_inputs_exact_beyond_fp32(oracle_lib):
 
 
 def test_every_small_n_exact():
+    """Expected values are numpy's binary64 prefix sums of small integers, which are exact (integers below
+    2^53), i.e. the oracle's values."""
     full = W.small_integers(2100, seed=3)
     want = np.concatenate([[0.0], np.cumsum(full.astype(np.float64))])
     for shift in (0, 7):

@@ -9,7 +9,9 @@ test checks what the kernel relies on for memory safety and for correctness:
 * every load of the masked last step (including the substitute slot of a lane
   past the row's end) lies inside the array's span, for the rows the kernel is
   given; the rows it is not given are few,
-* rows map to store lanes one to one.
+* rows map to store lanes one to one,
+* where the rows end in a tail tile, the tile's slots cover exactly what the plain steps leave, its loads stay
+  inside the span, and each storing lane fetches the column that holds its own row.
 """
 import numpy as np
 import pytest
@@ -24,7 +26,7 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
     plan = B.mfr_rows_plan(x_addr, dtype, rows, cols, stride, cus)
     if plan is None:
         return None
-    P, D, GF, iters, batches, plain_lo, plain_hi, row_lo, row_hi, all_plain, grid = plan
+    P, D, GF, iters, batches, plain_lo, plain_hi, row_lo, row_hi, all_plain, grid, tail = plan
     es = ESIZE[dtype]
     E = 16 // es
     RPT = 16 // P
@@ -40,8 +42,12 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
     stored = np.zeros(rows, dtype=np.int32)
     assert plain_lo == 0 and row_lo == 0
     assert batches - 1 <= plain_hi <= batches          # at most the last step is masked
+    if tail:
+        assert all_plain == 1 and D == 1 and P >= 8 and rpi <= 16 and batches >= 1
+        rest = cols - batches * 4 * P * E                # elements after the plain steps
+        assert 0 < rest <= 4 * E
     assert all_plain == (1 if plain_hi == batches else 0)
-    if all_plain:
+    if all_plain and not tail:
         assert row_hi == rows
     assert 0 < row_hi <= rows and rows - row_hi <= 8    # only rows within 16 bytes of the end are left out
     for it in range(iters):
@@ -75,6 +81,25 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
             mine = (part == 0) & (q == (u & 3)) & (r_raw < row_hi)
             for ln in np.nonzero(mine)[0]:
                 stored[r_raw[ln]] += 1
+                if tail:
+                    # the column this lane fetches from the tail accumulator holds its own row
+                    h = u // 4
+                    column = ((4 * h + q[ln]) * RPT + row_local[ln]) & 15
+                    assert it * rpi + column == r_raw[ln]
+        if tail:
+            # the tail tile: lane (q, j) reads slot 4 P batches + q of row j of the iteration
+            r_raw = it * rpi + np.where(j < rpi, j, 0)
+            r = np.minimum(r_raw, row_hi - 1)
+            off = r * stride * es
+            s = 4 * P * batches + q
+            hi = np.where(j < rpi, np.clip(cols - E * s, 0, E), 0)
+            addr = np.where(hi > 0, off + 16 * s, off)
+            assert np.all(addr >= 0) and np.all(addr + 16 <= span), it
+            for ln in range(64):
+                if j[ln] >= rpi or r_raw[ln] >= row_hi:
+                    continue
+                for t in range(hi[ln]):
+                    covered[r[ln], E * s[ln] + t] += 1
     assert np.all(covered[:row_hi] == 1) and not covered[row_hi:].any()
     assert np.all(stored[:row_hi] == 1) and not stored[row_hi:].any()
     return plan
@@ -88,6 +113,9 @@ SHAPES = [
     (4, 2048, 520, 523), (0, 600, 700, 704), (4, 600, 3000, 3002), (0, 600, 2304, 2312), (2, 1100, 2000, 2001),
     (0, 2048, 384, 384), (0, 2048, 640, 640), (0, 2048, 768, 768), (0, 2048, 300, 300), (6, 2048, 350, 353), (0, 2048, 700, 704),
     (0, 1040, 33, 37), (6, 1033, 3, 3),
+    # whole steps and a few bytes: the tail tile
+    (0, 2048, 257, 257), (0, 2048, 260, 260), (2, 1100, 514, 514), (0, 1030, 1030, 1030), (4, 1027, 515, 520),
+    (0, 1100, 2052, 2052), (0, 1030, 544, 544), (0, 2048, 288, 288), (0, 2048, 289, 289), (0, 1100, 2056, 2056),
 ]
 
 
@@ -122,13 +150,17 @@ def test_rows_over_512_bytes_take_the_shape_that_wastes_least():
     assert shape(f16, 640)[:3] == (4, 1, 4) and shape(f16, 640)[4] == 5
     assert shape(f16, 768)[:3] == (8, 1, 4) and shape(f16, 768)[9] == 1      # 1536 B = 3 whole steps of 512 B
     assert shape(f32, 192)[:3] == (4, 1, 4) and shape(f32, 384)[:3] == (8, 1, 4)
-    assert shape(f16, 260)[:3] == (8, 1, 8) and shape(f16, 260)[4] == 2       # 520 B: 51 % of one 1 KiB step
-    assert shape(f16, 520)[:3] == (8, 1, 8) and shape(f16, 520)[4] == 3
+    assert shape(f16, 260)[:3] == (8, 1, 8) and shape(f16, 260)[4] == 1 and shape(f16, 260)[11] == 1   # 512 B + 8: tail tile
+    assert shape(f16, 520)[:3] == (16, 1, 8) and shape(f16, 520)[4] == 1 and shape(f16, 520)[11] == 1  # 1024 B + 16
+    assert shape(f16, 545)[:3] == (8, 1, 8) and shape(f16, 545)[4] == 3 and shape(f16, 545)[11] == 0   # 1090 B: 53 % of two 1 KiB steps
+    assert shape(f16, 544)[11] == 1 and shape(f16, 288)[11] == 1 and shape(f16, 289)[11] == 0   # at most 64 bytes after the steps
     # a masked row of P = 16: eight groups when one step, or when under 80 % of the steps is filled
     assert shape(f16, 300)[:3] == (16, 1, 8) and shape(f16, 400)[:3] == (16, 1, 8) and shape(f16, 511)[:3] == (16, 1, 8)
-    assert shape(f16, 800)[:3] == (16, 1, 8) and shape(f16, 1100)[:3] == (16, 1, 8)
+    assert shape(f16, 800)[:3] == (16, 1, 8) and shape(f16, 800)[11] == 0 and shape(f16, 1100)[:3] == (16, 1, 8)
     assert shape(f16, 900)[:3] == (16, 1, 4) and shape(f16, 1000)[:3] == (16, 1, 4) and shape(f16, 2000)[:3] == (16, 1, 4)
-    assert shape(f16, 1030)[:3] == (16, 1, 8)                                 # over 2 KiB: P = 16
+    assert shape(f16, 1030)[:3] == (16, 1, 4) and shape(f16, 1030)[11] == 1   # 2048 B + 12: P = 16, two plain steps, tail tile
+    assert shape(f16, 2052)[11] == 0                                          # from 4 KiB on: no tail tile
+    assert shape(f16, 1100)[11] == 0
     assert shape(f16, 512)[:3] == (16, 1, 4) and shape(f16, 1024)[:3] == (16, 1, 4) and shape(f16, 1536)[:3] == (16, 1, 4)
 
 
@@ -157,7 +189,7 @@ def test_choice_between_kernels():
 
 
 def test_invalid_arguments():
-    plan = (B.ctypes.c_ulonglong * 11)()
+    plan = (B.ctypes.c_ulonglong * 12)()
     L = B.lib()
     assert L.mfr_rows_plan(1 << 20, 9, 4096, 64, 64, 256, plan) == -B.MFR_ERR_INVALID_ARG
     assert L.mfr_rows_plan((1 << 20) + 1, B.MFR_DTYPE_F16, 4096, 64, 64, 256, plan) == -B.MFR_ERR_INVALID_ARG
