@@ -51,6 +51,13 @@ class Timer:
         return float(self.out[0].item())
 
 
+def rows_shape_label(plan):
+    """Name of a many-rows kernel shape as mfr_rows_plan reports it."""
+    label = "P%d_D%d_GF%d" % (plan[0], plan[1], plan[2])
+    label += "_tail" if plan[11] & 1 else ("" if plan[9] else "_masked")
+    return label + ("_shifted" if plan[11] & 2 else "")
+
+
 def oracle_reference(x):
     """(sum, sum of |x|) of the fp16 array x from the CPU oracle, blocked over the host cores: the
     checking leg of the sweeps (every timed cell is also compared with it); nothing else here uses
@@ -376,7 +383,7 @@ def rows(args, torch, np, B, W):
         dt = e0.elapsed_time(e1) * 1e-3 / args.steps
         gb = (esize * r * c + 4 * r) / dt / 1e9
         plan = B.mfr_rows_plan(bufs[0].data_ptr() + off, dtype, r, c, stride, torch.cuda.get_device_properties(0).multi_processor_count)
-        shape = "per-row" if (t is not None or plan is None) else "P%d_D%d_GF%d%s" % (plan[0], plan[1], plan[2], "_tail" if plan[11] else ("" if plan[9] else "_masked"))
+        shape = "per-row" if (t is not None or plan is None) else rows_shape_label(plan)
         emit(f, "%s %d %d %d %d %s %s %.2f %.1f %.1f %.1f" % (names[dtype], r, c, stride, shift_elems, label, shape, dt * 1e6,
                                                        r * c / dt / 1e9, gb, 100 * gb / HBM_PEAK_GBPS))
 
@@ -422,18 +429,21 @@ def row_lengths(args, torch, np, B, W):
     heat(timer, bufs, total_bytes // 2, 0.5)         # fresh buffers start slow
     with open_out(args, "row_lengths.txt") as f:
         emit(f, "# contiguous rows filling 512 MiB per call, 4 rotating buffers, library defaults; GB/s counts the input and the 4-byte results")
+        emit(f, "# f16+2: the same binary16 rows with the array starting 2 bytes off a 16-byte boundary (rows of an even number of")
+        emit(f, "# elements then all start 2 bytes off a 4-byte boundary)")
         emit(f, "# type row_bytes cols rows kernel_shape steps_per_row us GB/s pct_of_8TB/s")
-        for name, dtype, esize in (("f16", B.MFR_DTYPE_F16, 2), ("f32", B.MFR_DTYPE_F32, 4)):
-            for nbytes in byte_lengths:
+        off2_lengths = [32, 64, 128, 200, 256, 300, 400, 512, 600, 700, 768, 1000, 1024, 1032, 1500, 2048, 2100, 3000, 4000, 4096, 6000, 8192]
+        for name, dtype, esize, first_byte in (("f16", B.MFR_DTYPE_F16, 2, 0), ("f32", B.MFR_DTYPE_F32, 4, 0), ("f16+2", B.MFR_DTYPE_F16, 2, 2)):
+            for nbytes in (off2_lengths if first_byte else byte_lengths):
                 if nbytes % esize:
                     continue
                 c = nbytes // esize
-                r = total_bytes // nbytes
+                r = (total_bytes - first_byte) // nbytes
                 if r + 8 > out.numel():
                     continue
 
                 def call(i):
-                    B.mfr_sum_rows_ex(bufs[i % 4].data_ptr(), dtype, r, c, c, out.data_ptr(), None, timer.stream)
+                    B.mfr_sum_rows_ex(bufs[i % 4].data_ptr() + first_byte, dtype, r, c, c, out.data_ptr(), None, timer.stream)
                 for i in range(20):
                     call(i)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -444,8 +454,8 @@ def row_lengths(args, torch, np, B, W):
                 torch.cuda.synchronize()
                 dt = e0.elapsed_time(e1) * 1e-3 / args.steps
                 gb = (esize * r * c + 4 * r) / dt / 1e9
-                plan = B.mfr_rows_plan(bufs[0].data_ptr(), dtype, r, c, c, cus)
-                shape = "per-row" if plan is None else "P%d_D%d_GF%d%s" % (plan[0], plan[1], plan[2], "_tail" if plan[11] else ("" if plan[9] else "_masked"))
+                plan = B.mfr_rows_plan(bufs[0].data_ptr() + first_byte, dtype, r, c, c, cus)
+                shape = "per-row" if plan is None else rows_shape_label(plan)
                 emit(f, "%s %d %d %d %s %s %.2f %.1f %.1f" % (name, nbytes, c, r, shape, "-" if plan is None else plan[4], dt * 1e6, gb,
                                                          100 * gb / HBM_PEAK_GBPS))
 

@@ -221,7 +221,11 @@ int mfr_sum_ex(const void *x, int dtype, size_t n, float *out, const mfr_tuning 
  * and masks what lies past the row's end, so bytes after a row (in the gap or
  * in the next rows, inside [x, x + ((rows - 1) * row_stride + cols) * element
  * size)) may be read; nothing outside that span is (the last rows, whose final
- * slot would reach past it, are summed one by one).
+ * slot would reach past it, are summed one by one), with one exception: a row
+ * of a 16-bit type that starts 2 bytes off a 4-byte boundary is read from that
+ * boundary, and its slots are counted from there (the element before the row
+ * is discarded).  For row 0 that element lies before x, in the aligned 32-bit
+ * word that also holds x[0].
  * With explicit tuning every row is reduced exactly as a single call would
  * (Section 5.2), grid_blocks counting blocks per row and MFR_GRID_AUTO dividing
  * the persistent grid among the rows (rounded down), all rows in one launch (up
@@ -318,10 +322,14 @@ int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *t, unsigne
  *            summed one by one as single arrays (in a tile that holds rows of both
  *            kinds they are replaced by row end - 1, and not stored)
  *   plan[9]  1 if every step is unmasked    plan[10] blocks of 256 threads
- *   plan[11] 1 if the rows end in a tail tile: plan[4] then counts the plain steps only (plan[9] is 1), and
+ *   plan[11] bit 0: the rows end in a tail tile: plan[4] then counts the plain steps only (plan[9] is 1), and
  *            the at most four slots of each row after them are read once per iteration, as one tile in
  *            which lane l = 16 q + j reads slot 4 P plan[4] + q of row j of the iteration (j below
- *            GF * 16 / P <= 16; masked and substituted like a masked step's slots)
+ *            GF * 16 / P <= 16; masked and substituted like a masked step's slots).
+ *            bit 1 (16-bit types, when some row starts 2 bytes off a 4-byte boundary): such a row's slots
+ *            are counted from the element before its first one, which is dropped; plan[4] to plan[6] and
+ *            the choice of substituted slots are those of rows of cols + 1 elements, plan[5], plan[6]
+ *            count the steps that are whole for a row read either way
  */
 int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row_stride, int cus,
                   unsigned long long plan[12]);

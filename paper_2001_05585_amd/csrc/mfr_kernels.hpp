@@ -708,7 +708,8 @@ struct RowsTiledShape {
     int groups;                  // GF: tiles (of different rows) side by side
     bool all_plain;              // every step consists of whole in-row slots (cols = a whole number of steps)
     bool tail;                   // all steps plain, and up to four more slots of every row go through one tail tile
-                                 // per iteration (P >= 8, D == 1)
+                                 // per iteration (D == 1, at most 16 rows per iteration)
+    bool shift;                  // 16-bit elements: rows at odd element addresses are read from one element earlier
     unsigned long long iters;    // ceil(rows / (GF * 16 / P))
     unsigned long long row_hi;   // rows [0, row_hi) go through this kernel: their slots lie inside the array's
                                  // span; the host sums the rows after them one by one

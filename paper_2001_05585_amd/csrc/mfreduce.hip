@@ -384,51 +384,60 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     const unsigned long long row_bytes = (unsigned long long)cols * esize;
     // rows this long are streamed as well or better by a grid of blocks per row
     if (row_bytes >= kRowsTiledMaxRowBytes) return false;
-    // 128-bit loads at 2-byte alignment lose a quarter of the rate; the per-row kernels read aligned
-    // slots whatever the rows' phases, and from 4 KiB rows on that is the better deal
-    const bool two_byte_phase = esize == 2u && ((x_addr & 2u) != 0u || (stride_bytes & 2u) != 0u);
-    if (two_byte_phase && row_bytes >= kRowsTiledLongRowBytes) return false;
+    // 128-bit loads at 2-byte alignment lose a quarter of the rate or more.  When some rows of a 16-bit type
+    // start at such addresses, those rows are read from one element earlier, and every row is planned as one
+    // element longer (no row then consists of whole steps): 512-byte rows 2 bytes off a boundary 67 -> 82 %,
+    // 1000-byte ones 64 -> 83 %, 200-byte ones 53 -> 77 %, rows of 257 elements 75 -> 78 %.  From 4 KiB rows on
+    // the per-row kernels, which read aligned slots whatever the rows' phases, do as well (6000-byte rows 78 %
+    // against 81 %, 8192-byte rows 79 % against 78 %).
+    const bool shift = esize == 2u && ((x_addr & 2u) != 0u || (stride_bytes & 2u) != 0u);
+    if (shift && row_bytes >= kRowsTiledLongRowBytes) return false;
+    const unsigned long long held_bytes = row_bytes + (shift ? 2ull : 0ull);      // what a row's steps have to hold
     int lp = 0;
-    while (lp < 4 && (64ull << lp) < row_bytes) ++lp;
+    while (lp < 4 && (64ull << lp) < held_bytes) ++lp;
     int d = 1, gf = 8;
     // Rows under 4 KiB that are whole 1 KiB steps (P = 16), or one 512-byte step (P = 8), and at most 64 bytes
     // more: plain steps, and the rest of all rows of an iteration in one tail tile instead of a masked step of
     // their own (520-byte rows 83 % against 69 %, 1040-byte rows 88 % against 74 %, 2060-byte rows 80 % against
     // 76 %).  One plain step: eight groups side by side; several: four (as for unmasked rows of these steps).
     // Longer rows gain nothing from it (4104-byte rows 78 % either way), nor do several 512-byte steps.
-    const unsigned long long rest16 = row_bytes % 1024ull, rest8 = row_bytes % 512ull;
-    const int tail_lp = row_bytes >= kRowsTiledLongRowBytes ? 0
-                        : (row_bytes > 1024ull && rest16 > 0 && rest16 <= 64ull) ? 4
-                        : (row_bytes > 512ull && row_bytes < 1024ull && rest8 <= 64ull) ? 3 : 0;
+    // Shifted rows of 256 to 318 bytes take one 256-byte step (P = 4) and the tail tile (256-byte rows 2 bytes
+    // off a boundary 67 -> 79 %).
+    int tail_lp = 0;
+    if (row_bytes < kRowsTiledLongRowBytes) {
+        auto rest_after = [&](unsigned long long step) { return held_bytes - row_bytes / step * step; };
+        if (row_bytes >= 1024ull && rest_after(1024ull) > 0 && rest_after(1024ull) <= 64ull) tail_lp = 4;
+        else if (row_bytes >= 512ull && row_bytes < 1024ull && rest_after(512ull) > 0 && rest_after(512ull) <= 64ull) tail_lp = 3;
+        else if (shift && row_bytes >= 256ull && row_bytes < 512ull && rest_after(256ull) <= 64ull) tail_lp = 2;
+    }
     bool tail = false;
     if (tail_lp != 0 && rows >= kRowsTiledMinRows) {
         lp = tail_lp;
         tail = true;
-        gf = row_bytes < 2048ull ? 8 : 4;
+        gf = (tail_lp == 2 || row_bytes >= 2048ull) ? 4 : 8;
     } else if (rows >= kRowsTiledMinRows && row_bytes < kRowsTiledLongRowBytes) {
         // Rows over 512 bytes: a step of P = 16 is 1 KiB, and a row that ends early in its last step
         // leaves the rest of that step's loads empty.  Rows that are whole steps of a narrower shape
         // take that shape, unmasked (768-byte rows 89 % against 69 %); rows under 2 KiB that fill
-        // less than 55 % of their 1 KiB steps (72 % when the loads are 2-byte aligned) take P = 8, whose
-        // steps are 512 bytes.
-        const unsigned long long covered = (row_bytes + 1023ull) / 1024ull * 1024ull;      // in 1 KiB steps
-        if (row_bytes > 512 && row_bytes % 1024ull != 0) {
-            if (row_bytes % 512ull == 0) lp = 3;
-            else if (row_bytes % 256ull == 0) lp = 2;
-            else if (row_bytes < 2048 && row_bytes * 100ull < covered * (two_byte_phase ? 72ull : 55ull)) lp = 3;
+        // less than 55 % of their 1 KiB steps take P = 8, whose steps are 512 bytes.
+        const unsigned long long covered = (held_bytes + 1023ull) / 1024ull * 1024ull;      // in 1 KiB steps
+        if (held_bytes > 512 && held_bytes % 1024ull != 0) {
+            if (held_bytes % 512ull == 0) lp = 3;
+            else if (held_bytes % 256ull == 0) lp = 2;
+            else if (held_bytes < 2048 && held_bytes * 100ull < covered * 55ull) lp = 3;
         }
         // Two steps are in flight per wave: 8 KiB with four groups, 16 KiB with eight.  Unmasked rows
         // made of 256- or 512-byte steps do better with four (256-element fp16 rows 88 % against 84 %);
-        // shorter rows, masked rows (100-element rows 67 % against 78 %) and rows read with
-        // 2-byte-aligned loads with eight.
-        const bool whole_steps = row_bytes % (64ull << lp) == 0;
-        if (lp == 4 || (lp >= 2 && whole_steps && !two_byte_phase)) gf = 4;
+        // shorter rows and masked rows (100-element rows 67 % against 78 %) with eight.
+        const bool whole_steps = !shift && row_bytes % (64ull << lp) == 0;
+        if (lp == 4 || (lp >= 2 && whole_steps)) gf = 4;
         // A masked last step of P = 16 carries fewer bytes than it has loads: when it is the only step,
         // or when the row fills under 80 % of its steps, eight groups keep enough of them in flight
         // (800-byte rows 87 % against 70 %, 2200-byte rows 78 % against 72 %).
-        if (lp == 4 && !whole_steps && (covered == 1024ull || row_bytes * 100ull < covered * 80ull)) gf = 8;
+        if (lp == 4 && !whole_steps && (covered == 1024ull || held_bytes * 100ull < covered * 80ull)) gf = 8;
     } else if (lp == 4 && rows >= kRowsTiledMinLongRows) {
         d = 4; gf = 1;
+        if (shift) { d = 1; gf = 4; }            // shifted rows: one tile per step
         // A step of four tiles leaves up to 4 KiB of its last step empty.  Rows that would waste
         // more than a fifth of their steps go four side by side, 1 KiB each per step, unless their
         // stride is a multiple of 1 KiB (the four pieces would share memory channels).
@@ -440,7 +449,7 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     const unsigned long long p = 1ull << lp;
     const unsigned long long rows_per_iter = (unsigned long long)gf * (16ull / p);
     const unsigned long long slots_per_step = 4ull * p * (unsigned)d;
-    const unsigned long long slots = (cols + per_slot - 1ull) / per_slot;
+    const unsigned long long slots = (cols + (shift ? 1ull : 0ull) + per_slot - 1ull) / per_slot;
     const unsigned long long plain_hi = (cols / per_slot) / slots_per_step;       // >= batches - 1
     const unsigned long long batches = tail ? plain_hi : (slots + slots_per_step - 1ull) / slots_per_step;
     if (batches > 0xffffffffull) return false;
@@ -452,8 +461,10 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     s->plain_hi = (unsigned int)plain_hi;
     s->all_plain = plain_hi == batches;
     s->tail = tail;
+    s->shift = shift;
     // Rows whose last slot would end past the array's span are not for this kernel: row r reads
-    // bytes [r * stride, r * stride + 16 * slots) from x, the span ends at (rows - 1) * stride + row_bytes.
+    // bytes [r * stride, r * stride + 16 * slots) from x (a shifted row 2 bytes less at either end), the span
+    // ends at (rows - 1) * stride + row_bytes.
     const unsigned long long span = (rows - 1ull) * stride_bytes + row_bytes;
     unsigned long long tail_rows = 0;
     while (tail_rows < rows && (rows - 1ull - tail_rows) * stride_bytes + 16ull * slots > span) ++tail_rows;
@@ -461,6 +472,11 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     s->row_hi = rows - tail_rows;
     // 256-thread blocks: one wave per SIMD
     unsigned long long g = (unsigned long long)cus;
+    // A single masked step that is under 69 % full, and 256-byte steps with a tail tile: two blocks per CU, so
+    // that more loads are in flight while so many of them carry nothing (600-byte rows 77 -> 81 %, 32-byte rows
+    // 66 -> 77 %, binary32 rows of 580 bytes 69 -> 80 %); everywhere else a second block costs 3 to 6 points.
+    const unsigned long long step_bytes = 64ull * p * (unsigned)d;
+    if ((batches == 1ull && plain_hi == 0ull && held_bytes * 100ull < step_bytes * 69ull) || (tail && lp == 2)) g *= 2ull;
     if (g * 4ull > s->iters) g = (s->iters + 3ull) / 4ull;
     *grid = (unsigned)g;
     return true;
@@ -923,7 +939,7 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
     plan[8] = s.row_hi;
     plan[9] = s.all_plain ? 1ull : 0ull;
     plan[10] = grid;
-    plan[11] = s.tail ? 1ull : 0ull;
+    plan[11] = (s.tail ? 1ull : 0ull) | (s.shift ? 2ull : 0ull);
     return 1;
 }
 

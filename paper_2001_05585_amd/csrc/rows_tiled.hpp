@@ -40,6 +40,12 @@
 // those few bytes: after the row's plain steps ONE further tile takes the rest of all rows of the iteration at
 // once, with every column a row of its own (lane l = 16 q + j reads slot q of the rest of row j), and one more
 // MFMA (eq. MMA1 again) leaves each row's rest in its column; the storing lanes fetch it across lanes.
+//
+// 16-bit elements, rows that start 2 bytes off a 4-byte boundary: 128-bit loads at such addresses run at three
+// quarters of the rate.  The SHIFT instances count such a row's slots from the element before its first one (a
+// 4-byte boundary; the other rows' slots stay as they are), drop that element from the row's first slot, and
+// let the row end one element later in its last step or tail tile.  The element before row 0 shares the aligned
+// 32-bit word of x[0]; its value is discarded like every other masked element's.
 #pragma once
 #include "mfr_kernels.hpp"
 
@@ -103,11 +109,14 @@ __device__ __forceinline__ float fold_columns(float v)
 // DT: element type.  LP: log2 P.  D: tiles of a row per step.  GF: groups side by side.
 // ALLPLAIN: every step consists of whole in-row slots (cols is a multiple of the elements per step).
 // NT: non-temporal loads and stores.  TAIL: every step is plain and up to four more slots of each row go
-// through the tail tile (P >= 8, D == 1, so that an iteration has at most 16 rows).
-template <int DT, int LP, int D, int GF, bool ALLPLAIN, bool NT, bool TAIL = false>
+// through the tail tile (D == 1 and at most 16 rows per iteration).  SHIFT: rows at odd element addresses
+// are read from one element earlier (16-bit types, D == 1, with a masked last step or a tail tile).
+template <int DT, int LP, int D, int GF, bool ALLPLAIN, bool NT, bool TAIL = false, bool SHIFT = false>
 __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 {
-    static_assert(!TAIL || (ALLPLAIN && D == 1 && LP >= 3), "the tail tile serves plain steps of P >= 8");
+    static_assert(!TAIL || (ALLPLAIN && D == 1 && GF * (16 >> LP) <= 16), "the tail tile holds one row per column");
+    static_assert(!SHIFT || (ElemTraits<DT>::per_slot == 8 && D == 1 && (TAIL || !ALLPLAIN)),
+                  "shifted rows end one element later: they need a masked step or a tail tile");
     constexpr unsigned P = 1u << LP, RPT = 16u / P;
     constexpr unsigned RPI = (unsigned)GF * RPT;          // rows per iteration
     constexpr long long E = (long long)ElemTraits<DT>::per_slot;
@@ -122,16 +131,20 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 
     // The last step of a row, if it is not plain: byte offset of each of this lane's slots from the
     // row's start (0 for a slot wholly past the end) and the mask of the elements inside the row.
+    // SHIFT: the same for a row read from one element earlier (one element more to keep); a slot that such a
+    // row needs is loaded for every row (for the others all of it is masked away).
     unsigned long long last_off[D];
-    uint4v last_keep[D];
+    uint4v last_keep[D], last_keep_shifted[D];
     if constexpr (!ALLPLAIN) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             const unsigned long long s = s_lane + 4ull * P * ((unsigned)d + (unsigned long long)D * (a.batches - 1u));
-            long long left = (long long)a.cols - E * (long long)s;          // elements of the row from this slot on
-            left = left < 0 ? 0 : (left > E ? E : left);
-            last_off[d] = left > 0 ? 16ull * s : 0ull;
+            const long long from_here = (long long)a.cols - E * (long long)s;      // elements of the row from this slot on
+            const long long left = from_here < 0 ? 0 : (from_here > E ? E : from_here);
+            const long long left_shifted = from_here + 1 < 0 ? 0 : (from_here + 1 > E ? E : from_here + 1);
+            last_off[d] = (SHIFT ? left_shifted : left) > 0 ? 16ull * s : 0ull;
             last_keep[d] = keep_first<DT>((int)left);
+            last_keep_shifted[d] = keep_first<DT>((int)left_shifted);
         }
     }
 
@@ -139,14 +152,19 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
     // j >= RPI carry nothing): its byte offset in the row and the mask of the elements inside the row, as for
     // a masked step.
     unsigned long long tail_off = 0ull;
-    uint4v tail_keep = {0u, 0u, 0u, 0u};
+    uint4v tail_keep = {0u, 0u, 0u, 0u}, tail_keep_shifted = {0u, 0u, 0u, 0u};
     if constexpr (TAIL) {
         const unsigned long long s = 4ull * P * a.batches + q;
-        long long left = (long long)a.cols - E * (long long)s;
-        left = (left < 0 || j >= RPI) ? 0 : (left > E ? E : left);
-        tail_off = left > 0 ? 16ull * s : 0ull;
+        const long long from_here = (long long)a.cols - E * (long long)s;
+        const long long left = (from_here < 0 || j >= RPI) ? 0 : (from_here > E ? E : from_here);
+        const long long left_shifted = (from_here + 1 < 0 || j >= RPI) ? 0 : (from_here + 1 > E ? E : from_here + 1);
+        tail_off = (SHIFT ? left_shifted : left) > 0 ? 16ull * s : 0ull;
         tail_keep = keep_first<DT>((int)left);
+        tail_keep_shifted = keep_first<DT>((int)left_shifted);
     }
+    // SHIFT: 1 for a row whose first element lies 2 bytes past a 4-byte boundary (byte offset `off` from x)
+    const unsigned x_low = (unsigned)(unsigned long long)a.x;
+    auto odd_start = [&](unsigned long long off) { return SHIFT ? (((unsigned)off + x_low) >> 1) & 1u : 0u; };
     auto tail_row_offset = [&](unsigned long long it) {
         unsigned long long r = it * (unsigned long long)RPI + (j < RPI ? j : 0u);
         r = r < a.row_hi ? r : a.row_hi - 1ull;
@@ -175,13 +193,18 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 
     // Loads of one step.  The address of a slot is chosen by a select, not by a branch, so that the
     // stream of loads does not depend on control flow.
-    auto issue = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], uint4v &vt) {
+    // `shifted` gets bit u set if this lane's row of group u is read from one element earlier, bit 31 for its
+    // row of the tail tile.
+    auto issue = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], uint4v &vt, unsigned &shifted) {
         const bool plain = is_plain(cb);
         unsigned long long off[GF];
         row_offsets(it, off);
+        shifted = 0u;
 #pragma unroll
         for (int u = 0; u < GF; ++u) {
-            const char *row = a.x + off[u];
+            const unsigned odd = odd_start(off[u]);
+            shifted |= odd << u;
+            const char *row = a.x + off[u] - 2u * odd;
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 unsigned long long rel = 16ull * (s_lane + 4ull * P * ((unsigned)d + (unsigned long long)D * cb));
@@ -190,20 +213,35 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
             }
         }
         // the tail tile is loaded with every step (no branch around a load); only the last step uses it
-        if constexpr (TAIL) vt = load_slot_at<NT>(a.x + tail_row_offset(it) + tail_off);
+        if constexpr (TAIL) {
+            const unsigned long long off_t = tail_row_offset(it);
+            const unsigned odd = odd_start(off_t);
+            shifted |= odd << 31;
+            vt = load_slot_at<NT>(a.x + off_t - 2u * odd + tail_off);
+        }
     };
 
     float4v acc[GF];                                                 // C_0 = 0
 #pragma unroll
     for (int u = 0; u < GF; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    auto consume = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], uint4v &vt) {
+    auto consume = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], uint4v &vt, unsigned shifted) {
+        if constexpr (SHIFT) {
+            // a shifted row's first slot begins with the element before the row (a select in every step: a
+            // branch here makes the compiler wait for all loads in flight)
+            const bool first_slot = cb == 0u && s_lane == 0u;
+#pragma unroll
+            for (int u = 0; u < GF; ++u) v[u][0].x &= (first_slot && ((shifted >> u) & 1u) != 0u) ? 0xffff0000u : 0xffffffffu;
+        }
         if constexpr (!ALLPLAIN) {
             if (!is_plain(cb)) {
 #pragma unroll
                 for (int u = 0; u < GF; ++u)
 #pragma unroll
-                    for (int d = 0; d < D; ++d) v[u][d] &= last_keep[d];
+                    for (int d = 0; d < D; ++d) {
+                        if constexpr (SHIFT) v[u][d] &= ((shifted >> u) & 1u) != 0u ? last_keep_shifted[d] : last_keep[d];
+                        else v[u][d] &= last_keep[d];
+                    }
             }
         }
 #pragma unroll
@@ -213,7 +251,8 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
         if (cb + 1u == a.batches) {
             float4v acc_tail = {0.f, 0.f, 0.f, 0.f};
             if constexpr (TAIL) {
-                vt &= tail_keep;
+                if constexpr (SHIFT) vt &= (shifted >> 31) != 0u ? tail_keep_shifted : tail_keep;
+                else vt &= tail_keep;
                 acc_tail = mma_ones<DT>(vt, acc_tail);        // column j: the rest of row j of the iteration
             }
             // Every lane of a row's P columns holds, after the fold, that row's sum for each group;
@@ -252,53 +291,44 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
     };
     uint4v v0[GF][D], v1[GF][D];
     uint4v vt0 = {0u, 0u, 0u, 0u}, vt1 = {0u, 0u, 0u, 0u};
+    unsigned sh0 = 0u, sh1 = 0u;
     unsigned long long it0 = w, it1 = w;
     unsigned cb0 = 0u, cb1 = 0u;
     unsigned long long k = 0;                   // step held in v0
-    issue(it0, cb0, v0, vt0);
+    issue(it0, cb0, v0, vt0, sh0);
     while (k + 2ull < steps) {
         it1 = it0; cb1 = cb0; advance(it1, cb1);
-        issue(it1, cb1, v1, vt1);
+        issue(it1, cb1, v1, vt1, sh1);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it0, cb0, v0, vt0);
+        consume(it0, cb0, v0, vt0, sh0);
         it0 = it1; cb0 = cb1; advance(it0, cb0);
-        issue(it0, cb0, v0, vt0);
+        issue(it0, cb0, v0, vt0, sh0);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it1, cb1, v1, vt1);
+        consume(it1, cb1, v1, vt1, sh1);
         k += 2ull;
     }
     if (k + 1ull < steps) {
         it1 = it0; cb1 = cb0; advance(it1, cb1);
-        issue(it1, cb1, v1, vt1);
+        issue(it1, cb1, v1, vt1, sh1);
         __builtin_amdgcn_sched_barrier(0);
-        consume(it0, cb0, v0, vt0);
-        consume(it1, cb1, v1, vt1);
+        consume(it0, cb0, v0, vt0, sh0);
+        consume(it1, cb1, v1, vt1, sh1);
     } else {
-        consume(it0, cb0, v0, vt0);
+        consume(it0, cb0, v0, vt0, sh0);
     }
 }
 
-template <int DT, int LP, int GF>
-static hipError_t launch_tail(const RowsArgs &a, unsigned grid, bool nt, hipStream_t stream)
+template <int DT, int LP, int D, int GF, bool ALLPLAIN, bool TAIL, bool SHIFT>
+static hipError_t launch_instance(const RowsArgs &a, unsigned grid, bool nt, hipStream_t stream)
 {
-    const dim3 g(grid), b(256);
-    if (nt) hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, 1, GF, true, true, true>), g, b, 0, stream, a);
-    else hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, 1, GF, true, false, true>), g, b, 0, stream, a);
-    return hipGetLastError();
-}
-
-template <int DT, int LP, int D, int GF>
-static hipError_t launch_cfg(const RowsArgs &a, unsigned grid, bool all_plain, bool nt, hipStream_t stream)
-{
-    const dim3 g(grid), b(256);
-    if (all_plain) {
-        if (nt) hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, D, GF, true, true>), g, b, 0, stream, a);
-        else hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, D, GF, true, false>), g, b, 0, stream, a);
+    if constexpr (SHIFT && ElemTraits<DT>::per_slot != 8) {
+        return hipErrorInvalidValue;                     // only 16-bit rows can start 2 bytes off a 4-byte boundary
     } else {
-        if (nt) hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, D, GF, false, true>), g, b, 0, stream, a);
-        else hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, D, GF, false, false>), g, b, 0, stream, a);
+        const dim3 g(grid), b(256);
+        if (nt) hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, D, GF, ALLPLAIN, true, TAIL, SHIFT>), g, b, 0, stream, a);
+        else hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, D, GF, ALLPLAIN, false, TAIL, SHIFT>), g, b, 0, stream, a);
+        return hipGetLastError();
     }
-    return hipGetLastError();
 }
 
 // Fills in the kernel arguments and launches the instance for the shape.
@@ -318,28 +348,58 @@ hipError_t launch_rows_tiled_dt(const void *x, unsigned long long rows, unsigned
     a.batches = s.batches;
     a.plain_hi = s.plain_hi;
     a.out = out;
+    // The instances are those the host's choice of shape can ask for: eight groups for 64- and 128-byte steps
+    // and for masked steps, four for unmasked steps of 256 bytes and more and for rows of several 1 KiB steps.
     const int key = s.log2_p * 100 + s.tiles_per_step * 10 + s.groups;
     if (s.tail) {
+        if (!s.all_plain) return hipErrorInvalidValue;
+        if (s.shift) {
+            switch (key) {
+            case 214: return launch_instance<DT, 2, 1, 4, true, true, true>(a, grid, nt, stream);
+            case 318: return launch_instance<DT, 3, 1, 8, true, true, true>(a, grid, nt, stream);
+            case 414: return launch_instance<DT, 4, 1, 4, true, true, true>(a, grid, nt, stream);
+            case 418: return launch_instance<DT, 4, 1, 8, true, true, true>(a, grid, nt, stream);
+            default: return hipErrorInvalidValue;
+            }
+        }
         switch (key) {
-        case 314: return launch_tail<DT, 3, 4>(a, grid, nt, stream);
-        case 318: return launch_tail<DT, 3, 8>(a, grid, nt, stream);
-        case 414: return launch_tail<DT, 4, 4>(a, grid, nt, stream);
-        case 418: return launch_tail<DT, 4, 8>(a, grid, nt, stream);
+        case 318: return launch_instance<DT, 3, 1, 8, true, true, false>(a, grid, nt, stream);
+        case 414: return launch_instance<DT, 4, 1, 4, true, true, false>(a, grid, nt, stream);
+        case 418: return launch_instance<DT, 4, 1, 8, true, true, false>(a, grid, nt, stream);
+        default: return hipErrorInvalidValue;
+        }
+    }
+    if (s.shift) {
+        if (s.all_plain) return hipErrorInvalidValue;
+        switch (key) {
+        case 18: return launch_instance<DT, 0, 1, 8, false, false, true>(a, grid, nt, stream);
+        case 118: return launch_instance<DT, 1, 1, 8, false, false, true>(a, grid, nt, stream);
+        case 218: return launch_instance<DT, 2, 1, 8, false, false, true>(a, grid, nt, stream);
+        case 318: return launch_instance<DT, 3, 1, 8, false, false, true>(a, grid, nt, stream);
+        case 414: return launch_instance<DT, 4, 1, 4, false, false, true>(a, grid, nt, stream);
+        case 418: return launch_instance<DT, 4, 1, 8, false, false, true>(a, grid, nt, stream);
+        default: return hipErrorInvalidValue;
+        }
+    }
+    if (s.all_plain) {
+        switch (key) {
+        case 18: return launch_instance<DT, 0, 1, 8, true, false, false>(a, grid, nt, stream);
+        case 118: return launch_instance<DT, 1, 1, 8, true, false, false>(a, grid, nt, stream);
+        case 214: return launch_instance<DT, 2, 1, 4, true, false, false>(a, grid, nt, stream);
+        case 314: return launch_instance<DT, 3, 1, 4, true, false, false>(a, grid, nt, stream);
+        case 414: return launch_instance<DT, 4, 1, 4, true, false, false>(a, grid, nt, stream);
+        case 441: return launch_instance<DT, 4, 4, 1, true, false, false>(a, grid, nt, stream);
         default: return hipErrorInvalidValue;
         }
     }
     switch (key) {
-    case 14: return launch_cfg<DT, 0, 1, 4>(a, grid, s.all_plain, nt, stream);
-    case 114: return launch_cfg<DT, 1, 1, 4>(a, grid, s.all_plain, nt, stream);
-    case 214: return launch_cfg<DT, 2, 1, 4>(a, grid, s.all_plain, nt, stream);
-    case 314: return launch_cfg<DT, 3, 1, 4>(a, grid, s.all_plain, nt, stream);
-    case 18: return launch_cfg<DT, 0, 1, 8>(a, grid, s.all_plain, nt, stream);
-    case 118: return launch_cfg<DT, 1, 1, 8>(a, grid, s.all_plain, nt, stream);
-    case 218: return launch_cfg<DT, 2, 1, 8>(a, grid, s.all_plain, nt, stream);
-    case 318: return launch_cfg<DT, 3, 1, 8>(a, grid, s.all_plain, nt, stream);
-    case 414: return launch_cfg<DT, 4, 1, 4>(a, grid, s.all_plain, nt, stream);
-    case 418: return launch_cfg<DT, 4, 1, 8>(a, grid, s.all_plain, nt, stream);
-    case 441: return launch_cfg<DT, 4, 4, 1>(a, grid, s.all_plain, nt, stream);
+    case 18: return launch_instance<DT, 0, 1, 8, false, false, false>(a, grid, nt, stream);
+    case 118: return launch_instance<DT, 1, 1, 8, false, false, false>(a, grid, nt, stream);
+    case 218: return launch_instance<DT, 2, 1, 8, false, false, false>(a, grid, nt, stream);
+    case 318: return launch_instance<DT, 3, 1, 8, false, false, false>(a, grid, nt, stream);
+    case 414: return launch_instance<DT, 4, 1, 4, false, false, false>(a, grid, nt, stream);
+    case 418: return launch_instance<DT, 4, 1, 8, false, false, false>(a, grid, nt, stream);
+    case 441: return launch_instance<DT, 4, 4, 1, false, false, false>(a, grid, nt, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -92,6 +92,10 @@ INT_CASES = [
     (2048, 300, 300, 0), (2049, 192, 192, 0),                                        # rows over 512 bytes in narrower shapes
     (2048, 257, 257, 0), (2048, 514, 514, 0), (2048, 1030, 1030, 0), (2048, 260, 260, 0),   # whole steps and a few bytes
     (1100, 257, 257, 1), (1100, 129, 129, 0), (1027, 515, 515, 0),
+    # 16-bit rows 2 bytes off a 4-byte boundary, all of them or every other one: read from one element earlier
+    (4096, 1, 1, 0), (4096, 32, 32, 1), (4096, 64, 64, 1), (4096, 128, 128, 1), (4096, 160, 160, 1), (4096, 256, 256, 1),
+    (700, 256, 256, 1), (2048, 1024, 1024, 1), (2048, 288, 288, 1), (2048, 512, 512, 1), (2048, 1025, 1025, 0),
+    (2048, 513, 513, 0), (2048, 150, 150, 3), (3000, 97, 97, 0), (1031, 1500, 1500, 5), (4096, 16, 16, 7),
 ]
 
 # few rows whose 16-byte phases differ: the per-row kernels, every block doing the slot arithmetic of its own row
@@ -153,18 +157,25 @@ def test_few_rows_of_differing_phase_bit_exact(dtype, rows, cols, stride, shift)
 
 
 def test_shapes_reach_every_kernel_shape():
+    """The bit-exact cases above go through every instance of the many-rows kernel that the library can choose:
+    (P, D, GF, unmasked, tail tile and shifted-rows flags)."""
     seen = set()
     for dtype in (F16, F32):
         for rows, cols, stride, shift in INT_CASES:
             esize = 2 if dtype != F32 else 4
             plan = B.mfr_rows_plan((1 << 20) + shift * esize, dtype, rows, cols, stride, 256)
             assert plan is not None
-            seen.add((plan[0], plan[1], plan[2], plan[9]))
-    for p, d, gf in ((1, 1, 8), (2, 1, 8), (16, 1, 4), (16, 4, 1)):
-        assert (p, d, gf, 0) in seen, (p, d, gf)
-        assert (p, d, gf, 1) in seen, (p, d, gf)
-    # 256- and 512-byte steps: eight groups side by side when masked, four when not
-    assert (4, 1, 8, 0) in seen and (8, 1, 8, 0) in seen and (4, 1, 4, 1) in seen and (8, 1, 4, 1) in seen
+            seen.add((plan[0], plan[1], plan[2], plan[9], plan[11]))
+    instances = {
+        # unmasked, masked
+        (1, 1, 8, 1, 0), (2, 1, 8, 1, 0), (4, 1, 4, 1, 0), (8, 1, 4, 1, 0), (16, 1, 4, 1, 0), (16, 4, 1, 1, 0),
+        (1, 1, 8, 0, 0), (2, 1, 8, 0, 0), (4, 1, 8, 0, 0), (8, 1, 8, 0, 0), (16, 1, 4, 0, 0), (16, 1, 8, 0, 0), (16, 4, 1, 0, 0),
+        # tail tile; shifted rows, masked; shifted rows with a tail tile
+        (8, 1, 8, 1, 1), (16, 1, 4, 1, 1), (16, 1, 8, 1, 1),
+        (1, 1, 8, 0, 2), (2, 1, 8, 0, 2), (4, 1, 8, 0, 2), (8, 1, 8, 0, 2), (16, 1, 4, 0, 2), (16, 1, 8, 0, 2),
+        (4, 1, 4, 1, 3), (8, 1, 8, 1, 3), (16, 1, 4, 1, 3), (16, 1, 8, 1, 3),
+    }
+    assert seen == instances, (sorted(instances - seen), sorted(seen - instances))
 
 
 @pytest.mark.parametrize("dtype,kind", [(F16, "normal"), (F16, "uniform01"), (BF16, "normal"), (F32, "uniform_pm1")])
@@ -203,6 +214,19 @@ def test_special_values_stay_in_their_row():
     assert got[7] == math.inf and got[8] == -math.inf and math.isnan(got[4000]) and math.isnan(got[4099])
     keep = np.ones(rows, dtype=bool); keep[[7, 8, 4000, 4099]] = False
     assert np.all(got[keep] == cols)
+    # contiguous rows of an odd number of 16-bit elements: every other row is read from the element before it,
+    # which is the last element of the row above
+    for rows, cols in ((2100, 257), (2100, 129), (3000, 33), (1100, 1025), (2100, 301)):
+        bits = encode(F16, np.ones((rows, cols), dtype=np.float32)).reshape(rows, cols).copy()
+        bits[10, cols - 1] = 0x7C00       # +Inf just before row 11
+        bits[21, cols - 1] = 0x7E00       # NaN just before row 22
+        bits[31, 0] = 0xFC00              # -Inf as a shifted row's first element
+        bits[rows - 2, cols - 1] = 0x7E00
+        inp = RowsInput(F16, bits, cols, 0)
+        got = call(F16, inp, rows, cols, cols).astype(np.float64)
+        assert got[10] == math.inf and math.isnan(got[21]) and got[31] == -math.inf and math.isnan(got[rows - 2])
+        keep = np.ones(rows, dtype=bool); keep[[10, 21, 31, rows - 2]] = False
+        assert np.all(got[keep] == cols), (rows, cols, np.nonzero(got[keep] != cols)[0][:5])
 
 
 def test_sparse_diagonals_every_column_position():

@@ -11,7 +11,9 @@ test checks what the kernel relies on for memory safety and for correctness:
   given; the rows it is not given are few,
 * rows map to store lanes one to one,
 * where the rows end in a tail tile, the tile's slots cover exactly what the plain steps leave, its loads stay
-  inside the span, and each storing lane fetches the column that holds its own row.
+  inside the span, and each storing lane fetches the column that holds its own row,
+* where rows of a 16-bit type at odd element addresses are read from one element earlier, every load starts on a
+  4-byte boundary, none starts below the aligned word that holds x[0], and the element before the row is dropped.
 """
 import numpy as np
 import pytest
@@ -26,13 +28,14 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
     plan = B.mfr_rows_plan(x_addr, dtype, rows, cols, stride, cus)
     if plan is None:
         return None
-    P, D, GF, iters, batches, plain_lo, plain_hi, row_lo, row_hi, all_plain, grid, tail = plan
+    P, D, GF, iters, batches, plain_lo, plain_hi, row_lo, row_hi, all_plain, grid, flags = plan
+    tail, shift = flags & 1, (flags >> 1) & 1
     es = ESIZE[dtype]
     E = 16 // es
     RPT = 16 // P
     rpi = GF * RPT
     assert iters == -(-rows // rpi)
-    assert 1 <= grid <= cus and grid * 4 >= min(iters, cus * 4) - 3
+    assert 1 <= grid <= 2 * cus and grid * 4 >= min(iters, cus * 4) - 3          # one block per CU, some shapes two
     span = ((rows - 1) * stride + cols) * es
     lane = np.arange(64)
     j, q = lane & 15, lane >> 4
@@ -42,10 +45,23 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
     stored = np.zeros(rows, dtype=np.int32)
     assert plain_lo == 0 and row_lo == 0
     assert batches - 1 <= plain_hi <= batches          # at most the last step is masked
+    if shift:
+        assert es == 2 and D == 1 and (tail or not all_plain)
+        assert (x_addr & 2) or ((stride * es) & 2)       # some row does start at an odd element address
     if tail:
-        assert all_plain == 1 and D == 1 and P >= 8 and rpi <= 16 and batches >= 1
-        rest = cols - batches * 4 * P * E                # elements after the plain steps
+        assert all_plain == 1 and D == 1 and rpi <= 16 and batches >= 1
+        rest = cols + shift - batches * 4 * P * E        # elements after the plain steps
         assert 0 < rest <= 4 * E
+
+    def odd_start(off):                                  # rows read from one element earlier
+        return ((x_addr + off) >> 1) & 1 if shift else np.zeros_like(off)
+
+    def check_loads(addr, odd):                          # byte offsets from x of 16-byte loads
+        assert np.all(addr + x_addr >= (x_addr & ~3)) and np.all(addr + 16 <= span)
+        if shift:
+            assert np.all((addr + x_addr) % 4 == 0)
+        else:
+            assert np.all(addr >= 0)
     assert all_plain == (1 if plain_hi == batches else 0)
     if all_plain and not tail:
         assert row_hi == rows
@@ -55,25 +71,29 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
             r_raw = (it * GF + u) * RPT + row_local
             r = np.minimum(r_raw, row_hi - 1)
             off = r * stride * es                  # byte offset of the row's first element from x
+            odd = odd_start(off)
+            base = off - 2 * odd                   # where the row's slots are counted from
             for cb in range(batches):
                 plain = cb < plain_hi
                 for d in range(D):
                     s = s_lane + 4 * P * (d + D * cb)
-                    rel = off + 16 * s
-                    e0 = E * s
+                    rel = base + 16 * s
+                    e0 = E * s - odd               # column of the slot's first element (-1: the element before the row)
+                    lo = np.where(e0 < 0, 1, 0)    # dropped from the first slot of a shifted row
                     if plain:
                         # the slot must be whole and inside the row
                         assert np.all(e0 + E <= cols), (it, u, cb, d)
-                        assert np.all(rel + 16 <= span)
+                        check_loads(rel, odd)
                         hi = np.full(64, E)
                     else:
                         hi = np.clip(cols - e0, 0, E)
-                        addr = np.where(hi > 0, rel, off)      # a slot past the end is replaced by the first slot
-                        assert np.all(addr >= 0) and np.all(addr + 16 <= span), (it, u, cb, d)
+                        hi_loaded = np.clip(cols + shift - E * s, 0, E)     # the kernel decides on the longer, shifted row
+                        addr = np.where(hi_loaded > 0, rel, base)           # a slot past the end is replaced by the first slot
+                        check_loads(addr, odd)
                     for ln in range(64):
                         if r_raw[ln] >= row_hi:
                             continue
-                        for t in range(hi[ln]):
+                        for t in range(lo[ln], hi[ln]):
                             c = e0[ln] + t
                             assert 0 <= c < cols
                             covered[r[ln], c] += 1
@@ -91,15 +111,19 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
             r_raw = it * rpi + np.where(j < rpi, j, 0)
             r = np.minimum(r_raw, row_hi - 1)
             off = r * stride * es
+            odd = odd_start(off)
+            base = off - 2 * odd
             s = 4 * P * batches + q
-            hi = np.where(j < rpi, np.clip(cols - E * s, 0, E), 0)
-            addr = np.where(hi > 0, off + 16 * s, off)
-            assert np.all(addr >= 0) and np.all(addr + 16 <= span), it
+            e0 = E * s - odd
+            hi = np.where(j < rpi, np.clip(cols - e0, 0, E), 0)
+            hi_loaded = np.where(j < rpi, np.clip(cols + shift - E * s, 0, E), 0)
+            addr = np.where(hi_loaded > 0, base + 16 * s, base)
+            check_loads(addr, odd)
             for ln in range(64):
                 if j[ln] >= rpi or r_raw[ln] >= row_hi:
                     continue
                 for t in range(hi[ln]):
-                    covered[r[ln], E * s[ln] + t] += 1
+                    covered[r[ln], e0[ln] + t] += 1
     assert np.all(covered[:row_hi] == 1) and not covered[row_hi:].any()
     assert np.all(stored[:row_hi] == 1) and not stored[row_hi:].any()
     return plan
@@ -116,6 +140,10 @@ SHAPES = [
     # whole steps and a few bytes: the tail tile
     (0, 2048, 257, 257), (0, 2048, 260, 260), (2, 1100, 514, 514), (0, 1030, 1030, 1030), (4, 1027, 515, 520),
     (0, 1100, 2052, 2052), (0, 1030, 544, 544), (0, 2048, 288, 288), (0, 2048, 289, 289), (0, 1100, 2056, 2056),
+    # 16-bit rows 2 bytes off a 4-byte boundary (all of them, or every other one): read from one element earlier
+    (2, 2048, 256, 256), (2, 2048, 128, 128), (6, 2048, 150, 150), (0, 2048, 129, 129), (2, 1100, 512, 512),
+    (0, 1100, 1025, 1025), (2, 1030, 300, 300), (2, 2048, 16, 16), (0, 2048, 17, 17), (6, 700, 1000, 1001),
+    (2, 2048, 159, 160), (0, 1040, 31, 33), (2, 1100, 1024, 1026), (0, 1100, 1055, 1055), (2, 1100, 1500, 1500),
 ]
 
 
@@ -139,8 +167,15 @@ def test_power_of_two_rows_are_unmasked_at_any_alignment():
     plan = B.mfr_rows_plan(1 << 20, B.MFR_DTYPE_F32, 4096, 64, 64, 256)
     assert plan[0] == 4 and plan[9] == 1
     # slots are counted from each row's first element: the base address and the stride do not matter
-    plan = B.mfr_rows_plan((1 << 20) + 6, B.MFR_DTYPE_F16, 4096, 64, 67, 256)
-    assert plan[0] == 2 and plan[9] == 1 and plan[8] == 4096
+    plan = B.mfr_rows_plan((1 << 20) + 4, B.MFR_DTYPE_F16, 4096, 64, 66, 256)
+    assert plan[0] == 2 and plan[9] == 1 and plan[8] == 4096 and plan[11] == 0
+    # ... unless rows of a 16-bit type start 2 bytes off a 4-byte boundary: read from that boundary, such a row
+    # is one element longer, and with it every row's plan
+    for x_addr, stride in (((1 << 20) + 6, 66), (1 << 20, 67)):
+        plan = B.mfr_rows_plan(x_addr, B.MFR_DTYPE_F16, 4096, 64, stride, 256)
+        assert plan[0] == 4 and plan[9] == 0 and plan[11] == 2
+    plan = B.mfr_rows_plan((1 << 20) + 4, B.MFR_DTYPE_F32, 4096, 64, 65, 256)
+    assert plan[9] == 1 and plan[11] == 0
 
 
 def test_rows_over_512_bytes_take_the_shape_that_wastes_least():
@@ -152,8 +187,21 @@ def test_rows_over_512_bytes_take_the_shape_that_wastes_least():
     assert shape(f32, 192)[:3] == (4, 1, 4) and shape(f32, 384)[:3] == (8, 1, 4)
     assert shape(f16, 260)[:3] == (8, 1, 8) and shape(f16, 260)[4] == 1 and shape(f16, 260)[11] == 1   # 512 B + 8: tail tile
     assert shape(f16, 520)[:3] == (16, 1, 8) and shape(f16, 520)[4] == 1 and shape(f16, 520)[11] == 1  # 1024 B + 16
-    assert shape(f16, 545)[:3] == (8, 1, 8) and shape(f16, 545)[4] == 3 and shape(f16, 545)[11] == 0   # 1090 B: 53 % of two 1 KiB steps
-    assert shape(f16, 544)[11] == 1 and shape(f16, 288)[11] == 1 and shape(f16, 289)[11] == 0   # at most 64 bytes after the steps
+    assert shape(f16, 546)[:3] == (8, 1, 8) and shape(f16, 546)[4] == 3 and shape(f16, 546)[11] == 0   # 1092 B: 53 % of two 1 KiB steps
+    assert shape(f16, 544)[11] == 1 and shape(f16, 288)[11] == 1 and shape(f16, 290)[11] == 0   # at most 64 bytes after the steps
+    # shifted rows: the element before the row counts (bit 1 of plan[11]); the tail tile (bit 0) from 256-byte rows on
+    shifted = lambda cols: B.mfr_rows_plan((1 << 20) + 2, f16, 4096, cols, cols, 256)
+    assert shifted(256)[:3] == (8, 1, 8) and shifted(256)[4] == 1 and shifted(256)[11] == 3
+    assert shifted(128)[:3] == (4, 1, 4) and shifted(128)[4] == 1 and shifted(128)[11] == 3
+    assert shifted(287)[11] == 3 and shifted(288)[11] == 2 and shape(f16, 287)[11] == 3 and shape(f16, 289)[11] == 2
+    assert shifted(1024)[:3] == (16, 1, 4) and shifted(1024)[4] == 2 and shifted(1024)[11] == 3
+    assert shifted(255)[:3] == (8, 1, 8) and shifted(255)[9] == 0 and shifted(255)[11] == 2      # 256 elements to hold: one masked step
+    # a single masked step under 69 % full, and 256-byte steps with a tail tile: two blocks per CU
+    many = lambda dt, cols, x_addr=1 << 20: B.mfr_rows_plan(x_addr, dt, 1 << 18, cols, cols, 256)
+    assert many(f16, 300)[10] == 512 and many(f16, 16)[10] == 512 and many(f32, 145)[10] == 512
+    assert many(f16, 128, (1 << 20) + 2)[10] == 512
+    assert many(f16, 400)[10] == 256 and many(f16, 24)[10] == 256 and many(f16, 600)[10] == 256
+    assert many(f16, 256, (1 << 20) + 2)[10] == 256
     # a masked row of P = 16: eight groups when one step, or when under 80 % of the steps is filled
     assert shape(f16, 300)[:3] == (16, 1, 8) and shape(f16, 400)[:3] == (16, 1, 8) and shape(f16, 511)[:3] == (16, 1, 8)
     assert shape(f16, 800)[:3] == (16, 1, 8) and shape(f16, 800)[11] == 0 and shape(f16, 1100)[:3] == (16, 1, 8)
