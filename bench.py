@@ -244,6 +244,8 @@ ROWS_TRAFFIC_SHAPES = (
     ("f16", 1024, 1024, 0), ("f16", 4096, 4096, 0), ("f16", 256, 256, 1), ("f32", 256, 256, 0),
     # rows a few bytes longer than a whole number of steps, and 32-byte rows
     ("f16", 257, 257, 0), ("f16", 514, 514, 0), ("f16", 1030, 1030, 0), ("f16", 16, 16, 0),
+    # a single masked step that is little more than half full; rows 2 bytes off a 4-byte boundary
+    ("f16", 300, 300, 0), ("f16", 500, 500, 1),
 )
 
 
