@@ -707,8 +707,8 @@ struct RowsTiledShape {
     int tiles_per_step;          // D: tiles of a row loaded together
     int groups;                  // GF: tiles (of different rows) side by side
     bool all_plain;              // every step consists of whole in-row slots (cols = a whole number of steps)
-    bool tail;                   // all steps plain, and up to four more slots of every row go through one tail tile
-                                 // per iteration (D == 1, at most 16 rows per iteration)
+    bool tail;                   // all steps plain, and up to 4 P_t more slots of every row go through tail tiles,
+    int tail_log2_p;             // in which a row has P_t = 2^tail_log2_p adjacent columns (D == 1)
     bool shift;                  // 16-bit elements: rows at odd element addresses are read from one element earlier
     unsigned long long iters;    // ceil(rows / (GF * 16 / P))
     unsigned long long row_hi;   // rows [0, row_hi) go through this kernel: their slots lie inside the array's

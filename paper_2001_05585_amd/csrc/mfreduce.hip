@@ -396,19 +396,31 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     int lp = 0;
     while (lp < 4 && (64ull << lp) < held_bytes) ++lp;
     int d = 1, gf = 8;
-    // Rows under 4 KiB that are whole 1 KiB steps (P = 16), or one 512-byte step (P = 8), and at most 64 bytes
-    // more: plain steps, and the rest of all rows of an iteration in one tail tile instead of a masked step of
-    // their own (520-byte rows 83 % against 69 %, 1040-byte rows 88 % against 74 %, 2060-byte rows 80 % against
-    // 76 %).  One plain step: eight groups side by side; several: four (as for unmasked rows of these steps).
-    // Longer rows gain nothing from it (4104-byte rows 78 % either way), nor do several 512-byte steps.
-    // Shifted rows of 256 to 318 bytes take one 256-byte step (P = 4) and the tail tile (256-byte rows 2 bytes
-    // off a boundary 67 -> 79 %).
-    int tail_lp = 0;
-    if (row_bytes < kRowsTiledLongRowBytes) {
+    // Rows under 4 KiB that are whole 1 KiB steps (P = 16), or one 512-byte step (P = 8), and at most 256 bytes
+    // more: plain steps, and the rests of all rows of an iteration in tail tiles (P_t = 1, 2 or 4 columns per row
+    // for rests of up to 64, 128, 256 bytes) instead of a masked step of their own (520-byte rows 83 % against
+    // 69 %, 1040-byte rows 88 % against 74 %, 1200-byte rows 87 % against 76 %, 2060-byte rows 80 % against 76 %,
+    // 2300-byte rows 82 % against 78 %).  One plain step: eight groups side by side; several: four (as for unmasked
+    // rows of these steps).  The tail tiles are loaded with every step, so after three steps only rests of up to
+    // 128 bytes pay (3200-byte rows 87 % against 83 %, 3300-byte rows 77 % against 78 %); rows of 4 KiB and more
+    // gain nothing (4104-byte rows 78 % either way), nor do several 512-byte steps; rows that are whole steps of a
+    // narrower shape keep that shape.  Shifted rows of 256 to 318 bytes take one 256-byte step (P = 4) and a
+    // tail tile (256-byte rows 2 bytes off a boundary 67 -> 79 %).
+    int tail_lp = 0, tail_lpt = 0;
+    if (row_bytes < kRowsTiledLongRowBytes && (shift || row_bytes % 256ull != 0)) {
         auto rest_after = [&](unsigned long long step) { return held_bytes - row_bytes / step * step; };
-        if (row_bytes >= 1024ull && rest_after(1024ull) > 0 && rest_after(1024ull) <= 64ull) tail_lp = 4;
-        else if (row_bytes >= 512ull && row_bytes < 1024ull && rest_after(512ull) > 0 && rest_after(512ull) <= 64ull) tail_lp = 3;
-        else if (shift && row_bytes >= 256ull && row_bytes < 512ull && rest_after(256ull) <= 64ull) tail_lp = 2;
+        unsigned long long rest = 0;
+        if (row_bytes >= 1024ull) {
+            rest = rest_after(1024ull);
+            if (rest > 0 && rest <= (row_bytes >= 3072ull ? 128ull : 256ull)) tail_lp = 4;
+        } else if (row_bytes >= 512ull) {
+            rest = rest_after(512ull);
+            if (rest > 0 && rest <= 256ull) tail_lp = 3;
+        } else if (shift && row_bytes >= 256ull) {
+            rest = rest_after(256ull);
+            if (rest <= 64ull) tail_lp = 2;
+        }
+        tail_lpt = rest <= 64ull ? 0 : (rest <= 128ull ? 1 : 2);
     }
     bool tail = false;
     if (tail_lp != 0 && rows >= kRowsTiledMinRows) {
@@ -418,13 +430,11 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     } else if (rows >= kRowsTiledMinRows && row_bytes < kRowsTiledLongRowBytes) {
         // Rows over 512 bytes: a step of P = 16 is 1 KiB, and a row that ends early in its last step
         // leaves the rest of that step's loads empty.  Rows that are whole steps of a narrower shape
-        // take that shape, unmasked (768-byte rows 89 % against 69 %); rows under 2 KiB that fill
-        // less than 55 % of their 1 KiB steps take P = 8, whose steps are 512 bytes.
+        // take that shape, unmasked (768-byte rows 89 % against 69 %).
         const unsigned long long covered = (held_bytes + 1023ull) / 1024ull * 1024ull;      // in 1 KiB steps
         if (held_bytes > 512 && held_bytes % 1024ull != 0) {
             if (held_bytes % 512ull == 0) lp = 3;
             else if (held_bytes % 256ull == 0) lp = 2;
-            else if (held_bytes < 2048 && held_bytes * 100ull < covered * 55ull) lp = 3;
         }
         // Two steps are in flight per wave: 8 KiB with four groups, 16 KiB with eight.  Unmasked rows
         // made of 256- or 512-byte steps do better with four (256-element fp16 rows 88 % against 84 %);
@@ -461,6 +471,7 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     s->plain_hi = (unsigned int)plain_hi;
     s->all_plain = plain_hi == batches;
     s->tail = tail;
+    s->tail_log2_p = tail ? tail_lpt : 0;
     s->shift = shift;
     // Rows whose last slot would end past the array's span are not for this kernel: row r reads
     // bytes [r * stride, r * stride + 16 * slots) from x (a shifted row 2 bytes less at either end), the span
@@ -473,8 +484,8 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     // 256-thread blocks: one wave per SIMD
     unsigned long long g = (unsigned long long)cus;
     // A single masked step that is under 69 % full, and 256-byte steps with a tail tile: two blocks per CU, so
-    // that more loads are in flight while so many of them carry nothing (600-byte rows 77 -> 81 %, 32-byte rows
-    // 66 -> 77 %, binary32 rows of 580 bytes 69 -> 80 %); everywhere else a second block costs 3 to 6 points.
+    // that more loads are in flight while so many of them carry nothing (32-byte rows 66 -> 77 %, binary32 rows
+    // of 160 bytes 72 -> 77 %, of 320 bytes 77 -> 80 %); everywhere else a second block costs 3 to 6 points.
     const unsigned long long step_bytes = 64ull * p * (unsigned)d;
     if ((batches == 1ull && plain_hi == 0ull && held_bytes * 100ull < step_bytes * 69ull) || (tail && lp == 2)) g *= 2ull;
     if (g * 4ull > s->iters) g = (s->iters + 3ull) / 4ull;
@@ -939,7 +950,7 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
     plan[8] = s.row_hi;
     plan[9] = s.all_plain ? 1ull : 0ull;
     plan[10] = grid;
-    plan[11] = (s.tail ? 1ull : 0ull) | (s.shift ? 2ull : 0ull);
+    plan[11] = (s.tail ? 1ull : 0ull) | (s.shift ? 2ull : 0ull) | ((unsigned long long)s.tail_log2_p << 2);
     return 1;
 }
 

@@ -36,10 +36,13 @@
 // left out -- the kernel stores rows [0, row_hi) and the host sums the others
 // with the single-array kernel.
 //
-// Rows that are a whole number of steps and at most four slots more (P = 8 or 16) do not pay a masked step for
-// those few bytes: after the row's plain steps ONE further tile takes the rest of all rows of the iteration at
-// once, with every column a row of its own (lane l = 16 q + j reads slot q of the rest of row j), and one more
-// MFMA (eq. MMA1 again) leaves each row's rest in its column; the storing lanes fetch it across lanes.
+// Rows that are a whole number of steps and at most 256 bytes more do not pay a masked step for those bytes:
+// after the row's plain steps, tail tiles take the rest of all rows of the iteration.  A tail tile gives P_t = 1, 2
+// or 4 adjacent columns to a row (a rest of up to 64 P_t bytes) and so holds the rests of 16 / P_t rows: lane
+// l = 16 q + j reads slot (j mod P_t) + P_t q of the rest of row j / P_t of the tile.  One more MFMA per tail tile
+// (eq. MMA1 again) and a fold over P_t columns leave each row's rest in its columns; the storing lanes fetch it
+// across lanes.  An iteration of up to 16 / P_t rows has one tail tile (possibly with unused columns), larger
+// iterations a whole number of them.
 //
 // 16-bit elements, rows that start 2 bytes off a 4-byte boundary: 128-bit loads at such addresses run at three
 // quarters of the rate.  The SHIFT instances count such a row's slots from the element before its first one (a
@@ -108,17 +111,21 @@ __device__ __forceinline__ float fold_columns(float v)
 
 // DT: element type.  LP: log2 P.  D: tiles of a row per step.  GF: groups side by side.
 // ALLPLAIN: every step consists of whole in-row slots (cols is a multiple of the elements per step).
-// NT: non-temporal loads and stores.  TAIL: every step is plain and up to four more slots of each row go
-// through the tail tile (D == 1 and at most 16 rows per iteration).  SHIFT: rows at odd element addresses
-// are read from one element earlier (16-bit types, D == 1, with a masked last step or a tail tile).
-template <int DT, int LP, int D, int GF, bool ALLPLAIN, bool NT, bool TAIL = false, bool SHIFT = false>
+// NT: non-temporal loads and stores.  LPT: -1, or log2 P_t: every step is plain and up to 4 P_t more slots of
+// each row go through tail tiles (D == 1).  SHIFT: rows at odd element addresses are read from one element
+// earlier (16-bit types, D == 1, with a masked last step or tail tiles).
+template <int DT, int LP, int D, int GF, bool ALLPLAIN, bool NT, int LPT = -1, bool SHIFT = false>
 __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 {
-    static_assert(!TAIL || (ALLPLAIN && D == 1 && GF * (16 >> LP) <= 16), "the tail tile holds one row per column");
-    static_assert(!SHIFT || (ElemTraits<DT>::per_slot == 8 && D == 1 && (TAIL || !ALLPLAIN)),
-                  "shifted rows end one element later: they need a masked step or a tail tile");
+    constexpr bool TAIL = LPT >= 0;
     constexpr unsigned P = 1u << LP, RPT = 16u / P;
     constexpr unsigned RPI = (unsigned)GF * RPT;          // rows per iteration
+    constexpr unsigned PT = TAIL ? 1u << (TAIL ? LPT : 0) : 1u, RPTT = 16u / PT;       // tail tile: columns per row, rows
+    constexpr unsigned NTT = TAIL ? (RPI * PT + 15u) / 16u : 1u;                        // tail tiles per iteration
+    static_assert(!TAIL || (ALLPLAIN && D == 1 && LPT <= 2 && (NTT == 1u || RPI * PT == NTT * 16u)),
+                  "tail tiles follow plain steps; several of them are all full");
+    static_assert(!SHIFT || (ElemTraits<DT>::per_slot == 8 && D == 1 && (TAIL || !ALLPLAIN)),
+                  "shifted rows end one element later: they need a masked step or a tail tile");
     constexpr long long E = (long long)ElemTraits<DT>::per_slot;
     const unsigned lane = threadIdx.x & 63u;
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -148,16 +155,18 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
         }
     }
 
-    // TAIL: this lane's slot of the tail tile is slot q of the rest of row j of the iteration (lanes with
-    // j >= RPI carry nothing): its byte offset in the row and the mask of the elements inside the row, as for
-    // a masked step.
+    // TAIL: this lane's slot in a tail tile is slot (j mod P_t) + P_t q of the rest of row j / P_t of the tile
+    // (a lone tail tile can have columns past the iteration's rows: those lanes carry nothing): its byte offset
+    // in the row and the mask of the elements inside the row, as for a masked step.
+    const unsigned row_t = j / PT;                 // this lane's row in a tail tile
+    const bool in_tail = row_t < RPI;              // only a lone tail tile has unused columns
     unsigned long long tail_off = 0ull;
     uint4v tail_keep = {0u, 0u, 0u, 0u}, tail_keep_shifted = {0u, 0u, 0u, 0u};
     if constexpr (TAIL) {
-        const unsigned long long s = 4ull * P * a.batches + q;
+        const unsigned long long s = 4ull * P * a.batches + (j & (PT - 1u)) + PT * q;
         const long long from_here = (long long)a.cols - E * (long long)s;
-        const long long left = (from_here < 0 || j >= RPI) ? 0 : (from_here > E ? E : from_here);
-        const long long left_shifted = (from_here + 1 < 0 || j >= RPI) ? 0 : (from_here + 1 > E ? E : from_here + 1);
+        const long long left = (from_here < 0 || !in_tail) ? 0 : (from_here > E ? E : from_here);
+        const long long left_shifted = (from_here + 1 < 0 || !in_tail) ? 0 : (from_here + 1 > E ? E : from_here + 1);
         tail_off = (SHIFT ? left_shifted : left) > 0 ? 16ull * s : 0ull;
         tail_keep = keep_first<DT>((int)left);
         tail_keep_shifted = keep_first<DT>((int)left_shifted);
@@ -165,8 +174,8 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
     // SHIFT: 1 for a row whose first element lies 2 bytes past a 4-byte boundary (byte offset `off` from x)
     const unsigned x_low = (unsigned)(unsigned long long)a.x;
     auto odd_start = [&](unsigned long long off) { return SHIFT ? (((unsigned)off + x_low) >> 1) & 1u : 0u; };
-    auto tail_row_offset = [&](unsigned long long it) {
-        unsigned long long r = it * (unsigned long long)RPI + (j < RPI ? j : 0u);
+    auto tail_row_offset = [&](unsigned long long it, unsigned tt) {
+        unsigned long long r = it * (unsigned long long)RPI + tt * RPTT + (in_tail ? row_t : 0u);
         r = r < a.row_hi ? r : a.row_hi - 1ull;
         return r * a.stride_bytes;
     };
@@ -193,9 +202,9 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 
     // Loads of one step.  The address of a slot is chosen by a select, not by a branch, so that the
     // stream of loads does not depend on control flow.
-    // `shifted` gets bit u set if this lane's row of group u is read from one element earlier, bit 31 for its
-    // row of the tail tile.
-    auto issue = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], uint4v &vt, unsigned &shifted) {
+    // `shifted` gets bit u set if this lane's row of group u is read from one element earlier, bit 24 + t for its
+    // row of tail tile t.
+    auto issue = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], uint4v (&vt)[NTT], unsigned &shifted) {
         const bool plain = is_plain(cb);
         unsigned long long off[GF];
         row_offsets(it, off);
@@ -212,12 +221,15 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
                 v[u][d] = load_slot_at<NT>(row + rel);
             }
         }
-        // the tail tile is loaded with every step (no branch around a load); only the last step uses it
+        // the tail tiles are loaded with every step (no branch around a load); only the last step uses them
         if constexpr (TAIL) {
-            const unsigned long long off_t = tail_row_offset(it);
-            const unsigned odd = odd_start(off_t);
-            shifted |= odd << 31;
-            vt = load_slot_at<NT>(a.x + off_t - 2u * odd + tail_off);
+#pragma unroll
+            for (unsigned tt = 0; tt < NTT; ++tt) {
+                const unsigned long long off_t = tail_row_offset(it, tt);
+                const unsigned odd = odd_start(off_t);
+                shifted |= odd << (24u + tt);
+                vt[tt] = load_slot_at<NT>(a.x + off_t - 2u * odd + tail_off);
+            }
         }
     };
 
@@ -225,7 +237,7 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 #pragma unroll
     for (int u = 0; u < GF; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    auto consume = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], uint4v &vt, unsigned shifted) {
+    auto consume = [&](unsigned long long it, unsigned cb, uint4v (&v)[GF][D], uint4v (&vt)[NTT], unsigned shifted) {
         if constexpr (SHIFT) {
             // a shifted row's first slot begins with the element before the row (a select in every step: a
             // branch here makes the compiler wait for all loads in flight)
@@ -249,11 +261,15 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
 #pragma unroll
             for (int d = 0; d < D; ++d) acc[u] = mma_ones<DT>(v[u][d], acc[u]);
         if (cb + 1u == a.batches) {
-            float4v acc_tail = {0.f, 0.f, 0.f, 0.f};
+            float tail_sum[NTT];
             if constexpr (TAIL) {
-                if constexpr (SHIFT) vt &= (shifted >> 31) != 0u ? tail_keep_shifted : tail_keep;
-                else vt &= tail_keep;
-                acc_tail = mma_ones<DT>(vt, acc_tail);        // column j: the rest of row j of the iteration
+#pragma unroll
+                for (unsigned tt = 0; tt < NTT; ++tt) {
+                    if constexpr (SHIFT) vt[tt] &= ((shifted >> (24u + tt)) & 1u) != 0u ? tail_keep_shifted : tail_keep;
+                    else vt[tt] &= tail_keep;
+                    // columns P_t i .. P_t i + P_t - 1: the rest of row i of tail tile tt
+                    tail_sum[tt] = fold_columns<TAIL ? LPT : 0>(mma_ones<DT>(vt[tt], float4v{0.f, 0.f, 0.f, 0.f}).x);
+                }
             }
             // Every lane of a row's P columns holds, after the fold, that row's sum for each group;
             // the lanes with part 0 and q = u mod 4 store group u.
@@ -265,9 +281,17 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
                 val = fold_columns<LP>(val);
                 if constexpr (TAIL) {
                     // the row this lane stores is row (4 h + q) RPT + row_local of the iteration: its rest sits in
-                    // that column of the tail accumulator (every 16-lane row of the wave holds a copy)
-                    const unsigned column = ((4u * (unsigned)h + q) * RPT + row_local) & 15u;
-                    val += __shfl(acc_tail.x, (int)((lane & 48u) | column), 64);
+                    // tail tile row / (16 / P_t), columns P_t (row mod (16 / P_t)) on (every 16-lane row of the
+                    // wave holds a copy)
+                    const unsigned row_i = (4u * (unsigned)h + q) * RPT + row_local;
+                    const int from = (int)((lane & 48u) | (((row_i % RPTT) * PT) & 15u));
+                    float rest = __shfl(tail_sum[0], from, 64);
+#pragma unroll
+                    for (unsigned tt = 1; tt < NTT; ++tt) {
+                        const float other = __shfl(tail_sum[tt], from, 64);
+                        rest = row_i / RPTT == tt ? other : rest;
+                    }
+                    val += rest;
                 }
                 const unsigned long long r = (it * GF + 4u * h + q) * RPT + row_local;
                 if (part == 0u && 4u * h + q < (unsigned)GF && r < a.row_hi) {
@@ -290,7 +314,9 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
         if (++cb == a.batches) { cb = 0u; it += W; }
     };
     uint4v v0[GF][D], v1[GF][D];
-    uint4v vt0 = {0u, 0u, 0u, 0u}, vt1 = {0u, 0u, 0u, 0u};
+    uint4v vt0[NTT], vt1[NTT];
+#pragma unroll
+    for (unsigned tt = 0; tt < NTT; ++tt) vt0[tt] = vt1[tt] = uint4v{0u, 0u, 0u, 0u};
     unsigned sh0 = 0u, sh1 = 0u;
     unsigned long long it0 = w, it1 = w;
     unsigned cb0 = 0u, cb1 = 0u;
@@ -318,15 +344,15 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
     }
 }
 
-template <int DT, int LP, int D, int GF, bool ALLPLAIN, bool TAIL, bool SHIFT>
+template <int DT, int LP, int D, int GF, bool ALLPLAIN, int LPT, bool SHIFT>
 static hipError_t launch_instance(const RowsArgs &a, unsigned grid, bool nt, hipStream_t stream)
 {
     if constexpr (SHIFT && ElemTraits<DT>::per_slot != 8) {
         return hipErrorInvalidValue;                     // only 16-bit rows can start 2 bytes off a 4-byte boundary
     } else {
         const dim3 g(grid), b(256);
-        if (nt) hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, D, GF, ALLPLAIN, true, TAIL, SHIFT>), g, b, 0, stream, a);
-        else hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, D, GF, ALLPLAIN, false, TAIL, SHIFT>), g, b, 0, stream, a);
+        if (nt) hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, D, GF, ALLPLAIN, true, LPT, SHIFT>), g, b, 0, stream, a);
+        else hipLaunchKernelGGL((rows_tiled_kernel<DT, LP, D, GF, ALLPLAIN, false, LPT, SHIFT>), g, b, 0, stream, a);
         return hipGetLastError();
     }
 }
@@ -352,54 +378,67 @@ hipError_t launch_rows_tiled_dt(const void *x, unsigned long long rows, unsigned
     // and for masked steps, four for unmasked steps of 256 bytes and more and for rows of several 1 KiB steps.
     const int key = s.log2_p * 100 + s.tiles_per_step * 10 + s.groups;
     if (s.tail) {
-        if (!s.all_plain) return hipErrorInvalidValue;
+        if (!s.all_plain || s.tail_log2_p < 0 || s.tail_log2_p > 2) return hipErrorInvalidValue;
+        const int tkey = key * 10 + s.tail_log2_p;
         if (s.shift) {
-            switch (key) {
-            case 214: return launch_instance<DT, 2, 1, 4, true, true, true>(a, grid, nt, stream);
-            case 318: return launch_instance<DT, 3, 1, 8, true, true, true>(a, grid, nt, stream);
-            case 414: return launch_instance<DT, 4, 1, 4, true, true, true>(a, grid, nt, stream);
-            case 418: return launch_instance<DT, 4, 1, 8, true, true, true>(a, grid, nt, stream);
+            switch (tkey) {
+            case 2140: return launch_instance<DT, 2, 1, 4, true, 0, true>(a, grid, nt, stream);
+            case 3180: return launch_instance<DT, 3, 1, 8, true, 0, true>(a, grid, nt, stream);
+            case 3181: return launch_instance<DT, 3, 1, 8, true, 1, true>(a, grid, nt, stream);
+            case 3182: return launch_instance<DT, 3, 1, 8, true, 2, true>(a, grid, nt, stream);
+            case 4140: return launch_instance<DT, 4, 1, 4, true, 0, true>(a, grid, nt, stream);
+            case 4141: return launch_instance<DT, 4, 1, 4, true, 1, true>(a, grid, nt, stream);
+            case 4142: return launch_instance<DT, 4, 1, 4, true, 2, true>(a, grid, nt, stream);
+            case 4180: return launch_instance<DT, 4, 1, 8, true, 0, true>(a, grid, nt, stream);
+            case 4181: return launch_instance<DT, 4, 1, 8, true, 1, true>(a, grid, nt, stream);
+            case 4182: return launch_instance<DT, 4, 1, 8, true, 2, true>(a, grid, nt, stream);
             default: return hipErrorInvalidValue;
             }
         }
-        switch (key) {
-        case 318: return launch_instance<DT, 3, 1, 8, true, true, false>(a, grid, nt, stream);
-        case 414: return launch_instance<DT, 4, 1, 4, true, true, false>(a, grid, nt, stream);
-        case 418: return launch_instance<DT, 4, 1, 8, true, true, false>(a, grid, nt, stream);
+        switch (tkey) {
+        case 3180: return launch_instance<DT, 3, 1, 8, true, 0, false>(a, grid, nt, stream);
+        case 3181: return launch_instance<DT, 3, 1, 8, true, 1, false>(a, grid, nt, stream);
+        case 3182: return launch_instance<DT, 3, 1, 8, true, 2, false>(a, grid, nt, stream);
+        case 4140: return launch_instance<DT, 4, 1, 4, true, 0, false>(a, grid, nt, stream);
+        case 4141: return launch_instance<DT, 4, 1, 4, true, 1, false>(a, grid, nt, stream);
+        case 4142: return launch_instance<DT, 4, 1, 4, true, 2, false>(a, grid, nt, stream);
+        case 4180: return launch_instance<DT, 4, 1, 8, true, 0, false>(a, grid, nt, stream);
+        case 4181: return launch_instance<DT, 4, 1, 8, true, 1, false>(a, grid, nt, stream);
+        case 4182: return launch_instance<DT, 4, 1, 8, true, 2, false>(a, grid, nt, stream);
         default: return hipErrorInvalidValue;
         }
     }
     if (s.shift) {
         if (s.all_plain) return hipErrorInvalidValue;
         switch (key) {
-        case 18: return launch_instance<DT, 0, 1, 8, false, false, true>(a, grid, nt, stream);
-        case 118: return launch_instance<DT, 1, 1, 8, false, false, true>(a, grid, nt, stream);
-        case 218: return launch_instance<DT, 2, 1, 8, false, false, true>(a, grid, nt, stream);
-        case 318: return launch_instance<DT, 3, 1, 8, false, false, true>(a, grid, nt, stream);
-        case 414: return launch_instance<DT, 4, 1, 4, false, false, true>(a, grid, nt, stream);
-        case 418: return launch_instance<DT, 4, 1, 8, false, false, true>(a, grid, nt, stream);
+        case 18: return launch_instance<DT, 0, 1, 8, false, -1, true>(a, grid, nt, stream);
+        case 118: return launch_instance<DT, 1, 1, 8, false, -1, true>(a, grid, nt, stream);
+        case 218: return launch_instance<DT, 2, 1, 8, false, -1, true>(a, grid, nt, stream);
+        case 318: return launch_instance<DT, 3, 1, 8, false, -1, true>(a, grid, nt, stream);
+        case 414: return launch_instance<DT, 4, 1, 4, false, -1, true>(a, grid, nt, stream);
+        case 418: return launch_instance<DT, 4, 1, 8, false, -1, true>(a, grid, nt, stream);
         default: return hipErrorInvalidValue;
         }
     }
     if (s.all_plain) {
         switch (key) {
-        case 18: return launch_instance<DT, 0, 1, 8, true, false, false>(a, grid, nt, stream);
-        case 118: return launch_instance<DT, 1, 1, 8, true, false, false>(a, grid, nt, stream);
-        case 214: return launch_instance<DT, 2, 1, 4, true, false, false>(a, grid, nt, stream);
-        case 314: return launch_instance<DT, 3, 1, 4, true, false, false>(a, grid, nt, stream);
-        case 414: return launch_instance<DT, 4, 1, 4, true, false, false>(a, grid, nt, stream);
-        case 441: return launch_instance<DT, 4, 4, 1, true, false, false>(a, grid, nt, stream);
+        case 18: return launch_instance<DT, 0, 1, 8, true, -1, false>(a, grid, nt, stream);
+        case 118: return launch_instance<DT, 1, 1, 8, true, -1, false>(a, grid, nt, stream);
+        case 214: return launch_instance<DT, 2, 1, 4, true, -1, false>(a, grid, nt, stream);
+        case 314: return launch_instance<DT, 3, 1, 4, true, -1, false>(a, grid, nt, stream);
+        case 414: return launch_instance<DT, 4, 1, 4, true, -1, false>(a, grid, nt, stream);
+        case 441: return launch_instance<DT, 4, 4, 1, true, -1, false>(a, grid, nt, stream);
         default: return hipErrorInvalidValue;
         }
     }
     switch (key) {
-    case 18: return launch_instance<DT, 0, 1, 8, false, false, false>(a, grid, nt, stream);
-    case 118: return launch_instance<DT, 1, 1, 8, false, false, false>(a, grid, nt, stream);
-    case 218: return launch_instance<DT, 2, 1, 8, false, false, false>(a, grid, nt, stream);
-    case 318: return launch_instance<DT, 3, 1, 8, false, false, false>(a, grid, nt, stream);
-    case 414: return launch_instance<DT, 4, 1, 4, false, false, false>(a, grid, nt, stream);
-    case 418: return launch_instance<DT, 4, 1, 8, false, false, false>(a, grid, nt, stream);
-    case 441: return launch_instance<DT, 4, 4, 1, false, false, false>(a, grid, nt, stream);
+    case 18: return launch_instance<DT, 0, 1, 8, false, -1, false>(a, grid, nt, stream);
+    case 118: return launch_instance<DT, 1, 1, 8, false, -1, false>(a, grid, nt, stream);
+    case 218: return launch_instance<DT, 2, 1, 8, false, -1, false>(a, grid, nt, stream);
+    case 318: return launch_instance<DT, 3, 1, 8, false, -1, false>(a, grid, nt, stream);
+    case 414: return launch_instance<DT, 4, 1, 4, false, -1, false>(a, grid, nt, stream);
+    case 418: return launch_instance<DT, 4, 1, 8, false, -1, false>(a, grid, nt, stream);
+    case 441: return launch_instance<DT, 4, 4, 1, false, -1, false>(a, grid, nt, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -96,6 +96,11 @@ INT_CASES = [
     (4096, 1, 1, 0), (4096, 32, 32, 1), (4096, 64, 64, 1), (4096, 128, 128, 1), (4096, 160, 160, 1), (4096, 256, 256, 1),
     (700, 256, 256, 1), (2048, 1024, 1024, 1), (2048, 288, 288, 1), (2048, 512, 512, 1), (2048, 1025, 1025, 0),
     (2048, 513, 513, 0), (2048, 150, 150, 3), (3000, 97, 97, 0), (1031, 1500, 1500, 5), (4096, 16, 16, 7),
+    # rests of up to 128 and 256 bytes after the whole steps: tail tiles with two and four columns per row
+    (2051, 289, 290, 0), (2051, 288, 288, 1), (2051, 321, 322, 0), (2051, 320, 320, 1), (2051, 545, 546, 0), (2051, 544, 544, 1),
+    (2051, 577, 578, 0), (2051, 576, 576, 1), (2051, 1057, 1058, 0), (2051, 1056, 1056, 1), (2051, 1089, 1090, 0),
+    (2051, 1088, 1088, 1), (1029, 600, 600, 0), (1029, 1150, 1150, 0), (1029, 1600, 1600, 0), (2051, 350, 350, 0),
+    (2051, 384, 384, 1),
 ]
 
 # few rows whose 16-byte phases differ: the per-row kernels, every block doing the slot arithmetic of its own row
@@ -158,7 +163,7 @@ def test_few_rows_of_differing_phase_bit_exact(dtype, rows, cols, stride, shift)
 
 def test_shapes_reach_every_kernel_shape():
     """The bit-exact cases above go through every instance of the many-rows kernel that the library can choose:
-    (P, D, GF, unmasked, tail tile and shifted-rows flags)."""
+    (P, D, GF, unmasked, flags: tail tiles, shifted rows, log2 of the tail tile's columns per row)."""
     seen = set()
     for dtype in (F16, F32):
         for rows, cols, stride, shift in INT_CASES:
@@ -166,15 +171,16 @@ def test_shapes_reach_every_kernel_shape():
             plan = B.mfr_rows_plan((1 << 20) + shift * esize, dtype, rows, cols, stride, 256)
             assert plan is not None
             seen.add((plan[0], plan[1], plan[2], plan[9], plan[11]))
+    tails = lambda p, gf: {(p, 1, gf, 1, 1 | shifted | pt << 2) for shifted in (0, 2) for pt in (0, 1, 2)}
     instances = {
         # unmasked, masked
         (1, 1, 8, 1, 0), (2, 1, 8, 1, 0), (4, 1, 4, 1, 0), (8, 1, 4, 1, 0), (16, 1, 4, 1, 0), (16, 4, 1, 1, 0),
         (1, 1, 8, 0, 0), (2, 1, 8, 0, 0), (4, 1, 8, 0, 0), (8, 1, 8, 0, 0), (16, 1, 4, 0, 0), (16, 1, 8, 0, 0), (16, 4, 1, 0, 0),
-        # tail tile; shifted rows, masked; shifted rows with a tail tile
-        (8, 1, 8, 1, 1), (16, 1, 4, 1, 1), (16, 1, 8, 1, 1),
+        # shifted rows, masked; shifted rows of 256-byte steps with a tail tile
         (1, 1, 8, 0, 2), (2, 1, 8, 0, 2), (4, 1, 8, 0, 2), (8, 1, 8, 0, 2), (16, 1, 4, 0, 2), (16, 1, 8, 0, 2),
-        (4, 1, 4, 1, 3), (8, 1, 8, 1, 3), (16, 1, 4, 1, 3), (16, 1, 8, 1, 3),
-    }
+        (4, 1, 4, 1, 3),
+        # tail tiles of one, two and four columns per row, rows shifted or not
+    } | tails(8, 8) | tails(16, 4) | tails(16, 8)
     assert seen == instances, (sorted(instances - seen), sorted(seen - instances))
 
 

@@ -10,8 +10,8 @@ test checks what the kernel relies on for memory safety and for correctness:
   past the row's end) lies inside the array's span, for the rows the kernel is
   given; the rows it is not given are few,
 * rows map to store lanes one to one,
-* where the rows end in a tail tile, the tile's slots cover exactly what the plain steps leave, its loads stay
-  inside the span, and each storing lane fetches the column that holds its own row,
+* where the rows end in tail tiles, the tiles' slots cover exactly what the plain steps leave, their loads stay
+  inside the span, and each storing lane fetches the tile and column that hold its own row,
 * where rows of a 16-bit type at odd element addresses are read from one element earlier, every load starts on a
   4-byte boundary, none starts below the aligned word that holds x[0], and the element before the row is dropped.
 """
@@ -29,7 +29,7 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
     if plan is None:
         return None
     P, D, GF, iters, batches, plain_lo, plain_hi, row_lo, row_hi, all_plain, grid, flags = plan
-    tail, shift = flags & 1, (flags >> 1) & 1
+    tail, shift, PT = flags & 1, (flags >> 1) & 1, 1 << (flags >> 2)        # PT: columns per row in a tail tile
     es = ESIZE[dtype]
     E = 16 // es
     RPT = 16 // P
@@ -49,9 +49,14 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
         assert es == 2 and D == 1 and (tail or not all_plain)
         assert (x_addr & 2) or ((stride * es) & 2)       # some row does start at an odd element address
     if tail:
-        assert all_plain == 1 and D == 1 and rpi <= 16 and batches >= 1
+        assert all_plain == 1 and D == 1 and batches >= 1 and PT in (1, 2, 4)
         rest = cols + shift - batches * 4 * P * E        # elements after the plain steps
-        assert 0 < rest <= 4 * E
+        assert 0 < rest <= 4 * PT * E
+        rptt = 16 // PT                                  # rows per tail tile
+        ntt = -(-rpi * PT // 16)                         # tail tiles per iteration: one (maybe not full), or all full
+        assert ntt == 1 or rpi * PT == ntt * 16
+    else:
+        assert PT == 1
 
     def odd_start(off):                                  # rows read from one element earlier
         return ((x_addr + off) >> 1) & 1 if shift else np.zeros_like(off)
@@ -102,28 +107,32 @@ def replay(x_addr, dtype, rows, cols, stride, cus=256):
             for ln in np.nonzero(mine)[0]:
                 stored[r_raw[ln]] += 1
                 if tail:
-                    # the column this lane fetches from the tail accumulator holds its own row
+                    # the tail tile and column this lane fetches its row's rest from
                     h = u // 4
-                    column = ((4 * h + q[ln]) * RPT + row_local[ln]) & 15
-                    assert it * rpi + column == r_raw[ln]
+                    row_i = (4 * h + q[ln]) * RPT + row_local[ln]
+                    tile, column = row_i // rptt, (row_i % rptt) * PT
+                    assert tile < ntt and it * rpi + tile * rptt + column // PT == r_raw[ln]
         if tail:
-            # the tail tile: lane (q, j) reads slot 4 P batches + q of row j of the iteration
-            r_raw = it * rpi + np.where(j < rpi, j, 0)
-            r = np.minimum(r_raw, row_hi - 1)
-            off = r * stride * es
-            odd = odd_start(off)
-            base = off - 2 * odd
-            s = 4 * P * batches + q
-            e0 = E * s - odd
-            hi = np.where(j < rpi, np.clip(cols - e0, 0, E), 0)
-            hi_loaded = np.where(j < rpi, np.clip(cols + shift - E * s, 0, E), 0)
-            addr = np.where(hi_loaded > 0, base + 16 * s, base)
-            check_loads(addr, odd)
-            for ln in range(64):
-                if j[ln] >= rpi or r_raw[ln] >= row_hi:
-                    continue
-                for t in range(hi[ln]):
-                    covered[r[ln], e0[ln] + t] += 1
+            # tail tile t: lane (q, j) reads slot 4 P batches + (j mod PT) + PT q of row j // PT of the tile
+            row_t = j // PT
+            in_tail = row_t < rpi
+            for tile in range(ntt):
+                r_raw = it * rpi + tile * rptt + np.where(in_tail, row_t, 0)
+                r = np.minimum(r_raw, row_hi - 1)
+                off = r * stride * es
+                odd = odd_start(off)
+                base = off - 2 * odd
+                s = 4 * P * batches + (j & (PT - 1)) + PT * q
+                e0 = E * s - odd
+                hi = np.where(in_tail, np.clip(cols - e0, 0, E), 0)
+                hi_loaded = np.where(in_tail, np.clip(cols + shift - E * s, 0, E), 0)
+                addr = np.where(hi_loaded > 0, base + 16 * s, base)
+                check_loads(addr, odd)
+                for ln in range(64):
+                    if not in_tail[ln] or r_raw[ln] >= row_hi:
+                        continue
+                    for t in range(hi[ln]):
+                        covered[r[ln], e0[ln] + t] += 1
     assert np.all(covered[:row_hi] == 1) and not covered[row_hi:].any()
     assert np.all(stored[:row_hi] == 1) and not stored[row_hi:].any()
     return plan
@@ -144,6 +153,9 @@ SHAPES = [
     (2, 2048, 256, 256), (2, 2048, 128, 128), (6, 2048, 150, 150), (0, 2048, 129, 129), (2, 1100, 512, 512),
     (0, 1100, 1025, 1025), (2, 1030, 300, 300), (2, 2048, 16, 16), (0, 2048, 17, 17), (6, 700, 1000, 1001),
     (2, 2048, 159, 160), (0, 1040, 31, 33), (2, 1100, 1024, 1026), (0, 1100, 1055, 1055), (2, 1100, 1500, 1500),
+    # rests of up to 128 and 256 bytes: tail tiles with two and four columns per row
+    (0, 2048, 300, 300), (0, 2048, 350, 352), (0, 2048, 384, 384), (0, 1100, 600, 600), (0, 1100, 640, 648), (0, 1030, 1100, 1100),
+    (0, 1030, 1150, 1150), (2, 2048, 310, 310), (2, 2048, 380, 380), (0, 1100, 575, 575), (2, 1100, 1130, 1130), (0, 1030, 1600, 1608),
 ]
 
 
@@ -187,28 +199,35 @@ def test_rows_over_512_bytes_take_the_shape_that_wastes_least():
     assert shape(f32, 192)[:3] == (4, 1, 4) and shape(f32, 384)[:3] == (8, 1, 4)
     assert shape(f16, 260)[:3] == (8, 1, 8) and shape(f16, 260)[4] == 1 and shape(f16, 260)[11] == 1   # 512 B + 8: tail tile
     assert shape(f16, 520)[:3] == (16, 1, 8) and shape(f16, 520)[4] == 1 and shape(f16, 520)[11] == 1  # 1024 B + 16
-    assert shape(f16, 546)[:3] == (8, 1, 8) and shape(f16, 546)[4] == 3 and shape(f16, 546)[11] == 0   # 1092 B: 53 % of two 1 KiB steps
-    assert shape(f16, 544)[11] == 1 and shape(f16, 288)[11] == 1 and shape(f16, 290)[11] == 0   # at most 64 bytes after the steps
+    assert shape(f16, 700)[:3] == (16, 1, 8) and shape(f16, 700)[4] == 2 and shape(f16, 700)[11] == 0  # 1400 B: a masked second step
+    assert shape(f16, 544)[11] == 1 and shape(f16, 288)[11] == 1         # at most 64 bytes after the steps: one column per row
+    assert shape(f16, 290)[11] == 1 | 1 << 2 and shape(f16, 320)[11] == 1 | 1 << 2      # 65 to 128 bytes: two columns per row
+    assert shape(f16, 322)[11] == 1 | 2 << 2 and shape(f16, 382)[11] == 1 | 2 << 2      # 129 to 256 bytes: four
+    assert shape(f16, 384)[11] == 0 and shape(f16, 386)[11] == 0                        # whole 256-byte steps; 260 bytes after a step
+    assert shape(f16, 600)[:3] == (16, 1, 8) and shape(f16, 600)[4] == 1 and shape(f16, 600)[11] == 1 | 2 << 2   # 1024 B + 176
+    assert shape(f16, 1150)[:3] == (16, 1, 4) and shape(f16, 1150)[4] == 2 and shape(f16, 1150)[11] == 1 | 2 << 2  # 2048 B + 252
+    assert shape(f16, 1600)[11] == 1 | 1 << 2 and shape(f16, 1650)[11] == 0            # after three steps: up to 128 bytes
     # shifted rows: the element before the row counts (bit 1 of plan[11]); the tail tile (bit 0) from 256-byte rows on
     shifted = lambda cols: B.mfr_rows_plan((1 << 20) + 2, f16, 4096, cols, cols, 256)
     assert shifted(256)[:3] == (8, 1, 8) and shifted(256)[4] == 1 and shifted(256)[11] == 3
     assert shifted(128)[:3] == (4, 1, 4) and shifted(128)[4] == 1 and shifted(128)[11] == 3
-    assert shifted(287)[11] == 3 and shifted(288)[11] == 2 and shape(f16, 287)[11] == 3 and shape(f16, 289)[11] == 2
+    assert shifted(287)[11] == 3 and shifted(288)[11] == 3 | 1 << 2 and shape(f16, 287)[11] == 3 and shape(f16, 289)[11] == 3 | 1 << 2
+    assert shifted(383)[11] == 3 | 2 << 2 and shifted(384)[11] == 2        # 768 + 2 bytes to hold: 258 after the step
     assert shifted(1024)[:3] == (16, 1, 4) and shifted(1024)[4] == 2 and shifted(1024)[11] == 3
     assert shifted(255)[:3] == (8, 1, 8) and shifted(255)[9] == 0 and shifted(255)[11] == 2      # 256 elements to hold: one masked step
     # a single masked step under 69 % full, and 256-byte steps with a tail tile: two blocks per CU
     many = lambda dt, cols, x_addr=1 << 20: B.mfr_rows_plan(x_addr, dt, 1 << 18, cols, cols, 256)
-    assert many(f16, 300)[10] == 512 and many(f16, 16)[10] == 512 and many(f32, 145)[10] == 512
+    assert many(f16, 165)[10] == 512 and many(f16, 16)[10] == 512 and many(f32, 40)[10] == 512
     assert many(f16, 128, (1 << 20) + 2)[10] == 512
-    assert many(f16, 400)[10] == 256 and many(f16, 24)[10] == 256 and many(f16, 600)[10] == 256
+    assert many(f16, 400)[10] == 256 and many(f16, 24)[10] == 256 and many(f16, 600)[10] == 256 and many(f16, 290)[10] == 256
     assert many(f16, 256, (1 << 20) + 2)[10] == 256
     # a masked row of P = 16: eight groups when one step, or when under 80 % of the steps is filled
-    assert shape(f16, 300)[:3] == (16, 1, 8) and shape(f16, 400)[:3] == (16, 1, 8) and shape(f16, 511)[:3] == (16, 1, 8)
-    assert shape(f16, 800)[:3] == (16, 1, 8) and shape(f16, 800)[11] == 0 and shape(f16, 1100)[:3] == (16, 1, 8)
+    assert shape(f16, 390)[:3] == (16, 1, 8) and shape(f16, 400)[:3] == (16, 1, 8) and shape(f16, 511)[:3] == (16, 1, 8)
+    assert shape(f16, 800)[:3] == (16, 1, 8) and shape(f16, 800)[11] == 0 and shape(f16, 1200)[:3] == (16, 1, 8)
     assert shape(f16, 900)[:3] == (16, 1, 4) and shape(f16, 1000)[:3] == (16, 1, 4) and shape(f16, 2000)[:3] == (16, 1, 4)
     assert shape(f16, 1030)[:3] == (16, 1, 4) and shape(f16, 1030)[11] == 1   # 2048 B + 12: P = 16, two plain steps, tail tile
     assert shape(f16, 2052)[11] == 0                                          # from 4 KiB on: no tail tile
-    assert shape(f16, 1100)[11] == 0
+    assert shape(f16, 1200)[11] == 0
     assert shape(f16, 512)[:3] == (16, 1, 4) and shape(f16, 1024)[:3] == (16, 1, 4) and shape(f16, 1536)[:3] == (16, 1, 4)
 
 
