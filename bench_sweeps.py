@@ -54,7 +54,7 @@ class Timer:
 def rows_shape_label(plan):
     """Name of a many-rows kernel shape as mfr_rows_plan reports it."""
     label = "P%d_D%d_GF%d" % (plan[0], plan[1], plan[2])
-    label += "_tail" if plan[11] & 1 else ("" if plan[9] else "_masked")
+    label += "_tail%d" % (1 << (plan[11] >> 2)) if plan[11] & 1 else ("" if plan[9] else "_masked")
     return label + ("_shifted" if plan[11] & 2 else "")
 
 

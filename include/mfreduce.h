@@ -321,11 +321,13 @@ int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *t, unsigne
  *            of theirs reaches past the array's span; the few rows after them are
  *            summed one by one as single arrays (in a tile that holds rows of both
  *            kinds they are replaced by row end - 1, and not stored)
- *   plan[9]  1 if every step is unmasked    plan[10] blocks of 256 threads
- *   plan[11] bit 0: the rows end in a tail tile: plan[4] then counts the plain steps only (plan[9] is 1), and
- *            the at most four slots of each row after them are read once per iteration, as one tile in
- *            which lane l = 16 q + j reads slot 4 P plan[4] + q of row j of the iteration (j below
- *            GF * 16 / P <= 16; masked and substituted like a masked step's slots).
+ *   plan[9]  1 if every step is unmasked    plan[10] blocks of 256 threads (one per compute unit, two for some shapes)
+ *   plan[11] bit 0: the rows end in tail tiles: plan[4] then counts the plain steps only (plan[9] is 1), and
+ *            the at most 4 P_t slots of each row after them (P_t = 2^(plan[11] >> 2) = 1, 2 or 4) are read as
+ *            tiles of 16 / P_t rows each, ceil(GF * P_t / P) of them per iteration: in tail tile t, lane
+ *            l = 16 q + j reads slot 4 P plan[4] + (j mod P_t) + P_t q of row t * 16 / P_t + j / P_t of the
+ *            iteration (lanes whose row lies past the iteration's GF * 16 / P rows read nothing of their
+ *            own; masked and substituted like a masked step's slots).
  *            bit 1 (16-bit types, when some row starts 2 bytes off a 4-byte boundary): such a row's slots
  *            are counted from the element before its first one, which is dropped; plan[4] to plan[6] and
  *            the choice of substituted slots are those of rows of cols + 1 elements, plan[5], plan[6]

@@ -277,3 +277,14 @@ def test_replay_of_random_shapes(dtype, low, rows, cols, gap, cus):
     if rows * cols > 200_000:
         cols = max(1, 200_000 // rows)
     replay(x_addr, dtype, rows, cols, cols + gap, cus)
+
+
+@settings(max_examples=25, deadline=None)
+@given(dtype=st.sampled_from([B.MFR_DTYPE_F16, B.MFR_DTYPE_BF16, B.MFR_DTYPE_F32]),
+       low=st.integers(0, 7), rows=st.integers(1024, 1060), cols=st.integers(129, 1700), gap=st.integers(0, 9))
+def test_replay_of_random_longer_rows(dtype, low, rows, cols, gap):
+    """Rows of several steps: tail tiles of every width after one to three steps, masked and shifted steps."""
+    es = ESIZE[dtype]
+    x_addr = (1 << 20) + (low * 2 // es) * es
+    replay(x_addr, dtype, rows, cols, cols + gap, 256)
+
