@@ -111,6 +111,7 @@ struct Plan {
     int waves;                   // waves per block
     bool half;                   // 32-thread geometry
     unsigned long long chains;
+    unsigned int dynamic_lds = 0;   // bytes of LDS asked for beyond what the kernel uses: limits the blocks resident per CU
 };
 
 template <int DT> struct ElemTraits;
@@ -649,14 +650,14 @@ hipError_t launch_ru(const Plan &p, dim3 grid, bool nt, hipStream_t stream)
     const dim3 b((unsigned)p.threads);
     if (p.half) {
         if constexpr (DT == MFR_DTYPE_F16 && KERNEL != MFR_KERNEL_SPLIT) {
-            if (nt) hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, true, true>), grid, b, 0, stream, p.a);
-            else hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, false, true>), grid, b, 0, stream, p.a);
+            if (nt) hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, true, true>), grid, b, p.dynamic_lds, stream, p.a);
+            else hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, false, true>), grid, b, p.dynamic_lds, stream, p.a);
         } else {
             return hipErrorInvalidValue;   // the 32-thread geometry exists for the paper's type only
         }
     } else {
-        if (nt) hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, true, false>), grid, b, 0, stream, p.a);
-        else hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, false, false>), grid, b, 0, stream, p.a);
+        if (nt) hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, true, false>), grid, b, p.dynamic_lds, stream, p.a);
+        else hipLaunchKernelGGL((sum_kernel<KERNEL, DT, R, U, false, false>), grid, b, p.dynamic_lds, stream, p.a);
     }
     return hipGetLastError();
 }
