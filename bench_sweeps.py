@@ -406,6 +406,13 @@ def rows(args, torch, np, B, W):
                           (50002, 50002), (268425, 268425), (268426, 268426), (16777209, 16777209), (16777210, 16777210)):
             r = total // stride
             measure(f, f16, r, c, stride, 0, None, "default")
+        # row counts that are no power of two: a few hundred rows leave SIMDs without a wave
+        for r in (100, 300, 400, 520, 600, 700, 800, 900, 1500, 3000):
+            c = total // r // 8 * 8
+            measure(f, f16, r, c, c, 0, None, "default")
+        for r in (520, 700):
+            c = total // 2 // r // 8 * 8
+            measure(f, B.MFR_DTYPE_F32, r, c, c, 0, None, "default")
         for dtype in (B.MFR_DTYPE_BF16, B.MFR_DTYPE_F32):
             esize = 4 if dtype == B.MFR_DTYPE_F32 else 2
             n = total_bytes // esize
