@@ -301,18 +301,23 @@ int block_threads_for_rows(size_t rows, size_t row_bytes, int cus)
 // 256-thread blocks), 12 (shorter rows of a 16-bit type: six 128-thread or three 256-thread blocks) or 16
 // (shorter binary32 rows, whose waves have one chain in flight); the LDS is not used.  binary16: 16 KiB rows
 // 86 -> 90 % of 8 TB/s, 32 KiB rows 85 -> 89 %, 64 KiB rows 84 -> 88 %, 128 KiB rows 84 -> 86 %; binary32: 16 and
-// 32 KiB rows 86 / 87 -> 88 / 89 %, 64 KiB rows 85 -> 87 %.  Only for rows that all start on a 16-byte boundary:
+// 32 KiB rows 86 / 87 -> 88 / 89 %, 64 KiB rows 85 -> 87 %.  Only for rows made of whole 16-byte slots:
 // a row with a head slot pays a round trip of element-wise loads, which fewer resident blocks hide worse (32 KiB
-// rows one element off a boundary: 86 % unlimited, 68 % with 12 waves).  Shorter rows (64-thread blocks) do
-// best unlimited.  Returns 0 (no limit) also when the launch has fewer blocks than two rounds of that many.
+// rows one element off a boundary: 86 % unlimited, 68 % with 12 waves), and so does a row with a ragged last slot
+// (-6 points).  Shorter rows (64-thread blocks) do best unlimited.  Returns 0 (no limit) also when the launch has
+// fewer blocks than two rounds of that many, or when its last round would be so empty that over 4 % of the time
+// went into it (1061 rows of 500 KB: two rounds of 512 blocks and one of 37).
 unsigned int resident_limit_lds(size_t rows, unsigned long long blocks_per_row, size_t row_bytes, unsigned esize,
-                                bool rows_on_boundaries, int waves_per_block, int cus)
+                                bool whole_slots, int waves_per_block, int cus)
 {
-    if (rows < 2 || waves_per_block < 1 || row_bytes < 12288u || !rows_on_boundaries) return 0;
+    if (rows < 2 || waves_per_block < 1 || row_bytes < 12288u || !whole_slots) return 0;
     const unsigned waves_per_cu = row_bytes >= 65536u ? 8u : (esize == 2u ? 12u : 16u);
     unsigned long long per_cu = waves_per_cu / (unsigned)waves_per_block;
     if (per_cu < 1) per_cu = 1;
-    if ((unsigned long long)rows * blocks_per_row < 2ull * per_cu * (unsigned)cus) return 0;
+    const unsigned long long blocks = (unsigned long long)rows * blocks_per_row, round = per_cu * (unsigned)cus;
+    if (blocks < 2ull * round) return 0;
+    const unsigned long long rounds = (blocks + round - 1ull) / round;
+    if (blocks * 100ull < rounds * round * 96ull) return 0;
     const unsigned long long lds_per_cu = 160ull * 1024ull;
     unsigned long long want = lds_per_cu / per_cu - 1536ull;      // per_cu blocks fit, per_cu + 1 do not
     if (want > 61440ull) want = 61440ull;                         // what a launch may ask for without more ado
@@ -614,7 +619,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     const long long grid = grid_blocks_for(p, t, info.cus, batch);
     if (grid < 1) return MFR_ERR_INVALID_ARG;
     p.dynamic_lds = resident_limit_lds(tin == nullptr ? rows : 0, (unsigned long long)grid, cols * esize, esize,
-                                       same_phase && ((size_t)x & 15u) == 0, p.waves, info.cus);
+                                       same_phase && ((size_t)x & 15u) == 0 && ((cols * esize) & 15u) == 0, p.waves, info.cus);
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kSingleLaunchHardMax ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kSingleLaunchAutoMax);
     if (stamps && stamps_len < 4u * (size_t)grid) return MFR_ERR_INVALID_ARG;

@@ -129,7 +129,8 @@ def test_integer_rows_bit_exact(dtype, rows, cols, stride, shift, oracle_lib):
 LONG_ROWS_PER_ROW_CASES = [(2049, 3000, 3001, 0), (513, 4001, 4003, 6), (2049, 4096, 4096, 1), (1500, 2048, 2048, 3),
                            (66000, 2048, 2049, 0), (1100, 8192, 8192, 0), (1100, 9001, 9001, 0),
                            # enough rows of 16 KiB and more that the launch limits the blocks resident per CU
-                           (3100, 8192, 8192, 0), (1600, 20001, 20001, 0)]
+                           # (whole rounds of six 128-thread or three 256-thread blocks per CU)
+                           (3072, 8192, 8192, 0), (1536, 20000, 20000, 0), (3100, 8192, 8192, 0)]
 
 
 @pytest.mark.parametrize("dtype", [F16, BF16])
