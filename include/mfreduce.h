@@ -294,7 +294,9 @@ long long mfr_grid_for(size_t n, size_t x_addr, const mfr_tuning *t);
  *   plan[3] full chains in the main region (each chain_R tiles)
  *   plan[4] slots per tile (64, or 32 for block_threads == 32)
  *   plan[5], plan[6] border positions [begin, end): position p stands for slot
- *           p, or for slot 0 when p >= plan[1]; read element-wise, range-checked
+ *           p, or for slot 0 when p >= plan[1]; a slot that lies wholly inside
+ *           the array is read with one 128-bit load, the elements of the two
+ *           slots that straddle its ends one by one, range-checked
  * The main region reads slots [plan[2], plan[2] + plan[3] * chain_R * plan[4])
  * with unchecked 128-bit loads, so all of them must lie inside [x, x + n).
  */

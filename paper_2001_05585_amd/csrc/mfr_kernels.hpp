@@ -133,6 +133,9 @@ __device__ __forceinline__ uint4v load_slot(const uint4v *p)
 // lies wholly inside is one 128-bit load; a straddling slot is read with
 // independent element loads whose indices are clamped into range, so that all
 // of them are in flight together, and out-of-range elements are replaced by +0.
+// (The level kernel of the recurrence variant reads its groups this way: there a
+// value's place in its tile matters.  The single-pass kernels use load_epilogue
+// and load_stragglers, which branch around no load.)
 template <int DT>
 __device__ __forceinline__ uint4v load_slot_guarded(const SumArgs &a, const uint4v *base, const void *x,
                                                     unsigned long long q, bool active)
@@ -164,14 +167,48 @@ __device__ __forceinline__ uint4v load_slot_guarded(const SumArgs &a, const uint
     return r;
 }
 
-// Border position p -> slot: positions past the last slot stand for slot 0
-// (the head slot is skipped by the main region and picked up here); positions
-// at or past epi1 yield zeros.
+// A slot of zeros in device memory: where a lane has nothing to load, its load goes here instead of
+// being branched around (a branch around a load makes the compiler wait for the loads before it).
+static __device__ __align__(16) const unsigned int zero_slot[4] = {0u, 0u, 0u, 0u};
+
+// Border position p -> slot: positions past the last slot stand for slot 0 (the head slot is skipped by
+// the main region and picked up here); positions at or past epi1 yield zeros.  Only slots that lie wholly
+// inside [x, x + n) are loaded, with one 128-bit load; a slot that straddles either end of the array
+// yields zeros here and its elements inside the array come through load_stragglers.  No branch: the loads
+// of all border positions of a wave are in flight together.
 template <int DT>
 __device__ __forceinline__ uint4v load_epilogue(const SumArgs &a, const uint4v *base, const void *x,
                                                 unsigned long long p, bool carries)
 {
-    return load_slot_guarded<DT>(a, base, x, p < a.slots ? p : 0ull, carries && p < a.epi1);
+    constexpr unsigned E = ElemTraits<DT>::per_slot;
+    (void)x;
+    const unsigned long long q = p < a.slots ? p : 0ull, v0 = q * E;
+    const bool full = carries && p < a.epi1 && v0 >= a.head && v0 + E <= a.vend;
+    // both pointers are named as global memory, or the select between them would be compiled to flat loads
+    typedef __attribute__((address_space(1))) const uint4v global_slot;
+    const global_slot *from = full ? (const global_slot *)(base + q) : (const global_slot *)zero_slot;
+    return *from;
+}
+
+// The elements of the array that lie in no wholly valid slot: those before the first slot boundary
+// (fewer than a slot, when x is not on a boundary) and those after the last one (fewer than a slot; all
+// of the array if it has no whole slot).  Lane k of the first E lanes takes the k-th of the former, lane
+// E + k the k-th of the latter, each with one element-wide load at an index clamped into the array; the
+// value becomes element 0 of an otherwise empty slot (which position of which tile a value occupies does
+// not change the sum).  One load instruction, no branch.
+template <int DT>
+__device__ __forceinline__ uint4v load_stragglers(const SumArgs &a, const void *x, unsigned lane)
+{
+    constexpr unsigned E = ElemTraits<DT>::per_slot;
+    typedef typename ElemTraits<DT>::storage storage;
+    const unsigned long long first_whole = a.head ? 1ull : 0ull, end_whole = a.vend / E;      // whole slots [first_whole, end_whole)
+    const unsigned long long front_end = a.vend < first_whole * E ? a.vend : first_whole * E;  // front: [head, front_end)
+    const unsigned long long back_begin = (end_whole > first_whole ? end_whole : first_whole) * E;   // back: [back_begin, vend)
+    const bool back_lane = lane >= E;
+    const unsigned long long v = (back_lane ? back_begin : (unsigned long long)a.head) + (lane & (E - 1u));
+    const bool ok = lane < 2u * E && (back_lane ? v < a.vend : v < front_end);
+    const unsigned int t = ((const storage *)x)[ok ? v - a.head : 0ull];        // n >= 1: x[0] is readable
+    return uint4v{t & (0u - (unsigned int)ok), 0u, 0u, 0u};       // a mask, not a select: the load stays unconditional
 }
 
 // ------------------------------------------------------- lane exchanges ---
@@ -445,18 +482,22 @@ __device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *bas
     const uint4v *lane_base = base + a.main0 + (carries ? lane : 0u);
     Acc partial = 0;
 
-    // Border: leftover whole tiles (fewer than R), leftover slots, the partial last slot and the head
-    // slot, as masked tiles in chains of R (at most two chains; tiles past the end are all zeros).
-    // The loads of the first border chain are issued early and consumed after the main loop, and
-    // they go out right after the loads of this wave's first main step, so that the border's own
-    // memory round trips (its element-wise loads wait for each other) run in the shadow of that
-    // step: the wave that carries the border neither starts nor ends with a round trip of its own.
+    // Border: leftover whole tiles (fewer than R) and leftover whole slots, as tiles in chains of R (at
+    // most two chains; positions past the end are all zeros), and one tile of stragglers: the elements
+    // of the two slots that straddle the ends of the array.  The loads of the first border chain and of
+    // the stragglers are issued early and consumed after the main loop: they go out right after the
+    // loads of this wave's first main step, so that their round trip runs in the shadow of that step
+    // and the wave that carries the border neither starts nor ends with a round trip of its own.
     uint4v vb[R];
+    uint4v vs[1] = {uint4v{0u, 0u, 0u, 0u}};
+    // an array made of whole slots has no stragglers (uniform over the block)
+    const bool stragglers = a.head != 0u || (a.vend % ElemTraits<DT>::per_slot) != 0ull;
     if (border) {
         auto load_border = [&]() {
 #pragma unroll
             for (int r = 0; r < R; ++r)
                 vb[r] = load_epilogue<DT>(a, base, x, a.epi0 + (unsigned long long)r * TS + lane, carries);
+            if (stragglers) vs[0] = load_stragglers<DT>(a, x, lane);
         };
         bool stepped = false;
         if constexpr (U > 1) {
@@ -524,6 +565,7 @@ __device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *bas
 
     if (border) {
         if (a.epi0 < a.epi1) partial += (Acc)consume_chain<KIND, DT, R>(vb);
+        if (stragglers) partial += (Acc)consume_chain<KIND, DT, 1>(vs);
         for (unsigned long long p0 = a.epi0 + (unsigned long long)R * TS; p0 < a.epi1; p0 += (unsigned long long)R * TS) {
             uint4v v[R];
 #pragma unroll
