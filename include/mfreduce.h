@@ -221,7 +221,8 @@ int mfr_sum_ex(const void *x, int dtype, size_t n, float *out, const mfr_tuning 
  * and masks what lies past the row's end, so bytes after a row (in the gap or
  * in the next rows, inside [x, x + ((rows - 1) * row_stride + cols) * element
  * size)) may be read; nothing outside that span is (the last rows, whose final
- * slot would reach past it, are summed one by one), with one exception: a row
+ * slot would reach past it, are read element by element by extra blocks of the
+ * same launch), with one exception: a row
  * of a 16-bit type that starts 2 bytes off a 4-byte boundary is read from that
  * boundary, and its slots are counted from there (the element before the row
  * is discarded).  For row 0 that element lies before x, in the aligned 32-bit
@@ -321,9 +322,11 @@ int mfr_plan_ex(size_t n, size_t x_addr, int dtype, const mfr_tuning *t, unsigne
  *            slot wholly past the row's end is replaced by the row's first slot
  *   plan[7], plan[8]  rows [begin, end) that this kernel sums (begin is 0): no slot
  *            of theirs reaches past the array's span; the few rows after them are
- *            summed one by one as single arrays (in a tile that holds rows of both
- *            kinds they are replaced by row end - 1, and not stored)
- *   plan[9]  1 if every step is unmasked    plan[10] blocks of 256 threads (one per compute unit, two for some shapes)
+ *            summed a wave each, from element-wide loads inside the row, by one
+ *            further block per four rows in the same launch (in a tile that holds
+ *            rows of both kinds they are replaced by row end - 1, and not stored)
+ *   plan[9]  1 if every step is unmasked    plan[10] blocks of 256 threads that run the tiles (one per compute
+ *            unit, two for some shapes)
  *   plan[11] bit 0: the rows end in tail tiles: plan[4] then counts the plain steps only (plan[9] is 1), and
  *            the at most 4 P_t slots of each row after them (P_t = 2^(plan[11] >> 2) = 1, 2 or 4) are read as
  *            tiles of 16 / P_t rows each, ceil(GF * P_t / P) of them per iteration: in tail tile t, lane

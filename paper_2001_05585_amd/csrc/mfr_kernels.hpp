@@ -755,7 +755,7 @@ struct RowsTiledShape {
     bool shift;                  // 16-bit elements: rows at odd element addresses are read from one element earlier
     unsigned long long iters;    // ceil(rows / (GF * 16 / P))
     unsigned long long row_hi;   // rows [0, row_hi) go through this kernel: their slots lie inside the array's
-                                 // span; the host sums the rows after them one by one
+                                 // span; extra blocks of the launch sum the rows after them, a wave per row
     unsigned int batches;        // steps per row
     unsigned int plain_hi;       // steps [0, plain_hi) are plain; at most the last step is not
 };

@@ -575,12 +575,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
                 : dtype == MFR_DTYPE_BF16 ? mfr::launch_rows_tiled_bf16(x, rows, cols, row_stride, out, shape, grid, nt, stream)
                                           : mfr::launch_rows_tiled_f32(x, rows, cols, row_stride, out, shape, grid, nt, stream);
             if (e != hipSuccess) return hip_fail(e, "rows_tiled launch");
-            // the few rows at the end whose last 16-byte slot would reach past the array: one more
-            // launch, of the per-row kernels, which read nothing outside a row
-            if (shape.row_hi < rows)
-                return sum_rows_impl((const char *)x + shape.row_hi * row_stride * esize, dtype, rows - shape.row_hi, cols,
-                                     row_stride, out + shape.row_hi, nullptr, stream, fixed, true);
-            return MFR_OK;
+            return MFR_OK;           // the few rows whose last 16-byte slot would reach past the array are summed by extra blocks of the same launch
         }
     }
 

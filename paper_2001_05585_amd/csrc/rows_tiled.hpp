@@ -33,8 +33,10 @@
 // past the end is replaced by the row's first slot and masked to zero).  The
 // bytes masked away belong to the gap or to the next rows, inside the array's
 // span; the few rows at the end whose last slot would reach past the span are
-// left out -- the kernel stores rows [0, row_hi) and the host sums the others
-// with the single-array kernel.
+// left out of the tiles -- rows [0, row_hi) go through them, and the blocks
+// from main_blocks on sum the others, a wave per row, from element-wide loads
+// that stay inside the row (the same MFMA chain over the row, one tile of 64
+// slots per step).
 //
 // Rows that are a whole number of steps and at most 256 bytes more do not pay a masked step for those bytes:
 // after the row's plain steps, tail tiles take the rest of all rows of the iteration.  A tail tile gives P_t = 1, 2
@@ -63,11 +65,49 @@ struct RowsArgs {
     unsigned long long row_hi;       // rows [0, row_hi) are summed here: all their slots lie inside the span
     unsigned int batches;            // steps per row (TAIL: the plain steps; the rest of the row is the tail tile)
     unsigned int plain_hi;           // steps [0, plain_hi) consist of whole in-row slots; plain_hi >= batches - 1
+    unsigned int main_blocks;        // blocks [0, main_blocks) run the tiles; the blocks after them take rows [row_hi, rows)
     float *out;
 };
 
 // a 16-byte slot at element alignment
 typedef uint4v slot_unaligned __attribute__((aligned(2)));
+
+// Rows [row_hi, rows), a wave each.  The row's whole slots (counted from its first element) are read with 128-bit
+// loads, four tiles of 64 slots in flight; lanes past the last whole slot read a slot of zeros instead of being
+// branched around.  The fewer-than-a-slot elements after them come through one element-wide load, lane k taking
+// the k-th, as element 0 of an otherwise empty slot.  All tiles are chained through the ones-matrix MFMA
+// (Sections 4.1, 4.3) as everywhere else.  Nothing outside the row is read.
+template <int DT>
+__device__ __forceinline__ void sum_last_rows(const RowsArgs &a)
+{
+    constexpr unsigned E = ElemTraits<DT>::per_slot;
+    typedef typename ElemTraits<DT>::storage storage;
+    typedef __attribute__((address_space(1))) const slot_unaligned global_slot;
+    const unsigned lane = threadIdx.x & 63u;
+    const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const unsigned long long r = a.row_hi + (unsigned long long)(blockIdx.x - a.main_blocks) * (blockDim.x >> 6) + wave;
+    if (r >= a.rows) return;
+    const char *row = a.x + r * a.stride_bytes;
+    const unsigned long long whole = a.cols / E, rest = a.cols % E;
+    // the stragglers first: their round trip runs in the shadow of the tiles
+    const bool mine = lane < rest;
+    const unsigned int t = ((const storage *)row)[mine ? whole * E + lane : 0ull];        // cols >= 1: row[0] is readable
+    float4v acc = {0.f, 0.f, 0.f, 0.f};
+    for (unsigned long long s0 = 0; s0 < whole; s0 += 256ull) {
+        uint4v v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const unsigned long long s = s0 + 64ull * (unsigned)i + lane;
+            const global_slot *from = s < whole ? (const global_slot *)(row + 16ull * s) : (const global_slot *)zero_slot;
+            v[i] = *from;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = mma_ones<DT>(v[i], acc);
+    }
+    acc = mma_ones<DT>(uint4v{t & (0u - (unsigned int)mine), 0u, 0u, 0u}, acc);
+    const float total = chain_total(acc);
+    if (lane == 0u) a.out[r] = total;
+}
 
 template <bool NT>
 __device__ __forceinline__ uint4v load_slot_at(const char *p)
@@ -127,10 +167,14 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
     static_assert(!SHIFT || (ElemTraits<DT>::per_slot == 8 && D == 1 && (TAIL || !ALLPLAIN)),
                   "shifted rows end one element later: they need a masked step or a tail tile");
     constexpr long long E = (long long)ElemTraits<DT>::per_slot;
+    if (blockIdx.x >= a.main_blocks) {          // uniform over the block
+        sum_last_rows<DT>(a);
+        return;
+    }
     const unsigned lane = threadIdx.x & 63u;
     const unsigned wave = (unsigned)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const unsigned wpb = blockDim.x >> 6;
-    const unsigned long long W = (unsigned long long)gridDim.x * wpb;
+    const unsigned long long W = (unsigned long long)a.main_blocks * wpb;
     const unsigned long long w = (unsigned long long)blockIdx.x * wpb + wave;
     const unsigned j = lane & 15u, q = lane >> 4;
     const unsigned part = j & (P - 1u), row_local = j >> LP;
@@ -373,7 +417,10 @@ hipError_t launch_rows_tiled_dt(const void *x, unsigned long long rows, unsigned
     a.row_hi = s.row_hi;
     a.batches = s.batches;
     a.plain_hi = s.plain_hi;
+    a.main_blocks = grid;
     a.out = out;
+    // rows whose last slot would reach past the array: four to a block, after the blocks of the tiles
+    if (s.row_hi < rows) grid += (unsigned)((rows - s.row_hi + 3ull) / 4ull);
     // The instances are those the host's choice of shape can ask for: eight groups for 64- and 128-byte steps
     // and for masked steps, four for unmasked steps of 256 bytes and more and for rows of several 1 KiB steps.
     const int key = s.log2_p * 100 + s.tiles_per_step * 10 + s.groups;

@@ -326,18 +326,33 @@ def test_batched_calls_can_be_captured_in_a_hip_graph():
             assert np.array_equal(r[:rows].astype(np.float64), want), (rep, rows)
 
 
-def test_tail_rows_after_the_many_rows_kernel_are_summed_in_one_more_launch(oracle_lib):
-    """Contiguous rows whose last 16-byte slot would reach past the array's end are left to the
-    per-row kernels (one launch for all of them); their sums and the rows before them are exact."""
-    for dtype in (F16, F32):
-        for rows, cols, shift in ((3000, 33, 0), (3000, 1, 3), (2048, 257, 0), (1500, 515, 1), (1200, 1021, 0)):
+def test_last_rows_whose_final_slot_would_pass_the_array_are_summed_by_extra_blocks(oracle_lib):
+    """Contiguous rows whose last 16-byte slot would reach past the array's end are left out of the tiles and
+    summed by extra blocks of the same launch from element-wide loads; their sums and the rows before them are
+    exact, and nothing past the array is read (RowsInput puts NaN there)."""
+    with_last_rows = 0
+    for dtype in (F16, BF16, F32):
+        for rows, cols, shift in ((3000, 33, 0), (3000, 1, 3), (2048, 257, 0), (1500, 515, 1), (1200, 1021, 0), (1030, 2047, 0),
+                                  (600, 2050, 0), (1027, 7, 5), (2049, 100, 1), (1100, 1201, 0)):
             rng = np.random.default_rng(rows + cols)
             vals = rng.integers(-3, 4, size=(rows, cols)).astype(np.float32)
+            vals[-1, -1] = 3.0                                   # the very last element of the array counts
             inp = RowsInput(dtype, encode(dtype, vals).reshape(rows, cols), cols, shift)
             plan = B.mfr_rows_plan(inp.ptr, dtype, rows, cols, cols, cus())
-            assert plan is not None and plan[8] < rows, (dtype, rows, cols, plan)      # there are tail rows
+            assert plan is not None, (dtype, rows, cols)
+            with_last_rows += plan[8] < rows
             got = call(dtype, inp, rows, cols, cols)
             assert np.array_equal(got.astype(np.float64), vals.astype(np.float64).sum(axis=1)), (dtype, rows, cols, shift)
+    assert with_last_rows >= 28          # all of them but a binary32 shape or two whose rows are whole slots
+    # special values in such a row stay in it
+    rows, cols = 2050, 33
+    bits = encode(F16, np.ones((rows, cols), dtype=np.float32)).reshape(rows, cols).copy()
+    bits[rows - 1, cols - 1] = 0x7C00
+    bits[rows - 2, 0] = 0x7E00
+    inp = RowsInput(F16, bits, cols, 0)
+    assert B.mfr_rows_plan(inp.ptr, F16, rows, cols, cols, cus())[8] < rows
+    got = call(F16, inp, rows, cols, cols).astype(np.float64)
+    assert got[rows - 1] == math.inf and math.isnan(got[rows - 2]) and np.all(got[: rows - 2] == cols)
 
 
 def test_alternating_inputs_never_see_the_previous_calls_partials_per_row_kernels():
