@@ -1033,6 +1033,6 @@ const char *mfr_strerror(int status)
 
 const char *mfr_last_hip_error(void) { return g_hip_error; }
 
-int mfr_version(void) { return 500; }
+int mfr_version(void) { return 600; }
 
 }  // extern "C"
