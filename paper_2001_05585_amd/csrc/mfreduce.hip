@@ -533,11 +533,10 @@ int fill_zero(float *out, size_t count, hipStream_t stream)
 
 // rows sums of cols elements each; consecutive rows are row_stride elements apart.
 // `fixed`: if not null, the block partials and slots live there and nothing is allocated; a call
-// that needs more than it holds fails with MFR_ERR_SCRATCH_LIMIT.  `per_row_only`: skip the
-// many-rows kernel although tin is null.
+// that needs more than it holds fails with MFR_ERR_SCRATCH_LIMIT.
 int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row_stride, float *out,
                   const mfr_tuning *tin, hipStream_t stream, const ScratchView *fixed = nullptr,
-                  bool per_row_only = false, unsigned long long *stamps = nullptr, size_t stamps_len = 0)
+                  unsigned long long *stamps = nullptr, size_t stamps_len = 0)
 {
     mfr_tuning t;
     const int st = resolve_tuning(tin, dtype, &t, rows == 1 && valid_dtype(dtype) ? (unsigned long long)cols * elem_size(dtype) : 0ull);
@@ -565,7 +564,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
 
     // Many rows: tiles shared out among rows, one launch for any alignment and stride.
-    if (tin == nullptr && !per_row_only) {
+    if (tin == nullptr) {
         mfr::RowsTiledShape shape;
         unsigned grid = 0;
         if (plan_rows_tiled((size_t)x, esize, rows, cols, row_stride, info.cus, &shape, &grid)) {
@@ -863,7 +862,7 @@ int mfr_sum_f16_stamped(const mfr_half *x, size_t n, float *out, const mfr_tunin
                         size_t stamps_len, hipStream_t stream)
 {
     if (!stamps) return MFR_ERR_INVALID_ARG;
-    return sum_rows_impl(x, MFR_DTYPE_F16, 1, n, n, out, t, stream, nullptr, false, stamps, stamps_len);
+    return sum_rows_impl(x, MFR_DTYPE_F16, 1, n, n, out, t, stream, nullptr, stamps, stamps_len);
 }
 
 int mfr_wall_clock_khz(int *khz)
