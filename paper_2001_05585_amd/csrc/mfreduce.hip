@@ -425,23 +425,22 @@ bool plan_rows_tiled(size_t x_addr, unsigned esize, size_t rows, size_t cols, si
     int lp = 0;
     while (lp < 4 && (64ull << lp) < held_bytes) ++lp;
     int d = 1, gf = 8;
-    // Rows under 4 KiB that are whole 1 KiB steps (P = 16), or one 512-byte step (P = 8), and at most 256 bytes
-    // more: plain steps, and the rests of all rows of an iteration in tail tiles (P_t = 1, 2 or 4 columns per row
-    // for rests of up to 64, 128, 256 bytes) instead of a masked step of their own (520-byte rows 83 % against
-    // 69 %, 1040-byte rows 88 % against 74 %, 1200-byte rows 87 % against 76 %, 2060-byte rows 80 % against 76 %,
-    // 2300-byte rows 82 % against 78 %).  One plain step: eight groups side by side; several: four (as for unmasked
-    // rows of these steps).  The tail tiles are loaded with every step, so after three steps only rests of up to
-    // 128 bytes pay (3200-byte rows 87 % against 83 %, 3300-byte rows 77 % against 78 %); rows of 4 KiB and more
-    // gain nothing (4104-byte rows 78 % either way), nor do several 512-byte steps; rows that are whole steps of a
-    // narrower shape keep that shape.  Shifted rows of 256 to 318 bytes take one 256-byte step (P = 4) and a
-    // tail tile (256-byte rows 2 bytes off a boundary 67 -> 79 %).
+    // Rows of up to four whole 1 KiB steps (P = 16), or one 512-byte step (P = 8), and at most 256 bytes more:
+    // plain steps, and the rests of all rows of an iteration in tail tiles (P_t = 1, 2 or 4 columns per row for
+    // rests of up to 64, 128, 256 bytes) instead of a masked step of their own (520-byte rows 83 % against 69 %,
+    // 1040-byte rows 88 % against 74 %, 1200-byte rows 87 % against 76 %, 2060-byte rows 85 % against 76 %,
+    // 2300-byte rows 87 % against 78 %, 4200-byte rows 85 % against 81 %).  One plain step: eight groups side by
+    // side; several: four (as for unmasked rows of these steps), with the steps written out so that the tail
+    // tiles are loaded once per iteration.  Rows that are whole steps of a narrower shape keep that shape; several
+    // 512-byte steps gain nothing.  Shifted rows of 256 to 318 bytes take one 256-byte step (P = 4) and a tail
+    // tile (256-byte rows 2 bytes off a boundary 67 -> 79 %).
     int tail_lp = 0, tail_lpt = 0;
-    if (row_bytes < kRowsTiledLongRowBytes && (shift || row_bytes % 256ull != 0)) {
+    if (row_bytes < 5120ull && (shift || row_bytes % 256ull != 0)) {
         auto rest_after = [&](unsigned long long step) { return held_bytes - row_bytes / step * step; };
         unsigned long long rest = 0;
         if (row_bytes >= 1024ull) {
             rest = rest_after(1024ull);
-            if (rest > 0 && rest <= (row_bytes >= 3072ull ? 128ull : 256ull)) tail_lp = 4;
+            if (rest > 0 && rest <= 256ull) tail_lp = 4;
         } else if (row_bytes >= 512ull) {
             rest = rest_after(512ull);
             if (rest > 0 && rest <= 256ull) tail_lp = 3;

@@ -101,6 +101,10 @@ INT_CASES = [
     (2051, 577, 578, 0), (2051, 576, 576, 1), (2051, 1057, 1058, 0), (2051, 1056, 1056, 1), (2051, 1089, 1090, 0),
     (2051, 1088, 1088, 1), (1029, 600, 600, 0), (1029, 1150, 1150, 0), (1029, 1600, 1600, 0), (2051, 350, 350, 0),
     (2051, 384, 384, 1),
+    # rows of two to four 1 KiB steps that end in a masked step or in tail tiles: the instances with the steps written out
+    (1030, 1229, 1230, 0), (1030, 1664, 1664, 1), (1030, 1537, 1538, 0), (1030, 1536, 1536, 1), (1030, 1568, 1568, 1),
+    (1030, 1601, 1602, 0), (1030, 1600, 1600, 1), (1030, 640, 640, 1), (1030, 1152, 1152, 1), (1031, 2052, 2052, 0),
+    (1029, 2100, 2100, 0), (1027, 2150, 2150, 0), (1100, 900, 900, 0), (1100, 1750, 1750, 0),
 ]
 
 # few rows whose 16-byte phases differ: the per-row kernels, every block doing the slot arithmetic of its own row
@@ -166,25 +170,29 @@ def test_few_rows_of_differing_phase_bit_exact(dtype, rows, cols, stride, shift)
 
 def test_shapes_reach_every_kernel_shape():
     """The bit-exact cases above go through every instance of the many-rows kernel that the library can choose:
-    (P, D, GF, unmasked, flags: tail tiles, shifted rows, log2 of the tail tile's columns per row)."""
-    seen = set()
+    (P, D, GF, unmasked, flags: tail tiles, shifted rows, log2 of the tail tile's columns per row, steps written
+    out).  The set of instances is found by asking for the plans of row lengths up to 8200 elements."""
+    def instance(plan):
+        written_out = plan[0] == 16 and plan[1] == 1 and plan[4] in (2, 3, 4) and \
+            ((plan[11] & 1 and plan[2] == 4) or (not plan[11] & 1 and not plan[9]))
+        written_out = written_out or (plan[0] == 16 and plan[1] == 4 and plan[4] in (2, 3) and not plan[9])
+        return (plan[0], plan[1], plan[2], plan[9], plan[11], plan[4] if written_out else 0)
+
+    seen, reachable = set(), set()
     for dtype in (F16, F32):
+        esize = 2 if dtype != F32 else 4
         for rows, cols, stride, shift in INT_CASES:
-            esize = 2 if dtype != F32 else 4
             plan = B.mfr_rows_plan((1 << 20) + shift * esize, dtype, rows, cols, stride, 256)
             assert plan is not None
-            seen.add((plan[0], plan[1], plan[2], plan[9], plan[11]))
-    tails = lambda p, gf: {(p, 1, gf, 1, 1 | shifted | pt << 2) for shifted in (0, 2) for pt in (0, 1, 2)}
-    instances = {
-        # unmasked, masked
-        (1, 1, 8, 1, 0), (2, 1, 8, 1, 0), (4, 1, 4, 1, 0), (8, 1, 4, 1, 0), (16, 1, 4, 1, 0), (16, 4, 1, 1, 0),
-        (1, 1, 8, 0, 0), (2, 1, 8, 0, 0), (4, 1, 8, 0, 0), (8, 1, 8, 0, 0), (16, 1, 4, 0, 0), (16, 1, 8, 0, 0), (16, 4, 1, 0, 0),
-        # shifted rows, masked; shifted rows of 256-byte steps with a tail tile
-        (1, 1, 8, 0, 2), (2, 1, 8, 0, 2), (4, 1, 8, 0, 2), (8, 1, 8, 0, 2), (16, 1, 4, 0, 2), (16, 1, 8, 0, 2),
-        (4, 1, 4, 1, 3),
-        # tail tiles of one, two and four columns per row, rows shifted or not
-    } | tails(8, 8) | tails(16, 4) | tails(16, 8)
-    assert seen == instances, (sorted(instances - seen), sorted(seen - instances))
+            seen.add(instance(plan))
+        for rows in (600, 1030):
+            for cols in list(range(1, 2700)) + list(range(2700, 8200, 7)):
+                for first, gap in ((0, 0), (1, 0), (0, 1), (0, 8)):
+                    plan = B.mfr_rows_plan((1 << 20) + first * esize, dtype, rows, cols, cols + gap, 256)
+                    if plan is not None:
+                        reachable.add(instance(plan))
+    assert len(reachable) == 59
+    assert seen == reachable, (sorted(reachable - seen), sorted(seen - reachable))
 
 
 @pytest.mark.parametrize("dtype,kind", [(F16, "normal"), (F16, "uniform01"), (BF16, "normal"), (F32, "uniform_pm1")])

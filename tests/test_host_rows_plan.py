@@ -156,6 +156,8 @@ SHAPES = [
     # rests of up to 128 and 256 bytes: tail tiles with two and four columns per row
     (0, 2048, 300, 300), (0, 2048, 350, 352), (0, 2048, 384, 384), (0, 1100, 600, 600), (0, 1100, 640, 648), (0, 1030, 1100, 1100),
     (0, 1030, 1150, 1150), (2, 2048, 310, 310), (2, 2048, 380, 380), (0, 1100, 575, 575), (2, 1100, 1130, 1130), (0, 1030, 1600, 1608),
+    # four steps and tail tiles (rows of 4 to 5 KiB)
+    (0, 1030, 2100, 2100), (0, 1030, 2170, 2176), (4, 1030, 2052, 2060),
 ]
 
 
@@ -206,7 +208,7 @@ def test_rows_over_512_bytes_take_the_shape_that_wastes_least():
     assert shape(f16, 384)[11] == 0 and shape(f16, 386)[11] == 0                        # whole 256-byte steps; 260 bytes after a step
     assert shape(f16, 600)[:3] == (16, 1, 8) and shape(f16, 600)[4] == 1 and shape(f16, 600)[11] == 1 | 2 << 2   # 1024 B + 176
     assert shape(f16, 1150)[:3] == (16, 1, 4) and shape(f16, 1150)[4] == 2 and shape(f16, 1150)[11] == 1 | 2 << 2  # 2048 B + 252
-    assert shape(f16, 1600)[11] == 1 | 1 << 2 and shape(f16, 1650)[11] == 0            # after three steps: up to 128 bytes
+    assert shape(f16, 1600)[11] == 1 | 1 << 2 and shape(f16, 1650)[11] == 1 | 2 << 2 and shape(f16, 1670)[11] == 0   # 3200, 3300, 3340 B
     # shifted rows: the element before the row counts (bit 1 of plan[11]); the tail tile (bit 0) from 256-byte rows on
     shifted = lambda cols: B.mfr_rows_plan((1 << 20) + 2, f16, 4096, cols, cols, 256)
     assert shifted(256)[:3] == (8, 1, 8) and shifted(256)[4] == 1 and shifted(256)[11] == 3
@@ -226,7 +228,8 @@ def test_rows_over_512_bytes_take_the_shape_that_wastes_least():
     assert shape(f16, 800)[:3] == (16, 1, 8) and shape(f16, 800)[11] == 0 and shape(f16, 1200)[:3] == (16, 1, 8)
     assert shape(f16, 900)[:3] == (16, 1, 4) and shape(f16, 1000)[:3] == (16, 1, 4) and shape(f16, 2000)[:3] == (16, 1, 4)
     assert shape(f16, 1030)[:3] == (16, 1, 4) and shape(f16, 1030)[11] == 1   # 2048 B + 12: P = 16, two plain steps, tail tile
-    assert shape(f16, 2052)[11] == 0                                          # from 4 KiB on: no tail tile
+    assert shape(f16, 2052)[:3] == (16, 1, 4) and shape(f16, 2052)[4] == 4 and shape(f16, 2052)[11] == 1     # 4096 B + 8
+    assert shape(f16, 2564)[11] == 0                                          # from 5 KiB on: no tail tiles
     assert shape(f16, 1200)[11] == 0
     assert shape(f16, 512)[:3] == (16, 1, 4) and shape(f16, 1024)[:3] == (16, 1, 4) and shape(f16, 1536)[:3] == (16, 1, 4)
 
@@ -281,7 +284,7 @@ def test_replay_of_random_shapes(dtype, low, rows, cols, gap, cus):
 
 @settings(max_examples=25, deadline=None)
 @given(dtype=st.sampled_from([B.MFR_DTYPE_F16, B.MFR_DTYPE_BF16, B.MFR_DTYPE_F32]),
-       low=st.integers(0, 7), rows=st.integers(1024, 1060), cols=st.integers(129, 1700), gap=st.integers(0, 9))
+       low=st.integers(0, 7), rows=st.integers(1024, 1060), cols=st.integers(129, 2600), gap=st.integers(0, 9))
 def test_replay_of_random_longer_rows(dtype, low, rows, cols, gap):
     """Rows of several steps: tail tiles of every width after one to three steps, masked and shifted steps."""
     es = ESIZE[dtype]
