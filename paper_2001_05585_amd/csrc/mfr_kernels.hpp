@@ -77,6 +77,8 @@ struct SumArgs {
     unsigned int *combine_slots; // single-launch combine: gridDim.x words per row, all zero between calls;
                                  // nullptr = two-launch combine
     float *out;                  // one per row
+    unsigned int rotate_rows;    // 0, or the number of starting points: row r reads its chains starting from chain
+                                 // (r mod rotate_rows) * (chains / rotate_rows) and wrapping round (rows of over 16 chains)
     unsigned long long *stamps;  // diagnostic: four wall-clock readings per block (see mfr_sum_f16_stamped); normally nullptr
 };
 
@@ -474,13 +476,16 @@ __device__ __forceinline__ float consume_chain(const uint4v (&v)[R])
 template <int KIND, int DT, int R, int U, bool NT, bool HALF, typename Acc = float>
 __device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *base, const void *x, unsigned lane,
                                              unsigned long long c, unsigned long long c_end,
-                                             unsigned long long stride, bool border)
+                                             unsigned long long stride, bool border, unsigned long long rot = 0ull)
 {
     constexpr unsigned TS = HALF ? 32u : 64u;          // slots per tile
     const bool carries = !HALF || lane < 32u;
     const uint4v zero4 = {0u, 0u, 0u, 0u};
     const uint4v *lane_base = base + a.main0 + (carries ? lane : 0u);
     Acc partial = 0;
+    // chain c of the wave's sequence is chain (c + rot) mod chains of the array (rot < chains)
+    const unsigned long long wrap = a.chains;
+    auto placed = [&](unsigned long long cc) { cc += rot; return cc >= wrap ? cc - wrap : cc; };
 
     // Border: leftover whole tiles (fewer than R) and leftover whole slots, as tiles in chains of R (at
     // most two chains; positions past the end are all zeros), and one tile of stragglers: the elements
@@ -507,7 +512,7 @@ __device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *bas
                 for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
-                        const uint4v *p = lane_base + ((c + (unsigned long long)u * stride) * R + r) * TS;
+                        const uint4v *p = lane_base + (placed(c + (unsigned long long)u * stride) * R + r) * TS;
                         v[u][r] = carries ? load_slot<NT>(p) : zero4;
                     }
                 __builtin_amdgcn_sched_barrier(0);
@@ -523,7 +528,7 @@ __device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *bas
             uint4v v[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                const uint4v *p = lane_base + (c * R + r) * TS;
+                const uint4v *p = lane_base + (placed(c) * R + r) * TS;
                 v[r] = carries ? load_slot<NT>(p) : zero4;
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -543,7 +548,7 @@ __device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *bas
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    const uint4v *p = lane_base + ((c + (unsigned long long)u * stride) * R + r) * TS;
+                    const uint4v *p = lane_base + (placed(c + (unsigned long long)u * stride) * R + r) * TS;
                     v[u][r] = carries ? load_slot<NT>(p) : zero4;
                 }
             // all U * R loads are issued before the first is consumed
@@ -556,7 +561,7 @@ __device__ __forceinline__ Acc stream_chains(const SumArgs &a, const uint4v *bas
         uint4v v[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const uint4v *p = lane_base + (c * R + r) * TS;
+            const uint4v *p = lane_base + (placed(c) * R + r) * TS;
             v[r] = carries ? load_slot<NT>(p) : zero4;
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -615,20 +620,25 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
         }
     }
 
+    // staggered rows of a batched call: this row's first chain (uniform over the block)
+    unsigned long long rot = 0ull;
+    if (launch_args.rotate_rows != 0u && a.chains > 16ull)
+        rot = (unsigned long long)((unsigned int)row % launch_args.rotate_rows) * (a.chains / launch_args.rotate_rows);
+
     // Level 1: the wave's running sum over the fp32 results of its chains.  MFMA path: uniform over
     // the wave.  Conventional path: one running sum per lane, added up across the wave at the end.
     WaveAcc partial;
     if constexpr (KERNEL == MFR_KERNEL_MFMA) {
-        partial = stream_chains<MFR_KERNEL_MFMA, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, w, a.chains, W, w == W - 1);
+        partial = stream_chains<MFR_KERNEL_MFMA, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, w, a.chains, W, w == W - 1, rot);
     } else if constexpr (KERNEL == MFR_KERNEL_SHFL) {
-        partial = wave64_sum_acc(stream_chains<MFR_KERNEL_SHFL, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, w, a.chains, W, w == W - 1));
+        partial = wave64_sum_acc(stream_chains<MFR_KERNEL_SHFL, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, w, a.chains, W, w == W - 1, rot));
     } else {
         const unsigned long long W1 = a.split_waves, C1 = a.split_chains;
         if (w < W1) {
-            partial = stream_chains<MFR_KERNEL_MFMA, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, w, C1, W1, w == W - 1);
+            partial = stream_chains<MFR_KERNEL_MFMA, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, w, C1, W1, w == W - 1, rot);
         } else {
             partial = wave64_sum_acc(stream_chains<MFR_KERNEL_SHFL, DT, R, U, NT, HALF, WaveAcc>(a, base, x, lane, C1 + (w - W1),
-                                                                                               a.chains, W - W1, w == W - 1));
+                                                                                               a.chains, W - W1, w == W - 1, rot));
         }
     }
 

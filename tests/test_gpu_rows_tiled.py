@@ -149,6 +149,35 @@ def test_many_long_rows_through_the_per_row_kernels_bit_exact(dtype, rows, cols,
     assert bad.size == 0, (rows, cols, stride, shift, bad[:5], got[bad[:5]], want[bad[:5]])
 
 
+@pytest.mark.parametrize("dtype", [F16, F32])
+@pytest.mark.parametrize("rows,cols,shift", [(8, (1 << 20) + 5, 0), (9, 300001, 3), (6, 70000, 1), (1000, 40008, 0)])
+def test_few_long_rows_count_every_position_once(dtype, rows, cols, shift):
+    """Few long rows with library defaults start at different chains of their row and wrap round: distinct powers
+    of two at the ends of the row, around every sixteenth of it and at random places (zero elsewhere) must add
+    up to 2^K - 1 in every row, whichever chain the row started at."""
+    K = 16 if dtype == F16 else 24
+    rng = np.random.default_rng(cols + rows)
+    marks = [0, 1, 7, 8, cols - 1, cols - 2, cols - 9]
+    for k in range(1, 16):
+        marks += [k * cols // 16 - 1, k * cols // 16, k * cols // 16 + 8]
+    marks += [int(v) for v in rng.integers(0, cols, 200)]
+    marks = np.unique(np.array(marks))
+    stride = cols + (3 if shift else 0)
+    vals = np.zeros((rows, cols), dtype=np.float32)
+    for trial in range(4):
+        vals[:] = 0
+        for r in range(rows):
+            pos = rng.choice(marks, K, replace=False) if trial else marks[(np.arange(K) * 3 + r + trial) % marks.size]
+            pos = np.unique(pos)
+            vals[r, pos] = 2.0 ** rng.permutation(K)[:pos.size]
+        want = vals.astype(np.float64).sum(axis=1)
+        inp = RowsInput(dtype, encode(dtype, vals).reshape(rows, cols), stride, shift)
+        assert B.mfr_rows_plan(inp.ptr, dtype, rows, cols, stride, cus()) is None
+        got = call(dtype, inp, rows, cols, stride).astype(np.float64)
+        bad = np.nonzero(got != want)[0]
+        assert bad.size == 0, (rows, cols, shift, trial, bad[:5], got[bad[:5]], want[bad[:5]])
+
+
 @pytest.mark.parametrize("dtype", [F16, BF16, F32])
 @pytest.mark.parametrize("rows,cols,stride,shift", MIXED_PHASE_CASES)
 def test_few_rows_of_differing_phase_bit_exact(dtype, rows, cols, stride, shift):
