@@ -77,8 +77,8 @@ struct SumArgs {
     unsigned int *combine_slots; // single-launch combine: gridDim.x words per row, all zero between calls;
                                  // nullptr = two-launch combine
     float *out;                  // one per row
-    unsigned int rotate_rows;    // 0, or the number of starting points: row r reads its chains starting from chain
-                                 // (r mod rotate_rows) * (chains / rotate_rows) and wrapping round (rows of over 16 chains)
+    unsigned long long rotate_step;   // 0, or: row r reads its chains starting from chain (r * rotate_step) mod chains
+                                      // and wrapping round
     unsigned long long *stamps;  // diagnostic: four wall-clock readings per block (see mfr_sum_f16_stamped); normally nullptr
 };
 
@@ -622,8 +622,8 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
 
     // staggered rows of a batched call: this row's first chain (uniform over the block)
     unsigned long long rot = 0ull;
-    if (launch_args.rotate_rows != 0u && a.chains > 16ull)
-        rot = (unsigned long long)((unsigned int)row % launch_args.rotate_rows) * (a.chains / launch_args.rotate_rows);
+    if (launch_args.rotate_step != 0ull)
+        rot = (row * launch_args.rotate_step) % a.chains;
 
     // Level 1: the wave's running sum over the fp32 results of its chains.  MFMA path: uniform over
     // the wave.  Conventional path: one running sum per lane, added up across the wave at the end.

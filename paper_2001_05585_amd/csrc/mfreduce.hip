@@ -95,6 +95,7 @@ constexpr int kDefaultWavesPerCU = 4;          // one wave per SIMD
 constexpr long long kSingleLaunchAutoMax = 2048;   // AUTO: larger grids combine with a second launch
 constexpr long long kSingleLaunchHardMax = 65536;  // single-launch combine is not offered beyond this
 constexpr size_t kMaxRowsPerLaunch = 65535;    // gridDim.y limit
+constexpr unsigned long long kRowsApartBytes = 1ull << 20;    // few long rows are read at addresses this far apart (or a multiple)
 constexpr unsigned long long kOneBlockMaxChains = 32;   // library defaults: arrays this short get one block
 // Inputs that fit in the eight 4 MiB L2s may be resident there (a reduction often follows the kernel
 // that produced its input): they are read with ordinary loads, which hit in L2 (20 % faster at 32 MiB
@@ -584,15 +585,30 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
         // Row counts that leave SIMDs without a wave (a few hundred rows): the waves there are keep more loads in
         // flight each, so that the device as a whole has about what one wave of 6 KiB per SIMD would have
         // (520 rows of 1 MiB: 57 -> 78 % of 8 TB/s, 600 rows 64 -> 82 %, 700 rows 70 -> 81 %, 260 rows 75 -> 83 %).
+        // 8 KiB per wave already when 6 KiB would leave the device under 92 % of that (300 rows of 1.7 MiB 80 -> 86 %,
+        // 450 rows 81 -> 85 %, 900 rows 81 -> 84 %; 1000 rows, at 98 %, are better off with 6 KiB: 84 against 81.5 %),
+        // as one chain for binary32 (2 points better on average) and as two for the 16-bit types.
+        // A few rows more than half the SIMDs: two one-wave blocks per row with 6 KiB each instead of one with 12 KiB.
+        // binary32, 513 to 640 rows: 516 to 540 rows of 1 MiB 70 -> 82 %, 600 rows 77.5 -> 82.5 %, 640 rows 80 -> 83 %
+        // (two of 28 row lengths measured lose 6 to 9 points).  16-bit types, 513 to 544 rows: 520 rows of 1 MiB
+        // 76 -> 80 %, +1.2 points on average; from there on no gain on average and single lengths 14 points lower.
         if (!default_geometry().overridden && t.kernel == MFR_KERNEL_MFMA) {
             const unsigned long long slots = (unsigned long long)info.cus * (256u / (unsigned)t.block_threads);
             unsigned long long per_row = slots / rows;
             if (per_row < 1) per_row = 1;
+            if (per_row == 1 && t.block_threads == 64 && 2ull * rows <= slots + slots / (esize == 4 ? 4ull : 16ull) &&
+                cols * esize >= 65536u) {
+                per_row = 2;
+                t.grid_blocks = 2;
+            }
             const unsigned long long waves = rows * per_row * ((unsigned)t.block_threads / 64u);
-            const unsigned long long tiles = (6ull * 4ull * (unsigned)info.cus + waves - 1ull) / waves;      // per wave
-            if (tiles > 12) { t.chain_R = 8; t.chains_in_flight = 2; }
-            else if (tiles > 8) { t.chain_R = 6; t.chains_in_flight = 2; }
-            else if (tiles > 7) { t.chain_R = 4; t.chains_in_flight = 2; }
+            const unsigned long long want = 6ull * 4ull * (unsigned)info.cus;      // tiles in flight on the device
+            if (want > 12ull * waves) { t.chain_R = 8; t.chains_in_flight = 2; }
+            else if (want > 8ull * waves) { t.chain_R = 6; t.chains_in_flight = 2; }
+            else if (2ull * want > 13ull * waves) {
+                if (esize == 4) { t.chain_R = 8; t.chains_in_flight = 1; }
+                else { t.chain_R = 4; t.chains_in_flight = 2; }
+            }
         }
     }
     const size_t batch = rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch;
@@ -651,13 +667,21 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
             p.a.split_waves = w1;
             p.a.split_chains = c1;
         }
-        // Library defaults, several rows: row r starts (r mod 4) quarters of its chains further on (and wraps
-        // round).  With some row pitches the rows being read at one time otherwise fall onto the same memory
-        // channels (145 rows of 3 702 544 bytes: 63 -> 73 % of 8 TB/s, 113 rows of 1 187 764 floats 58 -> 69 %);
-        // over random shapes the mean moves by +0.2 points and single pitches by -8 to +11.  Eight starting
-        // points lift the bad pitches further and cost the others up to 4 points, a pseudo-random start per row
-        // up to 14.  More rows than four per CU run in rounds and gain nothing (8192 rows of 64 KiB lose 3).
-        p.a.rotate_rows = (tin == nullptr && rows > 1 && rows < (size_t)info.cus * 4u) ? 4u : 0u;
+        // Library defaults, several rows: row r starts r * rotate_step chains further on (and wraps round), with the
+        // step chosen so that the addresses the rows are read at, at any one time, lie a multiple of 1 MiB apart
+        // whatever the row pitch is (to within a chain).  The memory channels take such a pattern evenly; with the
+        // rows all read at the same distance from their starts, some pitches put them onto the same channels
+        // (145 rows of 3 702 544 bytes: 63 -> 83 % of 8 TB/s, 143 rows of 3 754 336 bytes 60 -> 83 %, 339 rows
+        // 74 -> 83 %; mean over 95 random shapes of 2 to 1023 rows 82.6 -> 83.9 %).  Granularities of 512 KiB to 4 MiB
+        // do the same, 64 KiB less (83.3 %); four evenly spaced starting points gave 83.0 %, a pseudo-random start
+        // per row costs rows whose pitch was fine up to 14 points.  More rows than four per CU run in rounds and
+        // gain nothing.
+        p.a.rotate_step = 0ull;
+        if (tin == nullptr && rows > 1 && rows < (size_t)info.cus * 4u && p.a.chains > 16ull) {
+            const unsigned long long pitch = p.a.row_bytes, chain_bytes = 1024ull * (unsigned)t.chain_R;
+            const unsigned long long apart = (pitch + kRowsApartBytes - 1ull) / kRowsApartBytes * kRowsApartBytes;
+            p.a.rotate_step = ((apart - pitch + chain_bytes / 2ull) / chain_bytes) % p.a.chains;
+        }
         p.a.partials = s.partials;
         p.a.combine_slots = two_launches ? nullptr : s.slots;
         p.a.out = out + r0;

@@ -375,8 +375,8 @@ __global__ void __launch_bounds__(256) rows_tiled_kernel(const RowsArgs a)
     typedef std::integral_constant<bool, true> tail_too;
     typedef std::integral_constant<bool, false> no_tail;
     typedef std::integral_constant<int, -1> last_by_count;
-    typedef std::integral_constant<int, 0> not_last;
-    typedef std::integral_constant<int, 1> last;
+    typedef std::integral_constant<int, 0> not_last [[maybe_unused]];
+    typedef std::integral_constant<int, 1> last [[maybe_unused]];
 
     if constexpr (STEPS != 0) {
         // The steps of PER iterations written out (a.batches == STEPS): step j of the body belongs to iteration

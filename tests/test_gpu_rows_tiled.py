@@ -150,11 +150,14 @@ def test_many_long_rows_through_the_per_row_kernels_bit_exact(dtype, rows, cols,
 
 
 @pytest.mark.parametrize("dtype", [F16, F32])
-@pytest.mark.parametrize("rows,cols,shift", [(8, (1 << 20) + 5, 0), (9, 300001, 3), (6, 70000, 1), (1000, 40008, 0)])
+@pytest.mark.parametrize("rows,cols,shift", [(8, (1 << 20) + 5, 0), (9, 300001, 3), (6, 70000, 1), (300, 150001, 0),
+                                             (40, 1 << 19, 0), (700, 65544, 0),
+                                             # a few rows more than half the SIMDs: two one-wave blocks per row
+                                             (520, 66001, 0), (620, 40000, 2)])
 def test_few_long_rows_count_every_position_once(dtype, rows, cols, shift):
-    """Few long rows with library defaults start at different chains of their row and wrap round: distinct powers
-    of two at the ends of the row, around every sixteenth of it and at random places (zero elsewhere) must add
-    up to 2^K - 1 in every row, whichever chain the row started at."""
+    """Few long rows with library defaults start at different chains of their row (a step per row that depends on
+    the pitch) and wrap round: distinct powers of two at the ends of the row, around every sixteenth of it and at
+    random places (zero elsewhere) must add up to 2^K - 1 in every row, whichever chain the row started at."""
     K = 16 if dtype == F16 else 24
     rng = np.random.default_rng(cols + rows)
     marks = [0, 1, 7, 8, cols - 1, cols - 2, cols - 9]
