@@ -387,6 +387,7 @@ def rows(args, torch, np, B, W):
         emit(f, "%s %d %d %d %d %s %s %.2f %.1f %.1f %.1f" % (names[dtype], r, c, stride, shift_elems, label, shape, dt * 1e6,
                                                        r * c / dt / 1e9, gb, 100 * gb / HBM_PEAK_GBPS))
 
+    heat(timer, bufs, total_bytes // 2, 0.5)         # fresh buffers start slow
     with open_out(args, "rows.txt") as f:
         emit(f, "# rows x cols filling 512 MiB per call, 4 rotating buffers; 'default' = library choice (t == NULL), 'explicit' = the")
         emit(f, "# same call with an explicit all-default tuning, which selects the per-row kernels; shift = elements between a")
