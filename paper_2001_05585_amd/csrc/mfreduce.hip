@@ -269,13 +269,26 @@ long long grid_blocks_for(const Plan &p, const mfr_tuning &t, int cus, size_t ro
     return (long long)g;
 }
 
+// One to two rows per SIMD (binary32: up to 1.6), rows of 64 KiB and more: a one-wave block per row, all resident at
+// once, each with as many tiles in flight as bring the device to about one wave of 6 KiB per SIMD, instead of
+// 256-thread blocks in rounds.  512 MiB of binary16 rows: 1030 rows 75 -> 82 % of 8 TB/s, 1100 rows 79 -> 85 %, 1400
+// rows 78 -> 85 %, 1800 rows 80 -> 86 %, +3.5 points on average over 1024 to 2047 rows; binary32 +3 up to 1600 rows
+// and -0.4 from there on (left as it was); 1500 rows of 80 KB 73 -> 81 %.  Shorter rows (16 and 32 KiB) gain
+// nothing on average.
+bool one_wave_per_row(size_t rows, size_t row_bytes, unsigned esize, int cus)
+{
+    const size_t simds = (size_t)cus * 4u;
+    return rows >= simds && rows < (esize == 4 ? simds + simds * 5u / 8u : simds * 2u) && row_bytes >= 65536u;
+}
+
 // Block size for `rows` rows of row_bytes bytes sharing the persistent grid (one wave per SIMD in
 // all): the CUs hold cus * 256 / block blocks; a row gets floor(that / rows) of them (at least one).
 // Fewest rounds of blocks first, then the fullest round; a smaller block must fill more than a
 // tenth better to win.  With more rows than the CUs hold 64-thread blocks every row is one block
 // anyway and the row's length decides (measured with 512 MiB of rows of 4 KiB to 512 KiB).
-int block_threads_for_rows(size_t rows, size_t row_bytes, int cus)
+int block_threads_for_rows(size_t rows, size_t row_bytes, unsigned esize, int cus)
 {
+    if (one_wave_per_row(rows, row_bytes, esize, cus)) return 64;
     if (rows >= (size_t)cus * 4u) return row_bytes < 12288u ? 64 : (row_bytes < 32768u ? 128 : 256);
     int best_block = 256;
     unsigned long long best_rounds = 0;
@@ -581,7 +594,7 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
     // Row counts that do not divide the CUs well: smaller blocks, more of them per CU, fill the
     // device in one round (300 rows: 86 % with 64-thread blocks against 70 % with 256-thread ones).
     if (tin == nullptr && rows > 1) {
-        t.block_threads = block_threads_for_rows(rows, cols * esize, info.cus);
+        t.block_threads = block_threads_for_rows(rows, cols * esize, esize, info.cus);
         // Row counts that leave SIMDs without a wave (a few hundred rows): the waves there are keep more loads in
         // flight each, so that the device as a whole has about what one wave of 6 KiB per SIMD would have
         // (520 rows of 1 MiB: 57 -> 78 % of 8 TB/s, 600 rows 64 -> 82 %, 700 rows 70 -> 81 %, 260 rows 75 -> 83 %).
@@ -608,6 +621,11 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
             else if (2ull * want > 13ull * waves) {
                 if (esize == 4) { t.chain_R = 8; t.chains_in_flight = 1; }
                 else { t.chain_R = 4; t.chains_in_flight = 2; }
+            }
+            else if (one_wave_per_row(rows, cols * esize, esize, info.cus)) {
+                // more waves than SIMDs: 3 KiB each from 1.66 waves per SIMD on, 4 KiB from 1.2 on (6 KiB below that)
+                if (37ull * waves > 10ull * want) { t.chain_R = 3; t.chains_in_flight = 1; }
+                else if (5ull * waves > want) { t.chain_R = 4; t.chains_in_flight = 1; }
             }
         }
     }

@@ -134,7 +134,9 @@ LONG_ROWS_PER_ROW_CASES = [(2049, 3000, 3001, 0), (513, 4001, 4003, 6), (2049, 4
                            (66000, 2048, 2049, 0), (1100, 8192, 8192, 0), (1100, 9001, 9001, 0),
                            # enough rows of 16 KiB and more that the launch limits the blocks resident per CU
                            # (whole rounds of six 128-thread or three 256-thread blocks per CU)
-                           (3072, 8192, 8192, 0), (1536, 20000, 20000, 0), (3100, 8192, 8192, 0)]
+                           (3072, 8192, 8192, 0), (1536, 20000, 20000, 0), (3100, 8192, 8192, 0),
+                           # one to two rows per SIMD, rows of 64 KiB and more: a one-wave block per row with 6, 4 or 3 KiB in flight
+                           (1100, 40000, 40000, 0), (1300, 33000, 33001, 0), (1800, 33000, 33001, 1)]
 
 
 @pytest.mark.parametrize("dtype", [F16, BF16])
@@ -153,7 +155,9 @@ def test_many_long_rows_through_the_per_row_kernels_bit_exact(dtype, rows, cols,
 @pytest.mark.parametrize("rows,cols,shift", [(8, (1 << 20) + 5, 0), (9, 300001, 3), (6, 70000, 1), (300, 150001, 0),
                                              (40, 1 << 19, 0), (700, 65544, 0),
                                              # a few rows more than half the SIMDs: two one-wave blocks per row
-                                             (520, 66001, 0), (620, 40000, 2)])
+                                             (520, 66001, 0), (620, 40000, 2),
+                                             # one to two rows per SIMD: a one-wave block per row
+                                             (1400, 40000, 0)])
 def test_few_long_rows_count_every_position_once(dtype, rows, cols, shift):
     """Few long rows with library defaults start at different chains of their row (a step per row that depends on
     the pitch) and wrap round: distinct powers of two at the ends of the row, around every sixteenth of it and at
