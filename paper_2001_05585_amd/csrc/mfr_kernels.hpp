@@ -77,8 +77,8 @@ struct SumArgs {
     unsigned int *combine_slots; // single-launch combine: gridDim.x words per row, all zero between calls;
                                  // nullptr = two-launch combine
     float *out;                  // one per row
-    unsigned long long rotate_step;   // 0, or: row r reads its chains starting from chain (r * rotate_step) mod chains
-                                      // and wrapping round
+    unsigned long long rotate_bytes;  // 0, or: row r reads its chains starting r * rotate_bytes further on (rounded to
+                                      // whole chains, modulo the row's chains) and wrapping round
     unsigned long long *stamps;  // diagnostic: four wall-clock readings per block (see mfr_sum_f16_stamped); normally nullptr
 };
 
@@ -622,8 +622,10 @@ __global__ void __launch_bounds__(1024) sum_kernel(const SumArgs launch_args)
 
     // staggered rows of a batched call: this row's first chain (uniform over the block)
     unsigned long long rot = 0ull;
-    if (launch_args.rotate_step != 0ull)
-        rot = (row * launch_args.rotate_step) % a.chains;
+    if (launch_args.rotate_bytes != 0ull) {
+        constexpr unsigned long long chain_bytes = (HALF ? 512ull : 1024ull) * (unsigned)R;
+        rot = ((row * launch_args.rotate_bytes + chain_bytes / 2ull) / chain_bytes) % a.chains;
+    }
 
     // Level 1: the wave's running sum over the fp32 results of its chains.  MFMA path: uniform over
     // the wave.  Conventional path: one running sum per lane, added up across the wave at the end.

@@ -613,6 +613,8 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
                 cols * esize >= 65536u) {
                 per_row = 2;
                 t.grid_blocks = 2;
+                t.chain_R = 6;              // as one chain: +0.5 points on average against two chains of three tiles, and
+                t.chains_in_flight = 1;     // the unluckiest row lengths reach 68-77 % instead of 62-75 %
             }
             const unsigned long long waves = rows * per_row * ((unsigned)t.block_threads / 64u);
             const unsigned long long want = 6ull * 4ull * (unsigned)info.cus;      // tiles in flight on the device
@@ -685,20 +687,19 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
             p.a.split_waves = w1;
             p.a.split_chains = c1;
         }
-        // Library defaults, several rows: row r starts r * rotate_step chains further on (and wraps round), with the
-        // step chosen so that the addresses the rows are read at, at any one time, lie a multiple of 1 MiB apart
-        // whatever the row pitch is (to within a chain).  The memory channels take such a pattern evenly; with the
-        // rows all read at the same distance from their starts, some pitches put them onto the same channels
-        // (145 rows of 3 702 544 bytes: 63 -> 83 % of 8 TB/s, 143 rows of 3 754 336 bytes 60 -> 83 %, 339 rows
-        // 74 -> 83 %; mean over 95 random shapes of 2 to 1023 rows 82.6 -> 83.9 %).  Granularities of 512 KiB to 4 MiB
-        // do the same, 64 KiB less (83.3 %); four evenly spaced starting points gave 83.0 %, a pseudo-random start
-        // per row costs rows whose pitch was fine up to 14 points.  More rows than four per CU run in rounds and
-        // gain nothing.
-        p.a.rotate_step = 0ull;
+        // Library defaults, several rows: row r starts r * rotate_bytes further on, rounded to whole chains (and
+        // wraps round), with rotate_bytes what the row pitch lacks to the next multiple of 1 MiB: the addresses the
+        // rows are read at, at any one time, then lie a multiple of 1 MiB apart whatever the row pitch is (to within
+        // a chain).  The memory channels take such a pattern evenly; with the rows all read at the same distance
+        // from their starts, some pitches put them onto the same channels (145 rows of 3 702 544 bytes: 63 -> 83 % of
+        // 8 TB/s, 143 rows of 3 754 336 bytes 60 -> 83 %, 339 rows 74 -> 83 %; mean over 95 random shapes of 2 to 1023
+        // rows 82.6 -> 83.9 %).  Granularities of 512 KiB to 4 MiB do the same, 64 KiB less (83.3 %); four evenly spaced
+        // starting points gave 83.0 %, a pseudo-random start per row costs rows whose pitch was fine up to 14 points.
+        // More rows than four per CU gain nothing on average.
+        p.a.rotate_bytes = 0ull;
         if (tin == nullptr && rows > 1 && rows < (size_t)info.cus * 4u && p.a.chains > 16ull) {
-            const unsigned long long pitch = p.a.row_bytes, chain_bytes = 1024ull * (unsigned)t.chain_R;
-            const unsigned long long apart = (pitch + kRowsApartBytes - 1ull) / kRowsApartBytes * kRowsApartBytes;
-            p.a.rotate_step = ((apart - pitch + chain_bytes / 2ull) / chain_bytes) % p.a.chains;
+            const unsigned long long pitch = p.a.row_bytes;
+            p.a.rotate_bytes = (pitch + kRowsApartBytes - 1ull) / kRowsApartBytes * kRowsApartBytes - pitch;
         }
         p.a.partials = s.partials;
         p.a.combine_slots = two_launches ? nullptr : s.slots;
