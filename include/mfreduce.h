@@ -217,10 +217,11 @@ int mfr_sum_ex(const void *x, int dtype, size_t n, float *out, const mfr_tuning 
  * (mfr_rows_plan shows the shape); few rows, rows of 16 KiB or more, and rows
  * of a 16-bit type of 4 KiB or more that start 2 bytes off a 4-byte boundary
  * get a grid of blocks (or one block) each; of fewer rows than four per
- * compute unit, row r then starts r * s bytes further on (rounded to whole
- * chains) and wraps round, s being what the row pitch lacks to a multiple of
- * 1 MiB, so that the rows are read, at any one time, at addresses a multiple
- * of 1 MiB apart, which the memory channels take evenly
+ * compute unit (eight, for rows of 64 KiB and more), row r then starts r * s
+ * bytes further on (rounded to whole chains) and wraps round, s being what
+ * the row pitch lacks to a multiple of 1 MiB, so that the rows are read, at
+ * any one time, at addresses a multiple of 1 MiB apart, which the memory
+ * channels take evenly
  * (which chains a wave adds, hence the rounding of out[r], then depends on r
  * and on the pitch; the same call still gives the same bits).
  * That first kernel loads 16-byte slots counted from each row's first element
