@@ -408,11 +408,16 @@ def rows(args, torch, np, B, W):
             r = total // stride
             measure(f, f16, r, c, stride, 0, None, "default")
         # row counts that are no power of two: a few hundred rows leave SIMDs without a wave
-        for r in (100, 300, 400, 520, 600, 700, 800, 900, 1500, 3000):
+        for r in (100, 300, 400, 450, 520, 600, 700, 800, 900, 1030, 1100, 1400, 1500, 1800, 3000):
             c = total // r // 8 * 8
             measure(f, f16, r, c, c, 0, None, "default")
-        for r in (520, 700):
+        for r in (300, 520, 600, 700, 1100, 1400):
             c = total // 2 // r // 8 * 8
+            measure(f, B.MFR_DTYPE_F32, r, c, c, 0, None, "default")
+        # row pitches that put unstaggered rows onto the same memory channels, and 1500 rows of 80 KB
+        for r, c in ((145, 1851272), (143, 1877168), (339, 791840), (1024, 260144), (1500, 40000)):
+            measure(f, f16, r, c, c, 0, None, "default")
+        for r, c in ((113, 1187764), (1024, 130072)):
             measure(f, B.MFR_DTYPE_F32, r, c, c, 0, None, "default")
         for dtype in (B.MFR_DTYPE_BF16, B.MFR_DTYPE_F32):
             esize = 4 if dtype == B.MFR_DTYPE_F32 else 2
