@@ -491,6 +491,7 @@ def timeline(args, torch, np, B, W):
         emit(f, "# counted from the start of the first block: spread of the block starts, first / last block done with its chains,")
         emit(f, "# last partial handed over, result stored; ideal = 2 n bytes at 8 TB/s")
         emit(f, "# n blocks period start_spread first_streamed last_streamed last_handed_over stored ideal_8TB/s")
+        notes = []
         for k in (16, 18, 20, 22, 23, 24, 25, 26, 27, 28, 29, 30):
             n = 1 << k
             ptrs = arena_pointers(arena.data_ptr(), 2 * nmax, n)
@@ -500,6 +501,7 @@ def timeline(args, torch, np, B, W):
             stamps = torch.zeros(4 * grid, dtype=torch.int64, device="cuda")
             acc = np.zeros(5)
             reps = 20
+            done = np.zeros(grid)
             for r in range(reps):
                 stamps.zero_()
                 B.mfr_sum_f16_stamped(ptrs[(r + 7) % len(ptrs)], n, timer.out.data_ptr(), None, stamps.data_ptr(), 4 * grid, timer.stream)
@@ -508,8 +510,17 @@ def timeline(args, torch, np, B, W):
                 t0 = st[:, 0].min()
                 stored = st[:, 3].max()
                 acc += np.array([st[:, 0].max() - t0, st[:, 1].min() - t0, st[:, 1].max() - t0, st[:, 2].max() - t0, stored - t0]) * tick_us
+                done += (st[:, 1] - t0) * tick_us
             acc /= reps
+            done /= reps
+            if k in (26, 28):
+                by_xcd = [done[np.arange(grid) % 8 == j].mean() for j in range(8)]
+                notes.append("# n = 2^%d: mean time at which a block is done with its chains %.2f; by block index mod 8 (blocks are dealt to the "
+                             "eight XCDs in turn): %s; slowest and fastest block on average %.2f / %.2f"
+                             % (k, done.mean(), " ".join("%.2f" % v for v in by_xcd), done.max(), done.min()))
             emit(f, "%d %d %.2f %.2f %.2f %.2f %.2f %.2f %.2f" % (n, grid, period * 1e6, acc[0], acc[1], acc[2], acc[3], acc[4], 2 * n / 8e6))
+        for line in notes:
+            emit(f, line)
 
 
 def run(args):
