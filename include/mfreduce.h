@@ -349,6 +349,25 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
                   unsigned long long plan[12]);
 
 /*
+ * Geometry of the per-row kernels for mfr_sum_rows_ex(x, dtype, rows, cols,
+ * row_stride, out, t, stream) on a device with `cus` compute units (pure host
+ * arithmetic, no device access): every row is reduced as a single array is
+ * (Section 5.2), plan[1] blocks sharing a row.  Returns 1 and fills plan[], 0
+ * if t == NULL and the many-rows kernel takes the call (see mfr_rows_plan),
+ * negative status on invalid arguments (rows == 0 and cols == 0 included).
+ *   plan[0]  threads per block          plan[1]  blocks per row
+ *   plan[2]  chain_R                    plan[3]  chains in flight per wave
+ *   plan[4]  full chains per row (of a row that starts on a 16-byte boundary when plan[7] is 1)
+ *   plan[5]  stagger: row r reads its chains starting r * plan[5] bytes further on, rounded to whole chains
+ *            and taken modulo the row's chains, and wraps round (0: every row from its first chain)
+ *   plan[6]  bytes of LDS that the launch asks for without using them, which limits the blocks resident
+ *            per compute unit (0: no limit)
+ *   plan[7]  1 if the rows differ in 16-byte phase and each block works out the slots of its own row
+ */
+int mfr_rows_geometry(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row_stride, const mfr_tuning *t,
+                      int cus, unsigned long long plan[8]);
+
+/*
  * Frees the scratch that calls on `stream` of the current device have left
  * with the library (block partials, combine slots, the recurrence variant's
  * level buffers), after synchronising the stream.  For streams that are about

@@ -22,7 +22,7 @@ MFR_DTYPE_F16, MFR_DTYPE_BF16, MFR_DTYPE_F32 = 0, 1, 2
 
 EXPORTS = ("mfr_sum_f16", "mfr_sum_f16_tuned", "mfr_sum_f16_ex", "mfr_sum_f16_noalloc", "mfr_sum_f16_stamped", "mfr_wall_clock_khz", "mfr_sum_bf16", "mfr_sum_f32", "mfr_sum_ex",
            "mfr_sum_rows_ex", "mfr_sum_f16_rows", "mfr_sum_f16_recurrence", "mfr_sum_f16_f64", "mfr_sum_f16_f64_ex", "mfr_get_default_tuning", "mfr_grid_for", "mfr_plan_for",
-           "mfr_plan_ex", "mfr_rows_plan", "mfr_release_scratch", "mfr_strerror", "mfr_last_hip_error", "mfr_version")
+           "mfr_plan_ex", "mfr_rows_plan", "mfr_rows_geometry", "mfr_release_scratch", "mfr_strerror", "mfr_last_hip_error", "mfr_version")
 
 
 class mfr_tuning(ctypes.Structure):
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
     L.mfr_plan_ex.restype = ci
     L.mfr_rows_plan.argtypes = [sz, ci, sz, sz, sz, ci, ctypes.POINTER(ctypes.c_ulonglong)]
     L.mfr_rows_plan.restype = ci
+    L.mfr_rows_geometry.argtypes = [sz, ci, sz, sz, sz, ctypes.POINTER(mfr_tuning), ci, ctypes.POINTER(ctypes.c_ulonglong)]
+    L.mfr_rows_geometry.restype = ci
     ip = ctypes.POINTER(ci)
     L.mfr_get_default_tuning.argtypes = [ip, ip, ip]
     L.mfr_get_default_tuning.restype = ci
@@ -197,6 +199,17 @@ def mfr_rows_plan(x_addr: int, dtype: int, rows: int, cols: int, row_stride: int
     st = int(lib().mfr_rows_plan(x_addr, dtype, rows, cols, row_stride, cus, plan))
     if st < 0:
         _check(-st, "mfr_rows_plan")
+    return tuple(int(v) for v in plan) if st == 1 else None
+
+
+def mfr_rows_geometry(x_addr: int, dtype: int, rows: int, cols: int, row_stride: int, t: mfr_tuning | None = None,
+                      cus: int = 256):
+    """None if the many-rows kernel is chosen, else the 8 geometry values of the per-row kernels."""
+    plan = (ctypes.c_ulonglong * 8)()
+    tp = ctypes.byref(t) if t is not None else None
+    st = int(lib().mfr_rows_geometry(x_addr, dtype, rows, cols, row_stride, tp, cus, plan))
+    if st < 0:
+        _check(-st, "mfr_rows_geometry")
     return tuple(int(v) for v in plan) if st == 1 else None
 
 

@@ -544,6 +544,94 @@ int fill_zero(float *out, size_t count, hipStream_t stream)
     return MFR_OK;
 }
 
+// Geometry of the per-row kernels for a batched call (pure host arithmetic): block size, blocks per row, chain
+// shape, LDS that limits residency, stagger.  `t` comes in resolved and goes out as launched; `defaults` says that
+// the caller left the tuning to the library.
+int per_row_geometry(size_t x_addr, unsigned esize, size_t rows, size_t cols, size_t row_stride, bool defaults, int cus,
+                     mfr_tuning *t_io, Plan *p_out, long long *grid_out)
+{
+    mfr_tuning &t = *t_io;
+    Plan &p = *p_out;
+    // rows that all have the same 16-byte phase can be read in aligned slots
+    const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
+    // Row counts that do not divide the CUs well: smaller blocks, more of them per CU, fill the
+    // device in one round (300 rows: 86 % with 64-thread blocks against 70 % with 256-thread ones).
+    if (defaults && rows > 1) {
+        t.block_threads = block_threads_for_rows(rows, cols * esize, esize, cus);
+        // Row counts that leave SIMDs without a wave (a few hundred rows): the waves there are keep more loads in
+        // flight each, so that the device as a whole has about what one wave of 6 KiB per SIMD would have
+        // (520 rows of 1 MiB: 57 -> 78 % of 8 TB/s, 600 rows 64 -> 82 %, 700 rows 70 -> 81 %, 260 rows 75 -> 83 %).
+        // 8 KiB per wave already when 6 KiB would leave the device under 92 % of that (300 rows of 1.7 MiB 80 -> 86 %,
+        // 450 rows 81 -> 85 %, 900 rows 81 -> 84 %; 1000 rows, at 98 %, are better off with 6 KiB: 84 against 81.5 %),
+        // as one chain for binary32 (2 points better on average) and as two for the 16-bit types.
+        // A few rows more than half the SIMDs: two one-wave blocks per row with 6 KiB each instead of one with 12 KiB.
+        // binary32, 513 to 640 rows: 516 to 540 rows of 1 MiB 70 -> 82 %, 600 rows 77.5 -> 82.5 %, 640 rows 80 -> 83 %
+        // (two of 28 row lengths measured lose 6 to 9 points).  16-bit types, 513 to 544 rows: 520 rows of 1 MiB
+        // 76 -> 80 %, +1.2 points on average; from there on no gain on average and single lengths 14 points lower.
+        if (!default_geometry().overridden && t.kernel == MFR_KERNEL_MFMA) {
+            const unsigned long long slots = (unsigned long long)cus * (256u / (unsigned)t.block_threads);
+            unsigned long long per_row = slots / rows;
+            if (per_row < 1) per_row = 1;
+            if (per_row == 1 && t.block_threads == 64 && 2ull * rows <= slots + slots / (esize == 4 ? 4ull : 16ull) &&
+                cols * esize >= 65536u) {
+                per_row = 2;
+                t.grid_blocks = 2;
+                t.chain_R = 6;              // as one chain: +0.5 points on average against two chains of three tiles, and
+                t.chains_in_flight = 1;     // the unluckiest row lengths reach 68-77 % instead of 62-75 %
+            }
+            const unsigned long long waves = rows * per_row * ((unsigned)t.block_threads / 64u);
+            const unsigned long long want = 6ull * 4ull * (unsigned)cus;      // tiles in flight on the device
+            if (want > 12ull * waves) { t.chain_R = 8; t.chains_in_flight = 2; }
+            else if (want > 8ull * waves) { t.chain_R = 6; t.chains_in_flight = 2; }
+            else if (2ull * want > 13ull * waves) {
+                if (esize == 4) { t.chain_R = 8; t.chains_in_flight = 1; }
+                else { t.chain_R = 4; t.chains_in_flight = 2; }
+            }
+            else if (one_wave_per_row(rows, cols * esize, esize, cus)) {
+                // more waves than SIMDs: 3 KiB each from 1.66 waves per SIMD on, 4 KiB from 1.2 on (6 KiB below that)
+                if (37ull * waves > 10ull * want) { t.chain_R = 3; t.chains_in_flight = 1; }
+                else if (5ull * waves > want) { t.chain_R = 4; t.chains_in_flight = 1; }
+            }
+        }
+    }
+    const size_t batch = rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch;
+
+    // Rows are addressed in aligned slots counted from the boundary at or below their first element
+    // (the head slot is read element-wise).  Rows that share their 16-byte phase share the slot
+    // arithmetic done here; rows of differing phase are planned as if they started on a boundary
+    // (which gives the largest number of chains), and each block redoes the arithmetic for its row.
+    plan_region(cols, same_phase ? x_addr : 0, esize, t, &p);
+    // A short single array is summed by one block with a wave per chain (up to 16 waves, two chains
+    // each): combining several blocks costs three dependent device-scope round trips, 1.6 us, which a
+    // call replayed from a graph would see in full (1.9 us against 3.4 us per call).
+    if (defaults && rows == 1 && cols * esize <= kMidSizeMinBytes && one_block_default(p.chains, &t))
+        plan_region(cols, x_addr, esize, t, &p);
+    p.a.per_row_phase = same_phase ? 0u : 1u;
+    const long long grid = grid_blocks_for(p, t, cus, batch);
+    if (grid < 1) return MFR_ERR_INVALID_ARG;
+    *grid_out = grid;
+    p.dynamic_lds = resident_limit_lds(defaults ? rows : 0, (unsigned long long)grid, cols * esize, esize,
+                                       same_phase && (x_addr & 15u) == 0 && ((cols * esize) & 15u) == 0, p.waves, cus);
+    // Library defaults, several rows: row r starts r * rotate_bytes further on, rounded to whole chains (and
+    // wraps round), with rotate_bytes what the row pitch lacks to the next multiple of 1 MiB: the addresses the
+    // rows are read at, at any one time, then lie a multiple of 1 MiB apart whatever the row pitch is (to within
+    // a chain).  The memory channels take such a pattern evenly; with the rows all read at the same distance
+    // from their starts, some pitches put them onto the same channels (145 rows of 3 702 544 bytes: 63 -> 83 % of
+    // 8 TB/s, 143 rows of 3 754 336 bytes 60 -> 83 %, 339 rows 74 -> 83 %; mean over 95 random shapes of 2 to 1023
+    // rows 82.6 -> 83.9 %).  Granularities of 512 KiB to 4 MiB do the same, 64 KiB less (83.3 %); four evenly spaced
+    // starting points gave 83.0 %, a pseudo-random start per row costs rows whose pitch was fine up to 14 points.
+    // One to two rows per SIMD with a one-wave block each: same mean with and without (84 shapes), but the
+    // unluckiest are lifted (1024 rows of 520 288 bytes 65 -> 82 %, of 130 072 floats 65 -> 86 %; 24 -> 19 shapes
+    // under 78 %).  More rows run in rounds, not side by side, and are left alone.
+    p.a.rotate_bytes = 0ull;
+    if (defaults && rows > 1 && p.a.chains > 16ull &&
+        (rows < (size_t)cus * 4u || one_wave_per_row(rows, cols * esize, esize, cus))) {
+        const unsigned long long pitch = (unsigned long long)row_stride * esize;
+        p.a.rotate_bytes = (pitch + kRowsApartBytes - 1ull) / kRowsApartBytes * kRowsApartBytes - pitch;
+    }
+    return MFR_OK;
+}
+
 // rows sums of cols elements each; consecutive rows are row_stride elements apart.
 // `fixed`: if not null, the block partials and slots live there and nothing is allocated; a call
 // that needs more than it holds fails with MFR_ERR_SCRATCH_LIMIT.
@@ -573,9 +661,6 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
 
     if (cols == 0) return fill_zero(out, rows, stream);
 
-    // rows that all have the same 16-byte phase can be read in aligned slots
-    const bool same_phase = rows == 1 || ((row_stride * esize) & 15u) == 0;
-
     // Many rows: tiles shared out among rows, one launch for any alignment and stride.
     if (tin == nullptr) {
         mfr::RowsTiledShape shape;
@@ -591,64 +676,12 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
         }
     }
 
-    // Row counts that do not divide the CUs well: smaller blocks, more of them per CU, fill the
-    // device in one round (300 rows: 86 % with 64-thread blocks against 70 % with 256-thread ones).
-    if (tin == nullptr && rows > 1) {
-        t.block_threads = block_threads_for_rows(rows, cols * esize, esize, info.cus);
-        // Row counts that leave SIMDs without a wave (a few hundred rows): the waves there are keep more loads in
-        // flight each, so that the device as a whole has about what one wave of 6 KiB per SIMD would have
-        // (520 rows of 1 MiB: 57 -> 78 % of 8 TB/s, 600 rows 64 -> 82 %, 700 rows 70 -> 81 %, 260 rows 75 -> 83 %).
-        // 8 KiB per wave already when 6 KiB would leave the device under 92 % of that (300 rows of 1.7 MiB 80 -> 86 %,
-        // 450 rows 81 -> 85 %, 900 rows 81 -> 84 %; 1000 rows, at 98 %, are better off with 6 KiB: 84 against 81.5 %),
-        // as one chain for binary32 (2 points better on average) and as two for the 16-bit types.
-        // A few rows more than half the SIMDs: two one-wave blocks per row with 6 KiB each instead of one with 12 KiB.
-        // binary32, 513 to 640 rows: 516 to 540 rows of 1 MiB 70 -> 82 %, 600 rows 77.5 -> 82.5 %, 640 rows 80 -> 83 %
-        // (two of 28 row lengths measured lose 6 to 9 points).  16-bit types, 513 to 544 rows: 520 rows of 1 MiB
-        // 76 -> 80 %, +1.2 points on average; from there on no gain on average and single lengths 14 points lower.
-        if (!default_geometry().overridden && t.kernel == MFR_KERNEL_MFMA) {
-            const unsigned long long slots = (unsigned long long)info.cus * (256u / (unsigned)t.block_threads);
-            unsigned long long per_row = slots / rows;
-            if (per_row < 1) per_row = 1;
-            if (per_row == 1 && t.block_threads == 64 && 2ull * rows <= slots + slots / (esize == 4 ? 4ull : 16ull) &&
-                cols * esize >= 65536u) {
-                per_row = 2;
-                t.grid_blocks = 2;
-                t.chain_R = 6;              // as one chain: +0.5 points on average against two chains of three tiles, and
-                t.chains_in_flight = 1;     // the unluckiest row lengths reach 68-77 % instead of 62-75 %
-            }
-            const unsigned long long waves = rows * per_row * ((unsigned)t.block_threads / 64u);
-            const unsigned long long want = 6ull * 4ull * (unsigned)info.cus;      // tiles in flight on the device
-            if (want > 12ull * waves) { t.chain_R = 8; t.chains_in_flight = 2; }
-            else if (want > 8ull * waves) { t.chain_R = 6; t.chains_in_flight = 2; }
-            else if (2ull * want > 13ull * waves) {
-                if (esize == 4) { t.chain_R = 8; t.chains_in_flight = 1; }
-                else { t.chain_R = 4; t.chains_in_flight = 2; }
-            }
-            else if (one_wave_per_row(rows, cols * esize, esize, info.cus)) {
-                // more waves than SIMDs: 3 KiB each from 1.66 waves per SIMD on, 4 KiB from 1.2 on (6 KiB below that)
-                if (37ull * waves > 10ull * want) { t.chain_R = 3; t.chains_in_flight = 1; }
-                else if (5ull * waves > want) { t.chain_R = 4; t.chains_in_flight = 1; }
-            }
-        }
-    }
-    const size_t batch = rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch;
-
-    // Rows are addressed in aligned slots counted from the boundary at or below their first element
-    // (the head slot is read element-wise).  Rows that share their 16-byte phase share the slot
-    // arithmetic done here; rows of differing phase are planned as if they started on a boundary
-    // (which gives the largest number of chains), and each block redoes the arithmetic for its row.
+    // Block size, blocks per row, chain shape, stagger of the per-row kernels for this call.
     Plan p;
-    plan_region(cols, same_phase ? (size_t)x : 0, esize, t, &p);
-    // A short single array is summed by one block with a wave per chain (up to 16 waves, two chains
-    // each): combining several blocks costs three dependent device-scope round trips, 1.6 us, which a
-    // call replayed from a graph would see in full (1.9 us against 3.4 us per call).
-    if (tin == nullptr && rows == 1 && cols * esize <= kMidSizeMinBytes && one_block_default(p.chains, &t))
-        plan_region(cols, (size_t)x, esize, t, &p);
-    p.a.per_row_phase = same_phase ? 0u : 1u;
-    const long long grid = grid_blocks_for(p, t, info.cus, batch);
-    if (grid < 1) return MFR_ERR_INVALID_ARG;
-    p.dynamic_lds = resident_limit_lds(tin == nullptr ? rows : 0, (unsigned long long)grid, cols * esize, esize,
-                                       same_phase && ((size_t)x & 15u) == 0 && ((cols * esize) & 15u) == 0, p.waves, info.cus);
+    long long grid = 0;
+    const int gs = per_row_geometry((size_t)x, esize, rows, cols, row_stride, tin == nullptr, info.cus, &t, &p, &grid);
+    if (gs != MFR_OK) return gs;
+    const size_t batch = rows < kMaxRowsPerLaunch ? rows : kMaxRowsPerLaunch;
     const bool two_launches = t.combine == MFR_COMBINE_TWO_LAUNCHES || grid > kSingleLaunchHardMax ||
                               (t.combine == MFR_COMBINE_AUTO && grid > kSingleLaunchAutoMax);
     if (stamps && stamps_len < 4u * (size_t)grid) return MFR_ERR_INVALID_ARG;
@@ -686,23 +719,6 @@ int sum_rows_impl(const void *x, int dtype, size_t rows, size_t cols, size_t row
             if (c1 == p.a.chains) w1 = W;
             p.a.split_waves = w1;
             p.a.split_chains = c1;
-        }
-        // Library defaults, several rows: row r starts r * rotate_bytes further on, rounded to whole chains (and
-        // wraps round), with rotate_bytes what the row pitch lacks to the next multiple of 1 MiB: the addresses the
-        // rows are read at, at any one time, then lie a multiple of 1 MiB apart whatever the row pitch is (to within
-        // a chain).  The memory channels take such a pattern evenly; with the rows all read at the same distance
-        // from their starts, some pitches put them onto the same channels (145 rows of 3 702 544 bytes: 63 -> 83 % of
-        // 8 TB/s, 143 rows of 3 754 336 bytes 60 -> 83 %, 339 rows 74 -> 83 %; mean over 95 random shapes of 2 to 1023
-        // rows 82.6 -> 83.9 %).  Granularities of 512 KiB to 4 MiB do the same, 64 KiB less (83.3 %); four evenly spaced
-        // starting points gave 83.0 %, a pseudo-random start per row costs rows whose pitch was fine up to 14 points.
-        // One to two rows per SIMD with a one-wave block each: same mean with and without (84 shapes), but the
-        // unluckiest are lifted (1024 rows of 520 288 bytes 65 -> 82 %, of 130 072 floats 65 -> 86 %; 24 -> 19 shapes
-        // under 78 %).  More rows run in rounds, not side by side, and are left alone.
-        p.a.rotate_bytes = 0ull;
-        if (tin == nullptr && rows > 1 && p.a.chains > 16ull &&
-            (rows < (size_t)info.cus * 4u || one_wave_per_row(rows, cols * esize, esize, info.cus))) {
-            const unsigned long long pitch = p.a.row_bytes;
-            p.a.rotate_bytes = (pitch + kRowsApartBytes - 1ull) / kRowsApartBytes * kRowsApartBytes - pitch;
         }
         p.a.partials = s.partials;
         p.a.combine_slots = two_launches ? nullptr : s.slots;
@@ -1046,6 +1062,38 @@ int mfr_rows_plan(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row
     return 1;
 }
 
+int mfr_rows_geometry(size_t x_addr, int dtype, size_t rows, size_t cols, size_t row_stride, const mfr_tuning *tin,
+                      int cus, unsigned long long plan[8])
+{
+    if (!valid_dtype(dtype) || !plan || cus < 1) return -MFR_ERR_INVALID_ARG;
+    const unsigned esize = elem_size(dtype);
+    if ((x_addr & (esize - 1u)) || cols == 0 || rows == 0 || cols > ((size_t)1 << 60) || rows > ((size_t)1 << 40))
+        return -MFR_ERR_INVALID_ARG;
+    if (rows > 1 && row_stride < cols) return -MFR_ERR_INVALID_ARG;
+    if (!span_fits(rows, cols, row_stride)) return -MFR_ERR_INVALID_ARG;
+    mfr_tuning t;
+    const int st = resolve_tuning(tin, dtype, &t, rows == 1 ? (unsigned long long)cols * esize : 0ull);
+    if (st != MFR_OK) return -st;
+    if (tin == nullptr) {
+        mfr::RowsTiledShape shape;
+        unsigned tiled_grid = 0;
+        if (plan_rows_tiled(x_addr, esize, rows, cols, row_stride, cus, &shape, &tiled_grid)) return 0;
+    }
+    Plan p;
+    long long grid = 0;
+    const int gs = per_row_geometry(x_addr, esize, rows, cols, row_stride, tin == nullptr, cus, &t, &p, &grid);
+    if (gs != MFR_OK) return -gs;
+    plan[0] = (unsigned long long)t.block_threads;
+    plan[1] = (unsigned long long)grid;
+    plan[2] = (unsigned long long)t.chain_R;
+    plan[3] = (unsigned long long)t.chains_in_flight;
+    plan[4] = p.a.chains;
+    plan[5] = p.a.rotate_bytes;
+    plan[6] = p.dynamic_lds;
+    plan[7] = p.a.per_row_phase;
+    return 1;
+}
+
 int mfr_release_scratch(hipStream_t stream)
 {
     int dev = 0;
@@ -1084,6 +1132,6 @@ const char *mfr_strerror(int status)
 
 const char *mfr_last_hip_error(void) { return g_hip_error; }
 
-int mfr_version(void) { return 600; }
+int mfr_version(void) { return 610; }
 
 }  // extern "C"
