@@ -382,8 +382,13 @@ def rows(args, torch, np, B, W):
         torch.cuda.synchronize()
         dt = e0.elapsed_time(e1) * 1e-3 / args.steps
         gb = (esize * r * c + 4 * r) / dt / 1e9
-        plan = B.mfr_rows_plan(bufs[0].data_ptr() + off, dtype, r, c, stride, torch.cuda.get_device_properties(0).multi_processor_count)
-        shape = "per-row" if (t is not None or plan is None) else rows_shape_label(plan)
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        plan = B.mfr_rows_plan(bufs[0].data_ptr() + off, dtype, r, c, stride, cus)
+        if t is not None or plan is None:
+            g = B.mfr_rows_geometry(bufs[0].data_ptr() + off, dtype, r, c, stride, t, cus)
+            shape = "per-row_%dx%d_R%dU%d%s%s" % (g[0], g[1], g[2], g[3], "_staggered" if g[5] else "", "_limited" if g[6] else "")
+        else:
+            shape = rows_shape_label(plan)
         emit(f, "%s %d %d %d %d %s %s %.2f %.1f %.1f %.1f" % (names[dtype], r, c, stride, shift_elems, label, shape, dt * 1e6,
                                                        r * c / dt / 1e9, gb, 100 * gb / HBM_PEAK_GBPS))
 
@@ -392,6 +397,8 @@ def rows(args, torch, np, B, W):
         emit(f, "# rows x cols filling 512 MiB per call, 4 rotating buffers; 'default' = library choice (t == NULL), 'explicit' = the")
         emit(f, "# same call with an explicit all-default tuning, which selects the per-row kernels; shift = elements between a")
         emit(f, "# 16-byte boundary and x; GB/s counts the input and the 4-byte results")
+        emit(f, "# kernel_shape of the per-row kernels: threads per block x blocks per row, chain_R, chains in flight, whether the rows")
+        emit(f, "# start staggered and whether unused LDS limits the blocks resident per compute unit")
         emit(f, "# type rows cols stride shift tuning kernel_shape us Gelem/s GB/s pct_of_8TB/s")
         f16 = B.MFR_DTYPE_F16
         total = total_bytes // 2
@@ -468,7 +475,11 @@ def row_lengths(args, torch, np, B, W):
                 dt = e0.elapsed_time(e1) * 1e-3 / args.steps
                 gb = (esize * r * c + 4 * r) / dt / 1e9
                 plan = B.mfr_rows_plan(bufs[0].data_ptr() + first_byte, dtype, r, c, c, cus)
-                shape = "per-row" if plan is None else rows_shape_label(plan)
+                if plan is None:
+                    g = B.mfr_rows_geometry(bufs[0].data_ptr() + first_byte, dtype, r, c, c, None, cus)
+                    shape = "per-row_%dx%d_R%dU%d%s" % (g[0], g[1], g[2], g[3], "_limited" if g[6] else "")
+                else:
+                    shape = rows_shape_label(plan)
                 emit(f, "%s %d %d %d %s %s %.2f %.1f %.1f" % (name, nbytes, c, r, shape, "-" if plan is None else plan[4], dt * 1e6, gb,
                                                          100 * gb / HBM_PEAK_GBPS))
 
